@@ -1,0 +1,137 @@
+/* spmi: sparse x dense products under per-level dense/compressed storage, for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Plain pointers and sizes only; every pointer is marked HOST or
+ * DEVICE.  No call throws; every call returns an sp_status.  There is no global state
+ * other than what a handle owns.  All GPU work is enqueued on the HIP stream the caller
+ * passes (void* = hipStream_t, NULL = the null stream).
+ *
+ * Vocabulary follows arXiv 2202.04305: a rank-d tensor is stored level by level; level l
+ * holds dimension dimOrdering[l]; a level is "dense" (nothing stored, child position =
+ * parent * size + coordinate) or "compressed" (arrays pointers[l] and indices[l], called
+ * pos and crd here), and one values array holds the stored entries (Section 4.1).
+ */
+#ifndef SPMI_H
+#define SPMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_NULL = 1,         /* a required pointer is NULL                                  */
+    SP_ERR_RANK = 2,         /* rank outside [1, SP_MAX_RANK], or a rank-2 call on another rank */
+    SP_ERR_LEVEL_TYPE = 3,   /* level type not dense/compressed; pos/crd asked of a dense level */
+    SP_ERR_ORDERING = 4,     /* dimOrdering is not a permutation                            */
+    SP_ERR_WIDTH = 5,        /* width not in {0,32,64}, or a stored value does not fit it   */
+    SP_ERR_COORD_RANGE = 6,  /* a coordinate is < 0 or >= its dimension's size              */
+    SP_ERR_DUPLICATE = 7,    /* the same coordinate tuple appears twice                     */
+    SP_ERR_SHAPE = 8,        /* negative size, ld < N, and the like                         */
+    SP_ERR_DTYPE = 9,
+    SP_ERR_UNSUPPORTED = 10, /* valid request with no GPU path yet                          */
+    SP_ERR_TOO_LARGE = 11,   /* position count or linearised key overflows 63 bits, nnz >= 2^31 */
+    SP_ERR_ALLOC = 12,       /* the allocator returned NULL                                 */
+    SP_ERR_HIP = 13          /* a HIP runtime call failed (sp_last_hip_error has the code)  */
+} sp_status;
+
+typedef enum { SP_DENSE = 0, SP_COMPRESSED = 1 } sp_level_type;
+typedef enum { SP_F32 = 0, SP_F64 = 1 } sp_dtype;
+#define SP_MAX_RANK 8
+
+typedef struct sp_encoding sp_encoding;   /* HOST, immutable                                */
+typedef struct sp_tensor sp_tensor;       /* HOST handle that owns DEVICE arrays            */
+
+/* Device-memory allocator the library uses for everything it allocates (storage arrays and
+ * temporaries).  alloc returns a DEVICE pointer aligned to >= 256 bytes or NULL; free_
+ * releases one.  Both are called from the thread that calls into the library.  Pass NULL
+ * for both to use hipMalloc / hipFree. */
+typedef void *(*sp_alloc_fn)(size_t bytes, void *ctx);
+typedef void (*sp_free_fn)(void *ptr, void *ctx);
+
+/* The encoding attribute (Section 4.1: per-dimension level types, dimension ordering, bit
+ * widths).  levelTypes: HOST array of `rank` entries, by level.  dimOrdering: HOST array,
+ * dimOrdering[l] = dimension stored at level l (the result list of the paper's affine map
+ * read left to right); NULL = identity.  posWidth / crdWidth: bits of the pos and crd
+ * arrays; 0 means "native" = 64; this library stores signed integers and supports 32 and
+ * 64.  Checks run in the order rank, level type, ordering, width; *out is written only
+ * on SP_OK and is released with sp_encoding_free. */
+sp_status sp_encode(int rank, const sp_level_type *levelTypes, const int *dimOrdering,
+                    int posWidth, int crdWidth, sp_encoding **out);
+void sp_encoding_free(sp_encoding *enc);
+
+/* Build the storage from coordinate-scheme input (Section 4.2: tensors are materialised and
+ * converted through an intermediate coordinate scheme; Section 4.1 defines the arrays built).
+ *   shape   HOST  `rank` sizes by original dimension.
+ *   nnz     number of entries, in any order, zero-based coordinates, no tuple twice.
+ *   coords  HOST array of `rank` DEVICE pointers; coords[d][e] = coordinate of entry e in
+ *           dimension d (structure of arrays, int64).
+ *   values  DEVICE, nnz elements of `dt`.  Explicit zeros are kept as stored entries.
+ * The inputs are read, never kept.  The tensor owns its arrays; they are obtained from
+ * `alloc` and released through `free_` by sp_tensor_free (the callbacks and ctx must stay
+ * valid until then).  The call synchronises the stream (level sizes and the input checks
+ * come back to the host).  Errors, in this order: NULL, shape, TOO_LARGE, COORD_RANGE,
+ * DUPLICATE, WIDTH; on error nothing is left allocated and *out is NULL. */
+sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64_t nnz,
+                  const int64_t *const *coords, const void *values, sp_dtype dt,
+                  sp_alloc_fn alloc, sp_free_fn free_, void *ctx, void *stream, sp_tensor **out);
+void sp_tensor_free(sp_tensor *t);
+
+/* C[i,j] = sum_k A[i,k] * B[k,j] (Section 1, the SpMM kernel; Section 6.2, matrix times vector
+ * is the case N = 1), A a packed rank-2 tensor of shape m x n.
+ *   B  DEVICE, row-major n x N with leading dimension ldb >= N, A's dtype.
+ *   C  DEVICE, row-major m x N with leading dimension ldc >= N, A's dtype.
+ *   accumulate = 0: C is overwritten (rows of A without stored entries become zero);
+ *   accumulate = 1: C += A.B and rows without stored entries are not touched.
+ * Enqueues on `stream` and returns without synchronising.  B and C must not overlap.
+ * Summation order inside a row is unspecified (floating-point reassociation, Section 5.2). */
+sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
+                    void *C, int64_t ldc, int accumulate, void *stream);
+
+/* The paper's pointers / indices / values operations (Section 4.2): borrowed DEVICE
+ * pointers, valid until sp_tensor_free.  `level` is a storage level, not a dimension.  *len is in
+ * elements of the tensor's pos / crd width (sp_tensor_info) or dtype. */
+sp_status sp_pos(const sp_tensor *t, int level, const void **ptr, int64_t *len);
+sp_status sp_crd(const sp_tensor *t, int level, const void **ptr, int64_t *len);
+sp_status sp_values(const sp_tensor *t, const void **ptr, int64_t *len);
+
+/* Back to the coordinate scheme: every stored position in storage order (padding zeros of a
+ * dense level under a compressed one included), coordinates in the original dimension
+ * order.  coords: HOST array of `rank` DEVICE int64 arrays, each with room for the
+ * values length; values: DEVICE array of the tensor's dtype, same length.  Asynchronous. */
+sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream);
+
+typedef struct {
+    int rank;
+    int levelTypes[SP_MAX_RANK];
+    int dimOrdering[SP_MAX_RANK];
+    int posWidth, crdWidth;          /* resolved: 32 or 64 */
+    int dtype;
+    int64_t shape[SP_MAX_RANK];
+    int64_t nnz;                     /* entries given to sp_pack */
+    int64_t nvalues;                 /* length of the values array */
+    int64_t maxSegment;              /* longest innermost pos segment (rank 2: longest row/column) */
+    int64_t storageBytes;            /* pos + crd + values */
+} sp_info;
+sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
+
+/* Kernel choice for sp_matmul on this tensor, for A/B measurements.  key/value pairs:
+ *   SP_TUNE_SPMV_KERNEL: 0 = automatic, 1 = lanes-per-row, 2 = row-block streaming
+ *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
+ * Unknown keys or values give SP_ERR_UNSUPPORTED. */
+enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3 };
+sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);
+
+/* dst[i] = src[i] for `bytes` bytes (multiple of 16), a plain streaming copy kernel: the
+ * yardstick the benchmark scales its bandwidth figures and hardware counters by. */
+sp_status sp_stream_copy(void *dst /* DEVICE */, const void *src /* DEVICE */, size_t bytes, void *stream);
+
+const char *sp_status_str(sp_status s);
+int sp_last_hip_error(void);          /* hipError_t of the last SP_ERR_HIP on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPMI_H */

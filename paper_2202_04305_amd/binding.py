@@ -1,0 +1,246 @@
+"""ctypes binding of libspmi.so.  Same names as the C ABI; argument marshalling only."""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+SP_DENSE, SP_COMPRESSED = 0, 1
+SP_F32, SP_F64 = 0, 1
+SP_TUNE_SPMV_KERNEL, SP_TUNE_CSC_MODE, SP_TUNE_SPMM_KERNEL = 1, 2, 3
+SP_MAX_RANK = 8
+
+STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_ERR_ORDERING", "SP_ERR_WIDTH",
+                "SP_ERR_COORD_RANGE", "SP_ERR_DUPLICATE", "SP_ERR_SHAPE", "SP_ERR_DTYPE", "SP_ERR_UNSUPPORTED",
+                "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
+
+EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
+           "sp_unpack", "sp_tensor_info", "sp_tensor_tune", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+
+class SpInfo(ctypes.Structure):
+    _fields_ = [("rank", ctypes.c_int), ("levelTypes", ctypes.c_int * SP_MAX_RANK), ("dimOrdering", ctypes.c_int * SP_MAX_RANK),
+                ("posWidth", ctypes.c_int), ("crdWidth", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("shape", ctypes.c_int64 * SP_MAX_RANK), ("nnz", ctypes.c_int64), ("nvalues", ctypes.c_int64),
+                ("maxSegment", ctypes.c_int64), ("storageBytes", ctypes.c_int64)]
+
+
+class SpError(RuntimeError):
+    def __init__(self, code, what=""):
+        name = STATUS_NAMES[code] if 0 <= code < len(STATUS_NAMES) else str(code)
+        extra = ""
+        if code == 13 and _lib is not None:
+            extra = " (hipError %d)" % _lib.sp_last_hip_error()
+        super().__init__("%s%s %s" % (name, extra, what))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libspmi.so; builds it only when no built library exists.  Fails loudly otherwise."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = ctypes.CDLL(_build.LIB)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    L.sp_encode.restype = ci
+    L.sp_encode.argtypes = [ci, vp, vp, ci, ci, ctypes.POINTER(vp)]
+    L.sp_encoding_free.restype = None
+    L.sp_encoding_free.argtypes = [vp]
+    L.sp_pack.restype = ci
+    L.sp_pack.argtypes = [vp, vp, i64, vp, vp, ci, _ALLOC_FN, _FREE_FN, vp, vp, ctypes.POINTER(vp)]
+    L.sp_tensor_free.restype = None
+    L.sp_tensor_free.argtypes = [vp]
+    L.sp_matmul.restype = ci
+    L.sp_matmul.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
+    for f in (L.sp_pos, L.sp_crd):
+        f.restype = ci
+        f.argtypes = [vp, ci, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+    L.sp_values.restype = ci
+    L.sp_values.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+    L.sp_unpack.restype = ci
+    L.sp_unpack.argtypes = [vp, vp, vp, vp]
+    L.sp_tensor_info.restype = ci
+    L.sp_tensor_info.argtypes = [vp, ctypes.POINTER(SpInfo)]
+    L.sp_tensor_tune.restype = ci
+    L.sp_tensor_tune.argtypes = [vp, ci, i64]
+    L.sp_stream_copy.restype = ci
+    L.sp_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.sp_status_str.restype = ctypes.c_char_p
+    L.sp_status_str.argtypes = [ci]
+    L.sp_last_hip_error.restype = ci
+    L.sp_last_hip_error.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(code, what=""):
+    if code != 0:
+        raise SpError(code, what)
+
+
+def _stream_ptr():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class _TorchAllocator:
+    """Backs the library's allocator callbacks with torch's caching allocator (uint8 tensors kept alive by address)."""
+
+    def __init__(self, device):
+        self.device = device
+        self.live = {}
+        self.alloc_cb = _ALLOC_FN(self._alloc)
+        self.free_cb = _FREE_FN(self._free)
+
+    def _alloc(self, nbytes, _ctx):
+        try:
+            t = torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=self.device)
+        except Exception:          # out of memory: the library turns NULL into SP_ERR_ALLOC
+            return None
+        self.live[t.data_ptr()] = t
+        return t.data_ptr()
+
+    def _free(self, ptr, _ctx):
+        self.live.pop(ptr, None)
+
+
+class Encoding:
+    def __init__(self, handle, rank):
+        self._h, self.rank = handle, rank
+
+    def __del__(self):
+        if self._h and _lib is not None:
+            _lib.sp_encoding_free(self._h)
+            self._h = None
+
+
+class Tensor:
+    def __init__(self, handle, allocator, dtype, device):
+        self._h, self._allocator, self.dtype, self.device = handle, allocator, dtype, device
+
+    def free(self):
+        if self._h and _lib is not None:
+            _lib.sp_tensor_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.free()
+
+
+def sp_encode(level_types, dim_ordering=None, pos_width=0, crd_width=0, rank=None):
+    L = load_library()
+    rank = len(level_types) if rank is None else rank
+    lt = (ctypes.c_int * max(len(level_types), 1))(*[int(x) for x in level_types])
+    order = None
+    if dim_ordering is not None:
+        order = (ctypes.c_int * max(len(dim_ordering), 1))(*[int(x) for x in dim_ordering])
+    h = ctypes.c_void_p()
+    _check(L.sp_encode(rank, lt, order, pos_width, crd_width, ctypes.byref(h)), "in sp_encode")
+    return Encoding(h, rank)
+
+
+def _dt(t):
+    if t.dtype == torch.float64:
+        return SP_F64
+    if t.dtype == torch.float32:
+        return SP_F32
+    return -1
+
+
+def sp_pack(enc, shape, coords, values):
+    """coords: one int64 device tensor per dimension; values: device tensor (f32/f64)."""
+    L = load_library()
+    assert values.is_cuda and all(c.is_cuda and c.dtype == torch.int64 and c.is_contiguous() for c in coords)
+    assert values.is_contiguous()
+    nnz = int(values.shape[0])
+    shp = (ctypes.c_int64 * max(len(shape), 1))(*[int(s) for s in shape])
+    carr = (ctypes.c_void_p * max(len(coords), 1))(*[c.data_ptr() for c in coords])
+    allocator = _TorchAllocator(values.device)
+    h = ctypes.c_void_p()
+    code = L.sp_pack(enc._h, shp, nnz, carr, values.data_ptr(), _dt(values), allocator.alloc_cb, allocator.free_cb, None,
+                     _stream_ptr(), ctypes.byref(h))
+    _check(code, "in sp_pack")
+    return Tensor(h, allocator, values.dtype, values.device)
+
+
+def sp_matmul(A, B, C, accumulate=False, N=None, ldb=None, ldc=None):
+    """C = A.B (or C += A.B).  B: (n, N) or (n,), C: (m, N) or (m,), row-major device tensors of A's dtype."""
+    L = load_library()
+    assert B.is_cuda and C.is_cuda and B.dtype == A.dtype and C.dtype == A.dtype
+    if N is None:
+        N = 1 if B.dim() == 1 else int(B.shape[1])
+    if ldb is None:
+        ldb = 1 if B.dim() == 1 else int(B.stride(0))
+    if ldc is None:
+        ldc = 1 if C.dim() == 1 else int(C.stride(0))
+    _check(L.sp_matmul(A._h, B.data_ptr(), N, ldb, C.data_ptr(), ldc, int(bool(accumulate)), _stream_ptr()), "in sp_matmul")
+    return C
+
+
+_INT = {32: torch.int32, 64: torch.int64}
+
+
+def sp_tensor_info(A):
+    L = load_library()
+    info = SpInfo()
+    _check(L.sp_tensor_info(A._h, ctypes.byref(info)))
+    return info
+
+
+def _view(A, ptr, length, dtype):
+    """Borrowed torch view of an array the library allocated through the tensor's allocator (valid until A is freed)."""
+    if length == 0:
+        return torch.empty(0, dtype=dtype, device=A.device)
+    owner = A._allocator.live[ptr]
+    return owner[: length * torch.empty(0, dtype=dtype).element_size()].view(dtype)
+
+
+def sp_pos(A, level):
+    """pos[level] as a borrowed device tensor (int32/int64)."""
+    L = load_library()
+    p, n = ctypes.c_void_p(), ctypes.c_int64()
+    _check(L.sp_pos(A._h, level, ctypes.byref(p), ctypes.byref(n)), "in sp_pos")
+    return _view(A, p.value, n.value, _INT[sp_tensor_info(A).posWidth])
+
+
+def sp_crd(A, level):
+    L = load_library()
+    p, n = ctypes.c_void_p(), ctypes.c_int64()
+    _check(L.sp_crd(A._h, level, ctypes.byref(p), ctypes.byref(n)), "in sp_crd")
+    return _view(A, p.value, n.value, _INT[sp_tensor_info(A).crdWidth])
+
+
+def sp_values(A):
+    L = load_library()
+    p, n = ctypes.c_void_p(), ctypes.c_int64()
+    _check(L.sp_values(A._h, ctypes.byref(p), ctypes.byref(n)), "in sp_values")
+    return _view(A, p.value, n.value, A.dtype)
+
+
+def sp_unpack(A):
+    """(coords per dimension, values): every stored position in storage order, as device tensors."""
+    L = load_library()
+    info = sp_tensor_info(A)
+    n = info.nvalues
+    coords = [torch.empty(n, dtype=torch.int64, device=A.device) for _ in range(info.rank)]
+    vals = torch.empty(n, dtype=A.dtype, device=A.device)
+    carr = (ctypes.c_void_p * info.rank)(*[c.data_ptr() for c in coords])
+    _check(L.sp_unpack(A._h, carr, vals.data_ptr(), _stream_ptr()), "in sp_unpack")
+    return coords, vals
+
+
+def sp_tensor_tune(A, key, value):
+    _check(load_library().sp_tensor_tune(A._h, key, value), "in sp_tensor_tune")
+
+
+def sp_stream_copy(dst, src):
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().sp_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr()), "in sp_stream_copy")

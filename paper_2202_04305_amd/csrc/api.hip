@@ -1,0 +1,197 @@
+// C ABI entry points that are not the storage builder: the encoding attribute, the product's
+// dispatch, the pointers / indices / values accessors (arXiv 2202.04305, Sections 4.1 and 4.2).
+#include "spmi_internal.h"
+
+thread_local int g_last_hip_error = 0;
+
+extern "C" int sp_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" const char *sp_status_str(sp_status s)
+{
+    switch (s) {
+    case SP_OK: return "ok";
+    case SP_ERR_NULL: return "null pointer";
+    case SP_ERR_RANK: return "bad rank";
+    case SP_ERR_LEVEL_TYPE: return "bad level type";
+    case SP_ERR_ORDERING: return "dimension ordering is not a permutation";
+    case SP_ERR_WIDTH: return "bad or too narrow bit width";
+    case SP_ERR_COORD_RANGE: return "coordinate out of range";
+    case SP_ERR_DUPLICATE: return "duplicate coordinate";
+    case SP_ERR_SHAPE: return "bad shape or leading dimension";
+    case SP_ERR_DTYPE: return "bad dtype";
+    case SP_ERR_UNSUPPORTED: return "not supported on the GPU path";
+    case SP_ERR_TOO_LARGE: return "too large";
+    case SP_ERR_ALLOC: return "allocation failed";
+    case SP_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+extern "C" sp_status sp_encode(int rank, const sp_level_type *levelTypes, const int *dimOrdering, int posWidth, int crdWidth,
+                               sp_encoding **out)
+{
+    if (!levelTypes || !out) return SP_ERR_NULL;
+    *out = nullptr;
+    if (rank < 1 || rank > SP_MAX_RANK) return SP_ERR_RANK;
+    for (int l = 0; l < rank; ++l)
+        if (levelTypes[l] != SP_DENSE && levelTypes[l] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
+    bool seen[SP_MAX_RANK] = {false};
+    for (int l = 0; l < rank; ++l) {
+        const int d = dimOrdering ? dimOrdering[l] : l;
+        if (d < 0 || d >= rank || seen[d]) return SP_ERR_ORDERING;
+        seen[d] = true;
+    }
+    auto ok = [](int w) { return w == 0 || w == 32 || w == 64; };
+    if (!ok(posWidth) || !ok(crdWidth)) return SP_ERR_WIDTH;
+    sp_encoding *e = new sp_encoding();
+    memset(e, 0, sizeof(*e));
+    e->rank = rank;
+    for (int l = 0; l < rank; ++l) {
+        e->lt[l] = (int)levelTypes[l];
+        e->perm[l] = dimOrdering ? dimOrdering[l] : l;
+    }
+    e->pw = posWidth ? posWidth : 64;
+    e->cw = crdWidth ? crdWidth : 64;
+    *out = e;
+    return SP_OK;
+}
+
+extern "C" void sp_encoding_free(sp_encoding *enc) { delete enc; }
+
+extern "C" sp_status sp_pos(const sp_tensor *t, int level, const void **ptr, int64_t *len)
+{
+    if (!t || !ptr || !len) return SP_ERR_NULL;
+    if (level < 0 || level >= t->enc.rank) return SP_ERR_RANK;
+    if (t->enc.lt[level] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
+    *ptr = t->pos[level];
+    *len = t->npos[level];
+    return SP_OK;
+}
+
+extern "C" sp_status sp_crd(const sp_tensor *t, int level, const void **ptr, int64_t *len)
+{
+    if (!t || !ptr || !len) return SP_ERR_NULL;
+    if (level < 0 || level >= t->enc.rank) return SP_ERR_RANK;
+    if (t->enc.lt[level] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
+    *ptr = t->crd[level];
+    *len = t->ncrd[level];
+    return SP_OK;
+}
+
+extern "C" sp_status sp_values(const sp_tensor *t, const void **ptr, int64_t *len)
+{
+    if (!t || !ptr || !len) return SP_ERR_NULL;
+    *ptr = t->values;
+    *len = t->nvalues;
+    return SP_OK;
+}
+
+extern "C" sp_status sp_tensor_info(const sp_tensor *t, sp_info *info)
+{
+    if (!t || !info) return SP_ERR_NULL;
+    memset(info, 0, sizeof(*info));
+    info->rank = t->enc.rank;
+    int64_t bytes = t->nvalues * (t->dtype == SP_F64 ? 8 : 4);
+    for (int l = 0; l < t->enc.rank; ++l) {
+        info->levelTypes[l] = t->enc.lt[l];
+        info->dimOrdering[l] = t->enc.perm[l];
+        info->shape[l] = t->shape[l];
+        if (t->enc.lt[l] == SP_COMPRESSED) bytes += t->npos[l] * (t->enc.pw / 8) + t->ncrd[l] * (t->enc.cw / 8);
+    }
+    info->posWidth = t->enc.pw;
+    info->crdWidth = t->enc.cw;
+    info->dtype = t->dtype;
+    info->nnz = t->nnz;
+    info->nvalues = t->nvalues;
+    info->maxSegment = t->max_segment;
+    info->storageBytes = bytes;
+    return SP_OK;
+}
+
+extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
+{
+    if (!t) return SP_ERR_NULL;
+    switch (key) {
+    case SP_TUNE_SPMV_KERNEL:
+        if (value < 0 || value > 2) return SP_ERR_UNSUPPORTED;
+        t->tune_spmv = (int)value;
+        if (t->transposed) t->transposed->tune_spmv = (int)value;
+        return SP_OK;
+    case SP_TUNE_CSC_MODE:
+        if (value < 0 || value > 2) return SP_ERR_UNSUPPORTED;
+        t->tune_csc = (int)value;
+        return SP_OK;
+    case SP_TUNE_SPMM_KERNEL:
+        if (value != 0) return SP_ERR_UNSUPPORTED;
+        t->tune_spmm = (int)value;
+        return SP_OK;
+    }
+    return SP_ERR_UNSUPPORTED;
+}
+
+// Row-major copy of a column-major tensor, through the coordinate scheme (the paper's route for
+// conversions, Section 4.2).  Built on first use and kept by the handle.
+static sp_status build_transposed(sp_tensor *A, hipStream_t st)
+{
+    if (A->transposed) return SP_OK;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    sp_status s = SP_OK;
+    sp_tensor *T = nullptr;
+    {
+        sp_scratch tmp(mem);
+        const size_t cnt = (size_t)(A->nvalues > 0 ? A->nvalues : 1);
+        int64_t *rows = (int64_t *)tmp.get(cnt * 8);
+        int64_t *cols = (int64_t *)tmp.get(cnt * 8);
+        void *vals = tmp.get(cnt * 8);
+        if (!rows || !cols || !vals) return SP_ERR_ALLOC;
+        int64_t *coords[2] = {rows, cols};
+        SP_TRY(sp_unpack(A, coords, vals, st));
+        sp_encoding enc = A->enc;
+        enc.perm[0] = 0; enc.perm[1] = 1;
+        const int64_t *ccoords[2] = {rows, cols};
+        s = sp_pack(&enc, A->shape, A->nvalues, ccoords, vals, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, st, &T);
+    }
+    if (s != SP_OK) return s;
+    T->tune_spmv = A->tune_spmv;
+    A->transposed = T;
+    return SP_OK;
+}
+
+extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
+                               void *stream)
+{
+    if (!A) return SP_ERR_NULL;
+    if (A->enc.rank != 2) return SP_ERR_RANK;
+    if (N < 0 || ldb < N || ldc < N || ldb < 1 || ldc < 1) return SP_ERR_SHAPE;
+    const int64_t m = A->shape[0], n = A->shape[1];
+    if (N == 0 || m == 0) return SP_OK;
+    if (!C || (!B && n > 0)) return SP_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (A->enc.lt[1] != SP_COMPRESSED) return SP_ERR_UNSUPPORTED;     // dense innermost level: no GPU kernel yet
+    if (A->enc.perm[0] == 0) return spmi_matmul_rowmajor(A, B, N, ldb, C, ldc, accumulate, st);
+    int mode = A->tune_csc ? A->tune_csc : 2;
+    if (mode == 1) return spmi_matmul_colmajor_scatter(A, B, N, ldb, C, ldc, accumulate, st);
+    SP_TRY(build_transposed(const_cast<sp_tensor *>(A), st));
+    return spmi_matmul_rowmajor(A->transposed, B, N, ldb, C, ldc, accumulate, st);
+}
+
+// ---- plain streaming copy: the bandwidth yardstick ----------------------------------------
+__global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+extern "C" sp_status sp_stream_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return SP_ERR_NULL;
+    if (bytes % 16) return SP_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return SP_OK;
+    size_t nb = (n16 + 255) / 256;
+    if (nb > 256 * 32) nb = 256 * 32;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)nb), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}

@@ -1,0 +1,338 @@
+// C[i,j] = sum_k A[i,k] * B[k,j] with A sparse and B, C dense row-major (arXiv 2202.04305,
+// Section 1: the SpMM kernel; Section 6.2: matrix times vector).  The loops the paper's
+// compiler would emit visit, per outer position, the pos range of the inner compressed
+// level (Section 4.3); the kernels below visit exactly those entries, split differently:
+//
+//   rows kernel      G lanes per stored row, strided over the row, shuffle reduction.
+//   stream kernel    SpMV: every block owns 2048 consecutive stored entries whatever rows
+//                    they belong to: coalesced crd/values stream, gathered x, products
+//                    staged in LDS, rows reduced from LDS (a thread per short row, a wave per
+//                    long one); rows that cross a block boundary are completed by a small
+//                    fix-up kernel from per-block carries (deterministic, no atomics).
+//   spmm kernel      one wave per stored row, lanes across the columns of B.
+//   scatter kernel   column-major storage (CSC / DCSC): a wave per stored column, atomic
+//                    adds into the rows of C.
+//
+// "Row-major" means the outer level holds dimension 0; that level may be dense (CSR: row =
+// position) or compressed (DCSR: row = crd0[position], so empty rows cost nothing).
+#include "spmi_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kStreamT = 2048;      // stored entries per block of the stream kernel (matches the row blocks built at pack)
+constexpr int kLongRow = 64;        // in-window row length above which a wave reduces the row
+constexpr int kQueue = 64;
+static_assert(kStreamT / (kLongRow + 1) < kQueue, "queue of long rows too small");
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+template <typename VT>
+__global__ __launch_bounds__(kThreads) void zero_matrix_kernel(VT *__restrict__ C, int64_t m, int64_t N, int64_t ldc)
+{
+    const int64_t total = m * N;
+    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) C[(i / N) * ldc + (i % N)] = (VT)0;
+}
+
+// ---- G lanes per stored row -------------------------------------------------------------
+template <typename PT, typename CT, typename VT, int G>
+__global__ __launch_bounds__(kThreads) void spmv_rows_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                             const VT *__restrict__ val, const CT *__restrict__ rowid, int64_t nrows,
+                                                             const VT *__restrict__ x, int64_t ldb, VT *__restrict__ y, int64_t ldc,
+                                                             int accumulate)
+{
+    const int64_t r = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / G;
+    const int sub = threadIdx.x % G;
+    VT acc = 0;
+    if (r < nrows) {
+        const int64_t a = (int64_t)pos[r], b = (int64_t)pos[r + 1];
+        for (int64_t p = a + sub; p < b; p += G) acc += val[p] * x[(int64_t)crd[p] * ldb];
+    }
+#pragma unroll
+    for (int d = G / 2; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (sub == 0 && r < nrows) {
+        const int64_t row = rowid ? (int64_t)rowid[r] : r;
+        y[row * ldc] = accumulate ? y[row * ldc] + acc : acc;
+    }
+}
+
+// ---- stream kernel ----------------------------------------------------------------------
+template <typename PT, typename CT, typename VT>
+__global__ __launch_bounds__(kThreads) void spmv_stream_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                               const VT *__restrict__ val, const CT *__restrict__ rowid,
+                                                               const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
+                                                               const VT *__restrict__ x, int64_t ldb, VT *__restrict__ y, int64_t ldc,
+                                                               VT *__restrict__ carry, int accumulate)
+{
+    __shared__ VT prods[kStreamT];
+    __shared__ int queue[kQueue];
+    __shared__ int qn;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t s = (int64_t)blockIdx.x * kStreamT;
+    const int64_t e = (s + kStreamT < nnz) ? s + kStreamT : nnz;
+    if (tid == 0) qn = 0;
+
+    // phase A: products of this block's entries into LDS (two consecutive entries per lane and step)
+    if (e - s == kStreamT) {
+        CT k[8];
+        VT v[8];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t p = s + (int64_t)(t * kThreads + tid) * 2;
+            k[2 * t] = crd[p]; k[2 * t + 1] = crd[p + 1];
+            v[2 * t] = val[p]; v[2 * t + 1] = val[p + 1];
+        }
+        VT xv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xv[i] = x[(int64_t)k[i] * ldb];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            prods[(t * kThreads + tid) * 2] = v[2 * t] * xv[2 * t];
+            prods[(t * kThreads + tid) * 2 + 1] = v[2 * t + 1] * xv[2 * t + 1];
+        }
+    } else {
+        for (int i = tid; i < (int)(e - s); i += kThreads) prods[i] = val[s + i] * x[(int64_t)crd[s + i] * ldb];
+    }
+    __syncthreads();
+
+    // phase B: rows lo..hi meet this window.  Rows lo..hi-1 end here and are written; row hi only
+    // starts here (its head goes to y, the rest arrives through later blocks' carries); if row lo
+    // began in an earlier window its part goes to this block's carry.
+    const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
+    const bool lo_carried = (int64_t)pos[lo] < s;
+    const int64_t last = hi < nrows ? hi : nrows - 1;
+    for (int64_t r = lo + tid; r <= last; r += kThreads) {
+        const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
+        const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
+        if (r == hi && b <= a) continue;             // row hi starts at the next window: not ours
+        if (b - a > kLongRow) { queue[atomicAdd(&qn, 1)] = (int)(r - lo); continue; }
+        VT sum = 0;
+        for (int i = a; i < b; ++i) sum += prods[i];
+        if (r == lo && lo_carried) carry[blockIdx.x] = sum;
+        else {
+            const int64_t row = rowid ? (int64_t)rowid[r] : r;
+            y[row * ldc] = accumulate ? y[row * ldc] + sum : sum;
+        }
+    }
+    __syncthreads();
+    const int nq = qn;
+    for (int q = wave; q < nq; q += kThreads / 64) {
+        const int64_t r = lo + queue[q];
+        const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
+        const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
+        VT sum = 0;
+        for (int i = a + lane; i < b; i += 64) sum += prods[i];
+        sum = wave_sum(sum);
+        if (lane == 0) {
+            if (r == lo && lo_carried) carry[blockIdx.x] = sum;
+            else {
+                const int64_t row = rowid ? (int64_t)rowid[r] : r;
+                y[row * ldc] = accumulate ? y[row * ldc] + sum : sum;
+            }
+        }
+    }
+}
+
+// One thread per block boundary: the first boundary a row crosses adds all of that row's carries, in
+// block order, to the head part already in y.
+template <typename PT, typename CT, typename VT>
+__global__ __launch_bounds__(kThreads) void spmv_stream_fixup_kernel(const PT *__restrict__ pos, const CT *__restrict__ rowid,
+                                                                     const int32_t *__restrict__ rowblk, int64_t nblocks,
+                                                                     const VT *__restrict__ carry, VT *__restrict__ y, int64_t ldc)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x + 1;
+    if (b >= nblocks) return;
+    const int64_t r = rowblk[b];
+    const int64_t start = (int64_t)pos[r];
+    if (start >= b * kStreamT || start < (b - 1) * kStreamT) return;   // not crossed here, or crossed earlier already
+    VT sum = 0;
+    for (int64_t bb = b; bb < nblocks && rowblk[bb] == r; ++bb) sum += carry[bb];
+    const int64_t row = rowid ? (int64_t)rowid[r] : r;
+    y[row * ldc] += sum;
+}
+
+// ---- SpMM: a wave per stored row, CG lanes across a tile of B's columns, 64/CG entries in flight ----
+template <typename PT, typename CT, typename VT, int CG>
+__global__ __launch_bounds__(kThreads) void spmm_rows_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                             const VT *__restrict__ val, const CT *__restrict__ rowid, int64_t nrows,
+                                                             const VT *__restrict__ B, int64_t N, int64_t ldb, VT *__restrict__ C,
+                                                             int64_t ldc, int accumulate)
+{
+    constexpr int S = 64 / CG;                        // entries of the row handled side by side
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= nrows) return;                           // whole wave
+    const int jl = lane % CG, sl = lane / CG;
+    const int64_t a = (int64_t)pos[r], b = (int64_t)pos[r + 1];
+    const int64_t row = rowid ? (int64_t)rowid[r] : r;
+    for (int64_t j0 = 0; j0 < N; j0 += CG) {
+        const int64_t j = j0 + jl;
+        const bool jin = j < N;
+        VT acc0 = 0, acc1 = 0;
+        int64_t p = a + sl;
+        for (; p + S < b; p += 2 * S) {               // two independent gathers in flight per lane
+            const int64_t k0 = (int64_t)crd[p], k1 = (int64_t)crd[p + S];
+            const VT v0 = val[p], v1 = val[p + S];
+            if (jin) { acc0 += v0 * B[k0 * ldb + j]; acc1 += v1 * B[k1 * ldb + j]; }
+        }
+        if (p < b && jin) acc0 += val[p] * B[(int64_t)crd[p] * ldb + j];
+        VT acc = acc0 + acc1;
+#pragma unroll
+        for (int d = 32; d >= CG; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        if (sl == 0 && jin) C[row * ldc + j] = accumulate ? C[row * ldc + j] + acc : acc;
+    }
+}
+
+// ---- column-major storage: a wave per stored column, atomic adds into C ------------------
+template <typename PT, typename CT, typename VT, int CG>
+__global__ __launch_bounds__(kThreads) void spmm_scatter_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                                const VT *__restrict__ val, const CT *__restrict__ colid, int64_t ncols,
+                                                                const VT *__restrict__ B, int64_t N, int64_t ldb, VT *__restrict__ C,
+                                                                int64_t ldc)
+{
+    constexpr int S = 64 / CG;
+    const int lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (q >= ncols) return;
+    const int jl = lane % CG, sl = lane / CG;
+    const int64_t a = (int64_t)pos[q], b = (int64_t)pos[q + 1];
+    if (a == b) return;
+    const int64_t k = colid ? (int64_t)colid[q] : q;
+    for (int64_t j0 = 0; j0 < N; j0 += CG) {
+        const int64_t j = j0 + jl;
+        if (j >= N) continue;
+        const VT bj = B[k * ldb + j];
+        for (int64_t p = a + sl; p < b; p += S) unsafeAtomicAdd(&C[(int64_t)crd[p] * ldc + j], val[p] * bj);
+    }
+}
+
+inline unsigned grid_for(int64_t n, int64_t per_block) { return (unsigned)(n > 0 ? ceil_div(n, per_block) : 1); }
+
+template <typename PT, typename CT, typename VT>
+sp_status zero_c(VT *C, int64_t m, int64_t N, int64_t ldc, hipStream_t st)
+{
+    if (m * N == 0) return SP_OK;
+    const int64_t nb = ceil_div(m * N, kThreads);
+    hipLaunchKernelGGL(zero_matrix_kernel<VT>, dim3((unsigned)(nb < 16384 ? nb : 16384)), dim3(kThreads), 0, st, C, m, N, ldc);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+template <typename PT, typename CT, typename VT>
+sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
+{
+    const PT *pos = (const PT *)A->pos[1];
+    const CT *crd = (const CT *)A->crd[1];
+    const VT *val = (const VT *)A->values;
+    const bool dcsr = A->enc.lt[0] == SP_COMPRESSED;
+    const CT *rowid = dcsr ? (const CT *)A->crd[0] : nullptr;
+    const int64_t nrows = A->npos[1] - 1;              // stored rows
+    const int64_t m = A->shape[0];
+    const int64_t nnz = A->ncrd[1];
+    if (dcsr && !accumulate) SP_TRY((zero_c<PT, CT, VT>(C, m, N, ldc, st)));   // rows that are not stored become zero
+    if (nrows == 0) return SP_OK;
+    if (N == 1) {
+        int kernel = A->tune_spmv;
+        if (kernel == 0) kernel = (A->rowblocks.start && nnz >= 8 * kStreamT) ? 2 : 1;
+        if (kernel == 2 && !A->rowblocks.start) return SP_ERR_UNSUPPORTED;
+        if (kernel == 2) {
+            const int64_t nb = A->rowblocks.nblocks;
+            hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,
+                               (const int32_t *)A->rowblocks.start, nrows, nnz, B, ldb, C, ldc, (VT *)A->rowblocks.carry, accumulate);
+            SP_HIP(hipGetLastError());
+            if (nb > 1) {
+                hipLaunchKernelGGL((spmv_stream_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads)), dim3(kThreads), 0, st, pos,
+                                   rowid, (const int32_t *)A->rowblocks.start, nb, (const VT *)A->rowblocks.carry, C, ldc);
+                SP_HIP(hipGetLastError());
+            }
+            return SP_OK;
+        }
+        const double avg = (double)nnz / (double)nrows;
+#define SPMI_ROWS(G)                                                                                                          \
+    hipLaunchKernelGGL((spmv_rows_kernel<PT, CT, VT, G>), dim3(grid_for(nrows * G, kThreads)), dim3(kThreads), 0, st, pos, crd, \
+                       val, rowid, nrows, B, ldb, C, ldc, accumulate)
+        if (avg <= 3) SPMI_ROWS(2);
+        else if (avg <= 6) SPMI_ROWS(4);
+        else if (avg <= 12) SPMI_ROWS(8);
+        else if (avg <= 24) SPMI_ROWS(16);
+        else if (avg <= 48) SPMI_ROWS(32);
+        else SPMI_ROWS(64);
+#undef SPMI_ROWS
+        SP_HIP(hipGetLastError());
+        return SP_OK;
+    }
+#define SPMI_SPMM(CG)                                                                                                         \
+    hipLaunchKernelGGL((spmm_rows_kernel<PT, CT, VT, CG>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, crd, \
+                       val, rowid, nrows, B, N, ldb, C, ldc, accumulate)
+    if (N > 32) SPMI_SPMM(64);
+    else if (N > 16) SPMI_SPMM(32);
+    else if (N > 8) SPMI_SPMM(16);
+    else if (N > 4) SPMI_SPMM(8);
+    else SPMI_SPMM(4);
+#undef SPMI_SPMM
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+template <typename PT, typename CT, typename VT>
+sp_status scatter_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
+{
+    const PT *pos = (const PT *)A->pos[1];
+    const CT *crd = (const CT *)A->crd[1];
+    const VT *val = (const VT *)A->values;
+    const CT *colid = A->enc.lt[0] == SP_COMPRESSED ? (const CT *)A->crd[0] : nullptr;
+    const int64_t ncols = A->npos[1] - 1;
+    if (!accumulate) SP_TRY((zero_c<PT, CT, VT>(C, A->shape[0], N, ldc, st)));
+    if (ncols == 0) return SP_OK;
+#define SPMI_SCAT(CG)                                                                                                         \
+    hipLaunchKernelGGL((spmm_scatter_kernel<PT, CT, VT, CG>), dim3(grid_for(ncols, kThreads / 64)), dim3(kThreads), 0, st, pos, \
+                       crd, val, colid, ncols, B, N, ldb, C, ldc)
+    if (N > 32) SPMI_SCAT(64);
+    else if (N > 16) SPMI_SCAT(32);
+    else if (N > 8) SPMI_SCAT(16);
+    else if (N > 4) SPMI_SCAT(8);
+    else if (N > 2) SPMI_SCAT(4);
+    else if (N > 1) SPMI_SCAT(2);
+    else SPMI_SCAT(1);
+#undef SPMI_SCAT
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+}  // namespace
+
+#define SPMI_DISPATCH_TYPES(FN, A, ...)                                                             \
+    do {                                                                                            \
+        const int pw__ = (A)->enc.pw, cw__ = (A)->enc.cw;                                           \
+        if ((A)->dtype == SP_F64) {                                                                 \
+            if (pw__ == 32 && cw__ == 32) return FN<int32_t, int32_t, double>(A, (const double *)B, N, ldb, (double *)C, ldc, accumulate, st); \
+            if (pw__ == 32) return FN<int32_t, int64_t, double>(A, (const double *)B, N, ldb, (double *)C, ldc, accumulate, st);               \
+            if (cw__ == 32) return FN<int64_t, int32_t, double>(A, (const double *)B, N, ldb, (double *)C, ldc, accumulate, st);               \
+            return FN<int64_t, int64_t, double>(A, (const double *)B, N, ldb, (double *)C, ldc, accumulate, st);                               \
+        } else {                                                                                    \
+            if (pw__ == 32 && cw__ == 32) return FN<int32_t, int32_t, float>(A, (const float *)B, N, ldb, (float *)C, ldc, accumulate, st);    \
+            if (pw__ == 32) return FN<int32_t, int64_t, float>(A, (const float *)B, N, ldb, (float *)C, ldc, accumulate, st);                  \
+            if (cw__ == 32) return FN<int64_t, int32_t, float>(A, (const float *)B, N, ldb, (float *)C, ldc, accumulate, st);                  \
+            return FN<int64_t, int64_t, float>(A, (const float *)B, N, ldb, (float *)C, ldc, accumulate, st);                                  \
+        }                                                                                           \
+    } while (0)
+
+sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
+                               hipStream_t st)
+{
+    SPMI_DISPATCH_TYPES(rowmajor_t, A);
+}
+
+sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc,
+                                       int accumulate, hipStream_t st)
+{
+    SPMI_DISPATCH_TYPES(scatter_t, A);
+}

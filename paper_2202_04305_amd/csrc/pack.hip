@@ -1,0 +1,657 @@
+// Storage builder: coordinate scheme -> pos / crd / values per level (arXiv 2202.04305, Section 4.1).
+//
+// Steps, all on the GPU: linearise the level coordinates into one 64-bit key per entry,
+// stable LSD radix sort of (key, entry id), adjacent-equal check for duplicates, then one
+// sweep per level: a compressed level marks where a new (parent, coordinate) pair starts,
+// prefix-sums the marks into child positions, counts children per parent and prefix-sums
+// the counts into pos; a dense level only folds the coordinate into the position.  The
+// values are gathered last.  Only level sizes and the error flags travel to the host.
+#include "spmi_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// ---------------------------------------------------------------------------------------
+// exclusive scan (reduce / recurse on tile sums / downsweep): no spinning on other blocks
+// ---------------------------------------------------------------------------------------
+constexpr int kScanItems = 8;
+constexpr int kScanTile = kThreads * kScanItems;
+
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const T *__restrict__ data, int64_t n, T *__restrict__ sums)
+{
+    __shared__ T wsum[kThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    T s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i)
+        if (base + i < n) s += data[base + i];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T tot = 0;
+        for (int w = 0; w < kThreads / 64; ++w) tot += wsum[w];
+        sums[blockIdx.x] = tot;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void scan_downsweep_kernel(T *__restrict__ data, int64_t n, const T *__restrict__ tile_base)
+{
+    __shared__ T wsum[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    T v[kScanItems];
+    T s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        v[i] = (base + i < n) ? data[base + i] : (T)0;
+        s += v[i];
+    }
+    T incl = wave_inclusive_scan(s, lane);
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    T run = tile_base ? tile_base[blockIdx.x] : (T)0;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+    run += incl - s;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        if (base + i < n) data[base + i] = run;
+        run += v[i];
+    }
+}
+
+template <typename T>
+sp_status exclusive_scan_t(T *data, int64_t n, sp_scratch &tmp, hipStream_t st)
+{
+    if (n <= 0) return SP_OK;
+    const int64_t nt = ceil_div(n, kScanTile);
+    if (nt == 1) {
+        hipLaunchKernelGGL(scan_downsweep_kernel<T>, dim3(1), dim3(kThreads), 0, st, data, n, (const T *)nullptr);
+        SP_HIP(hipGetLastError());
+        return SP_OK;
+    }
+    T *sums = (T *)tmp.get((size_t)nt * sizeof(T));
+    if (!sums) return SP_ERR_ALLOC;
+    hipLaunchKernelGGL(scan_reduce_kernel<T>, dim3((unsigned)nt), dim3(kThreads), 0, st, (const T *)data, n, sums);
+    SP_HIP(hipGetLastError());
+    SP_TRY(exclusive_scan_t<T>(sums, nt, tmp, st));
+    hipLaunchKernelGGL(scan_downsweep_kernel<T>, dim3((unsigned)nt), dim3(kThreads), 0, st, data, n, (const T *)sums);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// LSD radix sort, 8-bit digits, (u64 key, u32 payload)
+// ---------------------------------------------------------------------------------------
+constexpr int kSortRounds = 16;
+constexpr int kSortTile = kThreads * kSortRounds;
+
+__global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, int shift,
+                                                              uint32_t *__restrict__ hist, int nblocks)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll 4
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int64_t i = tile0 + (int64_t)r * kThreads + threadIdx.x;
+        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];   // digit-major: one scan gives global offsets
+}
+
+// Lanes of the wave that hold the same digit as this lane (among lanes with valid set).
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
+{
+    uint64_t m = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bb = __ballot(bit);
+        m &= bit ? bb : ~bb;
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
+                                                                 uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
+                                                                 const uint32_t *__restrict__ offs, int64_t n, int shift, int nblocks)
+{
+    __shared__ uint32_t base[256];                    // next output slot of each digit for this block
+    __shared__ uint32_t wcnt[kThreads / 64][256];     // per-wave digit counts of the current round
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    base[tid] = offs[(int64_t)tid * nblocks + blockIdx.x];
+    const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int64_t i = tile0 + (int64_t)r * kThreads + tid;
+        if (tile0 + (int64_t)r * kThreads >= n) break;            // uniform across the block
+        const bool valid = i < n;
+        const uint64_t k = valid ? kin[i] : 0;
+        const uint32_t v = valid ? vin[i] : 0;
+        const uint32_t d = (uint32_t)(k >> shift) & 255u;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) wcnt[w][tid] = 0;
+        __syncthreads();
+        const uint64_t m = match_digit(d, valid);
+        const uint32_t rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (valid && rank == 0) wcnt[wave][d] = (uint32_t)__popcll(m);
+        __syncthreads();
+        if (valid) {
+            uint32_t p = base[d] + rank;
+            for (int w = 0; w < wave; ++w) p += wcnt[w][d];
+            kout[p] = k;
+            vout[p] = v;
+        }
+        __syncthreads();
+        uint32_t add = 0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) add += wcnt[w][tid];
+        base[tid] += add;
+    }
+}
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t nwords)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < nwords; i += stride) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------
+// keys, levels, values
+// ---------------------------------------------------------------------------------------
+struct level_args {
+    const int64_t *coord[SP_MAX_RANK];   // by level
+    int64_t size[SP_MAX_RANK];
+    int rank;
+};
+
+__global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64_t nnz, uint64_t *__restrict__ keys,
+                                                             uint32_t *__restrict__ idx, int *__restrict__ flags)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    uint64_t key = 0;
+    bool bad = false;
+    for (int l = 0; l < a.rank; ++l) {
+        const int64_t c = a.coord[l][e];
+        bad |= (c < 0) | (c >= a.size[l]);
+        key = key * (uint64_t)a.size[l] + (uint64_t)c;
+    }
+    keys[e] = bad ? 0 : key;
+    idx[e] = (uint32_t)e;
+    if (bad) atomicOr(&flags[0], 1);
+}
+
+__global__ __launch_bounds__(kThreads) void check_duplicates_kernel(const uint64_t *__restrict__ keys, int64_t nnz, int *__restrict__ flags)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= 1 && e < nnz && keys[e] == keys[e - 1]) atomicOr(&flags[1], 1);
+}
+
+// dense level: position = parent * size + coordinate
+__global__ __launch_bounds__(kThreads) void dense_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
+                                                               uint64_t size, const uint64_t *__restrict__ parent_in,
+                                                               uint64_t *__restrict__ parent_out)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    const uint64_t c = (keys[e] / stride) % size;
+    parent_out[e] = (parent_in ? parent_in[e] : 0ull) * size + c;
+}
+
+// compressed level, step 1: mark[e] = 1 where the key prefix down to this level changes
+__global__ __launch_bounds__(kThreads) void mark_children_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
+                                                                 uint32_t *__restrict__ mark)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    mark[e] = (e == 0 || keys[e] / stride != keys[e - 1] / stride) ? 1u : 0u;
+}
+
+// compressed level, step 2: write crd, count children per parent (one add per run end, one
+// subtract per run start: integer atomics, so the result does not depend on their order),
+// and hand each entry its child position.  child_excl = exclusive scan of the marks, or
+// nullptr on the innermost level, where every entry is its own child.
+template <typename PT, typename CT>
+__global__ __launch_bounds__(kThreads) void emit_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
+                                                              uint64_t size, const uint32_t *__restrict__ child_excl,
+                                                              const uint64_t *__restrict__ parent_in, uint64_t *__restrict__ parent_out,
+                                                              PT *__restrict__ cnt, CT *__restrict__ crd)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    const uint64_t pre = keys[e] / stride;
+    const bool first = (e == 0) || (keys[e - 1] / stride != pre);
+    const uint64_t child = child_excl ? (uint64_t)child_excl[e] + (first ? 1u : 0u) - 1u : (uint64_t)e;
+    if (first) crd[child] = (CT)(pre % size);
+    const uint64_t par = parent_in ? parent_in[e] : 0ull;
+    const bool head = (e == 0) || (parent_in && parent_in[e - 1] != par);
+    const bool tail = (e == nnz - 1) || (parent_in && parent_in[e + 1] != par);
+    typedef typename std::conditional<sizeof(PT) == 8, unsigned long long, unsigned int>::type UT;
+    if (tail) atomicAdd((UT *)&cnt[par], (UT)(child + 1));
+    if (head) atomicAdd((UT *)&cnt[par], (UT)(0) - (UT)child);
+    parent_out[e] = child;
+}
+
+template <typename VT>
+__global__ __launch_bounds__(kThreads) void gather_values_kernel(const VT *__restrict__ vin, const uint32_t *__restrict__ idx,
+                                                                 const uint64_t *__restrict__ position, int64_t nnz, VT *__restrict__ vout)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    vout[position ? position[e] : (uint64_t)e] = vin[idx[e]];
+}
+
+template <typename PT>
+__global__ __launch_bounds__(kThreads) void max_segment_kernel(const PT *__restrict__ pos, int64_t nseg, unsigned long long *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    unsigned long long len = (i < nseg) ? (unsigned long long)(pos[i + 1] - pos[i]) : 0ull;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        unsigned long long o = __shfl_xor(len, d, 64);
+        len = o > len ? o : len;
+    }
+    if ((threadIdx.x & 63) == 0 && len) atomicMax(out, len);
+}
+
+// row containing stored entry b*T (largest r with pos[r] <= b*T); block 0 starts at row 0 and the
+// sentinel is the row count, so that leading and trailing empty rows belong to some block.
+template <typename PT>
+__global__ __launch_bounds__(kThreads) void rowblocks_kernel(const PT *__restrict__ pos, int64_t nrows, int64_t nblocks, int64_t T,
+                                                             int32_t *__restrict__ start)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (b > nblocks) return;
+    if (b == 0) { start[0] = 0; return; }
+    if (b == nblocks) { start[b] = (int32_t)nrows; return; }
+    const int64_t target = b * T;
+    int64_t lo = 0, hi = nrows;            // invariant: pos[lo] <= target, pos[hi] > target or hi == nrows
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)pos[mid] <= target) lo = mid; else hi = mid;
+    }
+    start[b] = (int32_t)lo;
+}
+
+template <typename PT, typename CT>
+__global__ __launch_bounds__(kThreads) void unpack_kernel(int rank, level_args a /* coord[] unused */, const int *__restrict__ lt_perm,
+                                                          const void *const *__restrict__ pos_arr, const void *const *__restrict__ crd_arr,
+                                                          const int64_t *__restrict__ npos, int64_t nvalues, int64_t *const *__restrict__ out)
+{
+    const int64_t p0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p0 >= nvalues) return;
+    int64_t p = p0;
+    for (int l = rank - 1; l >= 0; --l) {
+        const int lt = lt_perm[l], dim = lt_perm[SP_MAX_RANK + l];
+        if (lt == SP_DENSE) {
+            out[dim][p0] = p % a.size[l];
+            p = p / a.size[l];
+        } else {
+            out[dim][p0] = (int64_t)((const CT *)crd_arr[l])[p];
+            const PT *pos = (const PT *)pos_arr[l];
+            int64_t lo = 0, hi = npos[l] - 1;       // largest q with pos[q] <= p  (q < npos-1 because pos[last] > p)
+            while (hi - lo > 1) {
+                const int64_t mid = (lo + hi) >> 1;
+                if ((int64_t)pos[mid] <= p) lo = mid; else hi = mid;
+            }
+            p = lo;
+        }
+    }
+}
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)(n > 0 ? ceil_div(n, kThreads) : 1); }
+
+}  // namespace
+
+// =========================================================================================
+void *sp_mem::get(size_t bytes) const
+{
+    if (alloc) return alloc(bytes, ctx);
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+    return p;
+}
+void sp_mem::put(void *p) const
+{
+    if (!p) return;
+    if (free_) free_(p, ctx); else (void)hipFree(p);
+}
+
+sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return SP_OK;
+    const size_t nwords = (bytes + 3) / 4;      // allocations are padded to 16 bytes by the callers
+    const unsigned nb = (unsigned)(nwords / kThreads + 1 < 4096 ? nwords / kThreads + 1 : 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(nb), dim3(kThreads), 0, st, (uint32_t *)p, nwords);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, hipStream_t st)
+{
+    if (bits == 32) return exclusive_scan_t<uint32_t>((uint32_t *)data, n, tmp, st);
+    return exclusive_scan_t<unsigned long long>((unsigned long long *)data, n, tmp, st);
+}
+
+sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
+{
+    if (n <= 1 || key_bits <= 0) return SP_OK;
+    const int passes = (key_bits + 7) / 8;
+    const int nblocks = (int)ceil_div(n, kSortTile);
+    uint64_t *kalt = (uint64_t *)tmp.get((size_t)n * 8);
+    uint32_t *valt = (uint32_t *)tmp.get((size_t)n * 4);
+    uint32_t *hist = (uint32_t *)tmp.get((size_t)256 * nblocks * 4);
+    if (!kalt || !valt || !hist) return SP_ERR_ALLOC;
+    uint64_t *kin = keys, *kout = kalt;
+    uint32_t *vin = vals, *vout = valt;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = 8 * p;
+        hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, n, shift, hist, nblocks);
+        SP_HIP(hipGetLastError());
+        SP_TRY(spmi_exclusive_scan(hist, (int64_t)256 * nblocks, 32, tmp, st));
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, (const uint32_t *)vin,
+                           kout, vout, (const uint32_t *)hist, n, shift, nblocks);
+        SP_HIP(hipGetLastError());
+        uint64_t *tk = kin; kin = kout; kout = tk;
+        uint32_t *tv = vin; vin = vout; vout = tv;
+    }
+    if (kin != keys) {      // odd number of passes: bring the result home
+        SP_HIP(hipMemcpyAsync(keys, kin, (size_t)n * 8, hipMemcpyDeviceToDevice, st));
+        SP_HIP(hipMemcpyAsync(vals, vin, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
+    }
+    return SP_OK;
+}
+
+static size_t pad16(size_t b) { return (b + 15) & ~(size_t)15; }
+
+sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st)
+{
+    // only for rank 2 with a compressed innermost level
+    if (t->enc.rank != 2 || t->enc.lt[1] != SP_COMPRESSED || t->rowblocks.start) return SP_OK;
+    const int64_t T = 2048;
+    const int64_t nrows = t->npos[1] - 1;
+    if (nrows >= ((int64_t)1 << 31)) return SP_OK;        // the streaming kernel keeps 32-bit row ids
+    const int64_t nb = ceil_div(t->ncrd[1], T);
+    if (nb == 0) return SP_OK;
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    void *start = mem.get(pad16((size_t)(nb + 1) * 4));
+    void *carry = mem.get(pad16((size_t)nb * 8));
+    if (!start || !carry) { mem.put(start); mem.put(carry); return SP_ERR_ALLOC; }
+    if (t->enc.pw == 32)
+        hipLaunchKernelGGL(rowblocks_kernel<int32_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, nb, T, (int32_t *)start);
+    else
+        hipLaunchKernelGGL(rowblocks_kernel<int64_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, nb, T, (int32_t *)start);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { mem.put(start); mem.put(carry); g_last_hip_error = (int)e; return SP_ERR_HIP; }
+    t->rowblocks.start = start;
+    t->rowblocks.carry = carry;
+    t->rowblocks.nblocks = nb;
+    return SP_OK;
+}
+
+static void release_tensor_arrays(sp_tensor *t)
+{
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    for (int l = 0; l < SP_MAX_RANK; ++l) { mem.put(t->pos[l]); mem.put(t->crd[l]); t->pos[l] = t->crd[l] = nullptr; }
+    mem.put(t->values); t->values = nullptr;
+    mem.put(t->rowblocks.start); t->rowblocks.start = nullptr;
+    mem.put(t->rowblocks.carry); t->rowblocks.carry = nullptr;
+}
+
+extern "C" void sp_tensor_free(sp_tensor *t)
+{
+    if (!t) return;
+    if (t->transposed) sp_tensor_free(t->transposed);
+    release_tensor_arrays(t);
+    delete t;
+}
+
+template <typename PT, typename CT>
+static sp_status launch_emit(const uint64_t *keys, int64_t nnz, uint64_t stride, uint64_t size, const uint32_t *child_excl,
+                             const uint64_t *pin, uint64_t *pout, void *cnt, void *crd, hipStream_t st)
+{
+    hipLaunchKernelGGL((emit_level_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, keys, nnz, stride, size, child_excl,
+                       pin, pout, (PT *)cnt, (CT *)crd);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64_t nnz, const int64_t *const *coords,
+                             const void *values, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx, void *stream,
+                             sp_tensor **out)
+{
+    if (!enc || !shape || !out) return SP_ERR_NULL;
+    *out = nullptr;
+    if ((alloc == nullptr) != (free_ == nullptr)) return SP_ERR_NULL;
+    if (nnz > 0 && (!coords || !values)) return SP_ERR_NULL;
+    if (dt != SP_F32 && dt != SP_F64) return SP_ERR_DTYPE;
+    if (nnz < 0) return SP_ERR_SHAPE;
+    const int rank = enc->rank;
+    for (int d = 0; d < rank; ++d) {
+        if (shape[d] < 0) return SP_ERR_SHAPE;
+        if (nnz > 0 && !coords[d]) return SP_ERR_NULL;
+    }
+    if (nnz >= ((int64_t)1 << 31)) return SP_ERR_TOO_LARGE;
+    hipStream_t st = (hipStream_t)stream;
+
+    sp_tensor *t = new sp_tensor();
+    memset(t, 0, sizeof(*t));
+    t->enc = *enc; t->dtype = dt; t->alloc = alloc; t->free_ = free_; t->ctx = ctx; t->nnz = nnz;
+    // the linearised key and every dense position count must stay below 2^63
+    unsigned __int128 prod = 1;
+    bool zero_dim = false;
+    for (int l = 0; l < rank; ++l) {
+        t->shape[l] = shape[l];
+        t->size[l] = shape[enc->perm[l]];
+        if (t->size[l] == 0) zero_dim = true;
+        prod *= (unsigned __int128)(t->size[l] > 0 ? t->size[l] : 1);
+        if (prod >= ((unsigned __int128)1 << 63)) { delete t; return SP_ERR_TOO_LARGE; }
+    }
+    if (zero_dim && nnz > 0) { delete t; return SP_ERR_COORD_RANGE; }
+    for (int l = 0; l < rank; ++l)
+        if (enc->lt[l] == SP_COMPRESSED && enc->cw == 32 && t->size[l] - 1 > INT32_MAX) { delete t; return SP_ERR_WIDTH; }
+    int key_bits = 0;
+    while (key_bits < 63 && ((unsigned __int128)1 << key_bits) < prod) ++key_bits;
+
+    sp_mem mem{alloc, free_, ctx};
+    sp_status status = SP_OK;
+    {
+        sp_scratch tmp(mem);
+        const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
+        uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
+        uint32_t *idx = (uint32_t *)tmp.get(cnt * 4);
+        uint64_t *parentA = (uint64_t *)tmp.get(cnt * 8);
+        uint64_t *parentB = (uint64_t *)tmp.get(cnt * 8);
+        uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
+        int *flags = (int *)tmp.get(64);
+        auto fail = [&](sp_status s) { status = s; return s; };
+        do {
+            if (!keys || !idx || !parentA || !parentB || !child || !flags) { fail(SP_ERR_ALLOC); break; }
+            if (spmi_fill_zero(flags, 64, st) != SP_OK) { fail(SP_ERR_HIP); break; }
+            if (nnz > 0) {
+                level_args la;
+                memset(&la, 0, sizeof(la));
+                la.rank = rank;
+                for (int l = 0; l < rank; ++l) { la.coord[l] = coords[enc->perm[l]]; la.size[l] = t->size[l]; }
+                hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz, keys, idx, flags);
+                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+                if (fail(spmi_radix_sort_pairs(keys, idx, nnz, key_bits, tmp, st)) != SP_OK) break;
+                hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
+                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+            }
+            int hflags[2] = {0, 0};
+            if (hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, st) != hipSuccess ||
+                hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+            if (hflags[0]) { fail(SP_ERR_COORD_RANGE); break; }
+            if (hflags[1]) { fail(SP_ERR_DUPLICATE); break; }
+
+            // level sweep
+            const uint64_t *pin = nullptr;      // nullptr = every entry has parent 0
+            uint64_t *pbuf[2] = {parentA, parentB};
+            int which = 0;
+            int64_t P = 1;
+            for (int l = 0; l < rank && status == SP_OK; ++l) {
+                uint64_t stride = 1;
+                for (int k = l + 1; k < rank; ++k) stride *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
+                const uint64_t size = (uint64_t)(t->size[l] > 0 ? t->size[l] : 1);
+                uint64_t *pout = pbuf[which];
+                if (enc->lt[l] == SP_DENSE) {
+                    if (nnz > 0) {
+                        hipLaunchKernelGGL(dense_level_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz,
+                                           stride, size, pin, pout);
+                        if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+                    }
+                    P *= t->size[l];
+                } else {
+                    int64_t nchild = nnz;
+                    const uint32_t *child_excl = nullptr;
+                    if (l != rank - 1 && nnz > 0) {
+                        hipLaunchKernelGGL(mark_children_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, stride, child);
+                        if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+                        if (fail(spmi_exclusive_scan(child, nnz, 32, tmp, st)) != SP_OK) break;
+                        // children = exclusive[nnz-1] + mark[nnz-1]; the last mark is recomputed from the two last keys
+                        uint32_t last_excl = 0;
+                        uint64_t lastk[2] = {0, 0};
+                        if (hipMemcpyAsync(&last_excl, child + (nnz - 1), 4, hipMemcpyDeviceToHost, st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+                        const int64_t from = nnz >= 2 ? nnz - 2 : 0;
+                        if (hipMemcpyAsync(lastk, keys + from, (size_t)(nnz - from) * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+                            hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+                        const bool last_mark = nnz == 1 || (lastk[0] / stride != lastk[1] / stride);
+                        nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
+                        child_excl = child;
+                    }
+                    if (enc->pw == 32 && nchild > INT32_MAX) { fail(SP_ERR_WIDTH); break; }
+                    const size_t pbytes = pad16((size_t)(P + 1) * (enc->pw / 8));
+                    const size_t cbytes = pad16((size_t)(nchild > 0 ? nchild : 1) * (enc->cw / 8));
+                    t->pos[l] = mem.get(pbytes);
+                    t->crd[l] = mem.get(cbytes);
+                    t->npos[l] = P + 1;
+                    t->ncrd[l] = nchild;
+                    if (!t->pos[l] || !t->crd[l]) { fail(SP_ERR_ALLOC); break; }
+                    if (spmi_fill_zero(t->pos[l], pbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
+                    if (nnz > 0) {
+                        sp_status s;
+                        if (enc->pw == 32 && enc->cw == 32) s = launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
+                        else if (enc->pw == 32) s = launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
+                        else if (enc->cw == 32) s = launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
+                        else s = launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
+                        if (fail(s) != SP_OK) break;
+                    }
+                    if (fail(spmi_exclusive_scan(t->pos[l], P + 1, enc->pw, tmp, st)) != SP_OK) break;
+                    P = nchild;
+                }
+                if (nnz > 0) { pin = pout; which ^= 1; }
+            }
+            if (status != SP_OK) break;
+
+            // values: zero padding only where a dense level sits below a compressed one
+            const size_t vsz = dt == SP_F64 ? 8 : 4;
+            const size_t vbytes = pad16((size_t)(P > 0 ? P : 1) * vsz);
+            t->values = mem.get(vbytes);
+            t->nvalues = P;
+            if (!t->values) { fail(SP_ERR_ALLOC); break; }
+            if (P != nnz && spmi_fill_zero(t->values, vbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
+            if (nnz > 0) {
+                const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : pin;
+                if (dt == SP_F64)
+                    hipLaunchKernelGGL(gather_values_kernel<double>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const double *)values,
+                                       (const uint32_t *)idx, position, nnz, (double *)t->values);
+                else
+                    hipLaunchKernelGGL(gather_values_kernel<float>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const float *)values,
+                                       (const uint32_t *)idx, position, nnz, (float *)t->values);
+                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+            }
+            // longest innermost segment (kernel choice) and the row blocks of the streaming kernels
+            if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
+                unsigned long long *mx = (unsigned long long *)(flags + 4);
+                const int64_t nseg = t->npos[rank - 1] - 1;
+                if (enc->pw == 32)
+                    hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(blocks_for(nseg)), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
+                else
+                    hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(blocks_for(nseg)), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
+                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+                unsigned long long hmx = 0;
+                if (hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+                t->max_segment = (int64_t)hmx;
+            }
+            if (fail(spmi_build_rowblocks(t, st)) != SP_OK) break;
+            if (hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+        } while (0);
+        if (status == SP_ERR_HIP && g_last_hip_error == 0) g_last_hip_error = (int)hipGetLastError();
+        if (status != SP_OK) (void)hipStreamSynchronize(st);   // temporaries may still be in use by queued kernels
+    }
+    if (status != SP_OK) { release_tensor_arrays(t); delete t; return status; }
+    *out = t;
+    return SP_OK;
+}
+
+extern "C" sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream)
+{
+    if (!t || !coords || (!values && t->nvalues > 0)) return SP_ERR_NULL;
+    const int rank = t->enc.rank;
+    for (int d = 0; d < rank; ++d) if (!coords[d] && t->nvalues > 0) return SP_ERR_NULL;
+    if (t->nvalues == 0) return SP_OK;
+    hipStream_t st = (hipStream_t)stream;
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    // small descriptor tables for the kernel: level types + ordering, array pointers, pos lengths, outputs
+    struct tables {
+        int lt_perm[2 * SP_MAX_RANK];
+        const void *pos[SP_MAX_RANK];
+        const void *crd[SP_MAX_RANK];
+        int64_t npos[SP_MAX_RANK];
+        int64_t *out[SP_MAX_RANK];
+    } h;
+    memset(&h, 0, sizeof(h));
+    level_args la;
+    memset(&la, 0, sizeof(la));
+    la.rank = rank;
+    for (int l = 0; l < rank; ++l) {
+        h.lt_perm[l] = t->enc.lt[l];
+        h.lt_perm[SP_MAX_RANK + l] = t->enc.perm[l];
+        h.pos[l] = t->pos[l]; h.crd[l] = t->crd[l]; h.npos[l] = t->npos[l];
+        h.out[l] = coords[l];
+        la.size[l] = t->size[l] > 0 ? t->size[l] : 1;
+    }
+    tables *d = (tables *)mem.get(sizeof(tables));
+    if (!d) return SP_ERR_ALLOC;
+    sp_status s = SP_OK;
+    do {
+        if (hipMemcpyAsync(d, &h, sizeof(h), hipMemcpyHostToDevice, st) != hipSuccess) { s = SP_ERR_HIP; break; }
+        const unsigned nb = blocks_for(t->nvalues);
+#define SPMI_UNPACK(PT, CT)                                                                                                   \
+    hipLaunchKernelGGL((unpack_kernel<PT, CT>), dim3(nb), dim3(kThreads), 0, st, rank, la, (const int *)d->lt_perm,            \
+                       (const void *const *)d->pos, (const void *const *)d->crd, (const int64_t *)d->npos, t->nvalues,        \
+                       (int64_t *const *)d->out)
+        if (t->enc.pw == 32 && t->enc.cw == 32) SPMI_UNPACK(int32_t, int32_t);
+        else if (t->enc.pw == 32) SPMI_UNPACK(int32_t, int64_t);
+        else if (t->enc.cw == 32) SPMI_UNPACK(int64_t, int32_t);
+        else SPMI_UNPACK(int64_t, int64_t);
+#undef SPMI_UNPACK
+        if (hipGetLastError() != hipSuccess) { s = SP_ERR_HIP; break; }
+        const size_t vsz = t->dtype == SP_F64 ? 8 : 4;
+        if (hipMemcpyAsync(values, t->values, (size_t)t->nvalues * vsz, hipMemcpyDeviceToDevice, st) != hipSuccess) { s = SP_ERR_HIP; break; }
+    } while (0);
+    // the descriptor table is read by the queued kernel: wait before handing it back
+    if (hipStreamSynchronize(st) != hipSuccess && s == SP_OK) s = SP_ERR_HIP;
+    mem.put(d);
+    return s;
+}

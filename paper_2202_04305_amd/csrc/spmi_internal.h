@@ -1,0 +1,101 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <type_traits>
+#include <vector>
+#include "spmi.h"
+
+struct sp_encoding {
+    int rank;
+    int lt[SP_MAX_RANK];
+    int perm[SP_MAX_RANK];   // perm[l] = dimension stored at level l
+    int pw, cw;              // resolved widths: 32 or 64
+};
+
+// Row blocks of the streaming SpMV: block b covers rows [rowblk[b], rowblk[b+1]) of the
+// outer level; built once at pack time from pos of the innermost level.
+struct sp_rowblocks {
+    void *start = nullptr;   // DEVICE int32[nblocks + 1]
+    void *carry = nullptr;   // DEVICE value-typed[nblocks]: partial sums of rows that cross block boundaries
+    int64_t nblocks = 0;
+};
+
+struct sp_tensor {
+    sp_encoding enc;
+    int dtype;
+    int64_t shape[SP_MAX_RANK];
+    int64_t size[SP_MAX_RANK];       // by level
+    void *pos[SP_MAX_RANK];          // DEVICE, nullptr for dense levels
+    int64_t npos[SP_MAX_RANK];
+    void *crd[SP_MAX_RANK];
+    int64_t ncrd[SP_MAX_RANK];
+    void *values;
+    int64_t nvalues;
+    int64_t nnz;
+    int64_t max_segment;
+    sp_alloc_fn alloc;
+    sp_free_fn free_;
+    void *ctx;
+    // derived, built lazily by sp_matmul or eagerly by sp_pack
+    sp_rowblocks rowblocks;
+    sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
+    int tune_spmv, tune_csc, tune_spmm;
+};
+
+extern thread_local int g_last_hip_error;
+
+#define SP_HIP(call)                                            \
+    do {                                                        \
+        hipError_t e__ = (call);                                \
+        if (e__ != hipSuccess) {                                \
+            g_last_hip_error = (int)e__;                        \
+            return SP_ERR_HIP;                                  \
+        }                                                       \
+    } while (0)
+
+#define SP_TRY(call)                                            \
+    do {                                                        \
+        sp_status s__ = (call);                                 \
+        if (s__ != SP_OK) return s__;                           \
+    } while (0)
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Device memory through the caller's allocator (or hipMalloc when none was given).
+struct sp_mem {
+    sp_alloc_fn alloc; sp_free_fn free_; void *ctx;
+    void *get(size_t bytes) const;
+    void put(void *p) const;
+};
+
+// A scope that frees its temporaries on exit.
+struct sp_scratch {
+    const sp_mem &mem;
+    std::vector<void *> ptrs;
+    explicit sp_scratch(const sp_mem &m) : mem(m) {}
+    ~sp_scratch() { for (void *p : ptrs) mem.put(p); }
+    void *get(size_t bytes) {
+        void *p = mem.get(bytes ? bytes : 16);
+        if (p) ptrs.push_back(p);
+        return p;
+    }
+};
+
+// ---- pack.hip ----------------------------------------------------------------------------
+// In-place exclusive prefix sum of n elements of width `bits` (32 or 64); data[n-1] afterwards
+// holds the sum of the first n-1 inputs.
+sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, hipStream_t st);
+// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits; results end in keys/vals.
+sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int key_bits,
+                                sp_scratch &tmp, hipStream_t st);
+sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
+sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
+
+// ---- matmul.hip --------------------------------------------------------------------------
+sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
+                               void *C, int64_t ldc, int accumulate, hipStream_t st);
+sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
+                                       void *C, int64_t ldc, int accumulate, hipStream_t st);

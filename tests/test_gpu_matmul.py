@@ -1,0 +1,208 @@
+"""GPU sparse x dense products against the CPU checker, element by element, through the C ABI.
+
+Tolerance (stated with the target): |C_gpu - C_ref| <= 1e-12 * sum|a*b| for f64, 1e-5 * sum|a*b| for f32;
+exact-integer inputs must match bit for bit whatever the summation order.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_04305_amd as sp
+from gen import workloads as W, prng
+from gpu_util import say, dev, gpu_pack, assert_product_close, DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def run(A, w, B, accumulate=False, C0=None, vals=None):
+    m = w.shape[0]
+    Bn = np.ascontiguousarray(B, dtype=w.dtype).reshape(w.shape[1], -1)
+    N = Bn.shape[1]
+    if C0 is None:
+        C = torch.full((m, N), float("nan"), dtype=A.dtype, device=DEV)      # overwrite mode must not read C
+    else:
+        C = dev(np.ascontiguousarray(C0, dtype=w.dtype).reshape(m, N))
+    sp.sp_matmul(A, dev(Bn), C, accumulate=accumulate)
+    ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals if vals is None else vals, Bn, accumulate, C0)
+    torch.cuda.synchronize()
+    return C, ref, mag
+
+
+SPMV_CASES = [
+    ("cfg1 full", lambda: W.cfg1_uniform_csr()),
+    ("cfg2 scaled, rows cross several blocks", lambda: W.cfg2_powerlaw_csr(40000, 30000, mean=24.0, cap=9000)),
+    ("long rows only", lambda: W.cfg2_powerlaw_csr(64, 20000, mean=6000.0, sigma=0.3, cap=15000)),
+    ("ragged tail, one block and a bit", lambda: W.cfg2_powerlaw_csr(300, 500, mean=8.0, cap=200)),
+    ("many empty rows as CSR", lambda: W.cfg4_hypersparse_dcsr(1 << 17, 1 << 17, frac=0.02, per_row=40)),
+]
+
+
+@pytest.mark.parametrize("name,maker", SPMV_CASES)
+@pytest.mark.parametrize("kernel", [0, 1, 2])
+@pytest.mark.parametrize("widths", [(32, 32), (64, 64)])
+def test_csr_spmv(name, maker, kernel, widths):
+    w = maker()
+    say("case spmv", name, "kernel", kernel, widths, w.stats)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, *widths)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    x = w.dense_operand(1)
+    y, ref, mag = run(A, w, x)
+    assert_product_close(y, ref, mag, w.dtype, name)
+    y0 = prng.uniform_pm1(5, 5, w.shape[0])
+    y, ref, mag = run(A, w, x, accumulate=True, C0=y0)
+    assert_product_close(y, ref, mag, w.dtype, name + " accumulate")
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_exact_integer_inputs_bit_exact(kernel):
+    w = W.cfg2_powerlaw_csr(30000, 30000, mean=20.0, cap=7000)
+    vals = w.exact_values()
+    say("case exact ints kernel", kernel)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    x = w.dense_operand(1, exact=True)
+    y, ref, mag = run(A, w, x, vals=vals)
+    assert np.array_equal(y.cpu().numpy(), ref)
+    # all-ones: y[i] = row length = pos[i+1] - pos[i]
+    ones = np.ones(w.nnz)
+    A1 = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], ones)
+    sp.sp_tensor_tune(A1, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A1, dev(np.ones(w.shape[1])), y)
+    pos = sp.sp_pos(A1, 1).cpu().numpy()
+    assert np.array_equal(y.cpu().numpy(), np.diff(pos).astype(np.float64))
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_spmv_is_reproducible_run_to_run(kernel):
+    w = W.cfg2_powerlaw_csr(30000, 30000, mean=20.0, cap=7000)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    x = dev(w.dense_operand(1))
+    ys = []
+    for _ in range(3):
+        y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, x, y)
+        ys.append(y.cpu().numpy())
+    assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[0], ys[2])
+
+
+@pytest.mark.parametrize("N", [2, 3, 8, 32, 64, 70])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_csr_spmm(N, dtype):
+    w = W.cfg3_powerlaw_csr_spmm(6000, 5000, N=N, cap=2500)
+    w.vals = w.vals.astype(dtype)
+    w.dtype = dtype
+    say("case spmm N", N, dtype.__name__)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    B = w.dense_operand(N)
+    C, ref, mag = run(A, w, B)
+    assert_product_close(C, ref, mag, dtype, "spmm")
+    C0 = prng.uniform_pm1(5, 6, w.shape[0] * N).reshape(-1, N)
+    C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
+    assert_product_close(C, ref, mag, dtype, "spmm accumulate")
+
+
+def test_leading_dimensions():
+    w = W.cfg3_powerlaw_csr_spmm(3000, 2000, N=5, cap=500)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    B = w.dense_operand(5)
+    Bp = torch.full((2000, 9), float("nan"), dtype=torch.float64, device=DEV)
+    Bp[:, :5] = dev(B)
+    Cp = torch.full((3000, 7), -7.0, dtype=torch.float64, device=DEV)
+    say("case leading dimensions")
+    sp.sp_matmul(A, Bp, Cp, N=5, ldb=9, ldc=7)
+    ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B)
+    assert_product_close(Cp[:, :5].contiguous(), ref, mag, np.float64, "ld")
+    assert torch.all(Cp[:, 5:] == -7.0)
+    # SpMV on a strided x and y
+    xs = torch.zeros((2000, 3), dtype=torch.float64, device=DEV)
+    xs[:, 0] = dev(B[:, 0].copy())
+    ys = torch.full((3000, 2), -7.0, dtype=torch.float64, device=DEV)
+    for kernel in (1, 2):
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+        sp.sp_matmul(A, xs, ys, N=1, ldb=3, ldc=2)
+        ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B[:, :1].copy())
+        assert_product_close(ys[:, 0].contiguous(), ref, mag, np.float64, "strided spmv")
+        assert torch.all(ys[:, 1] == -7.0)
+
+
+@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("N", [1, 4])
+def test_dcsr(kernel, N):
+    w = W.cfg4_hypersparse_dcsr(1 << 18, 1 << 18)
+    say("case dcsr kernel", kernel, "N", N, w.stats)
+    A = gpu_pack((1, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    B = w.dense_operand(N)
+    C, ref, mag = run(A, w, B)                       # overwrite: rows that are not stored must come out as zero
+    assert_product_close(C, ref, mag, w.dtype, "dcsr")
+    assert torch.all(C[torch.from_numpy(mag[:, 0] == 0).to(DEV)] == 0)
+    C0 = prng.uniform_pm1(5, 7, w.shape[0] * N).reshape(-1, N)
+    C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
+    assert_product_close(C, ref, mag, w.dtype, "dcsr accumulate")
+    untouched = torch.from_numpy(np.bincount(w.rows, minlength=w.shape[0]) == 0).to(DEV)
+    assert torch.equal(C[untouched], dev(C0)[untouched])     # accumulate touches stored rows only
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("lt", [(0, 1), (1, 1)])
+@pytest.mark.parametrize("N", [1, 32, 40])
+def test_column_major(mode, lt, N):
+    w = W.cfg5_zipf_csc_spmm(30000, 30000, N=N, cap=6000)
+    say("case csc mode", mode, lt, "N", N, w.stats)
+    A = gpu_pack(lt, (1, 0), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_CSC_MODE, mode)
+    B = w.dense_operand(N)
+    C, ref, mag = run(A, w, B)
+    assert_product_close(C, ref, mag, w.dtype, "csc")
+    C0 = prng.uniform_pm1(5, 8, w.shape[0] * N, dtype=np.float32).reshape(-1, N)
+    C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
+    assert_product_close(C, ref, mag, w.dtype, "csc accumulate")
+    # exact integers: the atomic order cannot matter
+    vals = w.exact_values()
+    A2 = gpu_pack(lt, (1, 0), w.shape, [w.rows, w.cols], vals)
+    sp.sp_tensor_tune(A2, sp.SP_TUNE_CSC_MODE, mode)
+    Bx = w.dense_operand(N, exact=True)
+    C, ref, mag = run(A2, w, Bx, vals=vals)
+    assert np.array_equal(C.cpu().numpy(), ref)
+
+
+def test_result_is_independent_of_the_encoding():
+    """The paper's own check (Section 5.2): the same COO under every supported annotation gives the same C."""
+    w = W.cfg2_powerlaw_csr(5000, 4000, cap=1500)
+    B = w.dense_operand(6)
+    ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B)
+    for lt in [(0, 1), (1, 1)]:
+        for order in [(0, 1), (1, 0)]:
+            for pw, cw in [(32, 32), (64, 32), (32, 64), (0, 0)]:
+                say("case encoding", lt, order, pw, cw)
+                A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
+                C = torch.empty((w.shape[0], 6), dtype=torch.float64, device=DEV)
+                sp.sp_matmul(A, dev(B), C)
+                assert_product_close(C, ref, mag, np.float64, str((lt, order, pw, cw)))
+    for lt in [(1, 0), (0, 0)]:
+        A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], w.vals)
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_matmul(A, dev(B), torch.empty((w.shape[0], 6), dtype=torch.float64, device=DEV))
+        assert e.value.code == oracle.ERR_UNSUPPORTED
+
+
+def test_degenerate_products():
+    z = np.zeros(0, dtype=np.int64)
+    for lt, order in [((0, 1), (0, 1)), ((1, 1), (0, 1)), ((0, 1), (1, 0))]:
+        say("case nnz=0", lt, order)
+        A = gpu_pack(lt, order, (50, 60), [z, z], np.zeros(0))
+        C = torch.full((50, 3), float("nan"), dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, torch.ones((60, 3), dtype=torch.float64, device=DEV), C)
+        assert torch.all(C == 0)
+    idx = np.arange(100, dtype=np.int64)
+    A = gpu_pack((0, 1), None, (100, 100), [idx, idx], np.ones(100))      # identity: C = B exactly
+    B = dev(prng.uniform_pm1(1, 1, 700).reshape(100, 7))
+    C = torch.empty((100, 7), dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, B, C)
+    assert torch.equal(C, B)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_matmul(A, B, C, N=7, ldb=3, ldc=7)
+    assert e.value.code == oracle.ERR_SHAPE

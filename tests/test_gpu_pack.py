@@ -1,0 +1,142 @@
+"""GPU storage builder against the CPU checker: every pos / crd / values array bit-exact (through the C ABI)."""
+import glob
+import itertools
+import json
+import os
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_04305_amd as sp
+from gen import workloads as W, prng
+from gpu_util import say, dev, gpu_pack, assert_storage_equal
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+LT = {"dense": 0, "compressed": 1}
+
+
+@pytest.mark.parametrize("name", sorted(os.path.basename(p) for p in glob.glob(os.path.join(GOLDEN, "*.json"))))
+def test_paper_worked_examples(name):
+    say("case", name)
+    g = json.load(open(os.path.join(GOLDEN, name)))
+    if "dense" in g:
+        d = np.asarray(g["dense"], dtype=np.float64)
+        coords, vals = [np.nonzero(d)[0].astype(np.int64)], d[np.nonzero(d)[0]]
+    else:
+        coo = np.asarray(g["coo"], dtype=np.int64).reshape(len(g["values"]), len(g["shape"]))
+        coords, vals = [coo[:, k].copy() for k in range(len(g["shape"]))], np.asarray(g["values"], dtype=np.float64)
+    p = prng.permutation(3, 1, len(vals))
+    A = gpu_pack([LT[x] for x in g["level_types"]], g["dim_ordering"], g["shape"], [c[p] for c in coords], vals[p], 64, 64)
+    for l in range(len(g["shape"])):
+        if g["pos"][l] is not None:
+            assert sp.sp_pos(A, l).cpu().tolist() == g["pos"][l]
+            assert sp.sp_crd(A, l).cpu().tolist() == g["crd"][l]
+    assert sp.sp_values(A).cpu().tolist() == [float(v) for v in g["values_out"]]
+
+
+@pytest.mark.parametrize("lt", list(itertools.product([0, 1], repeat=2)))
+@pytest.mark.parametrize("order", [(0, 1), (1, 0)])
+def test_rank2_every_encoding_and_width(lt, order):
+    w = W.cfg2_powerlaw_csr(700, 900, cap=300)
+    for pw, cw in [(32, 32), (64, 32), (32, 64), (0, 0)]:
+        say("case", lt, order, pw, cw)
+        ref = oracle.pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
+        A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
+        assert_storage_equal(A, ref)
+        info = sp.sp_tensor_info(A)
+        assert info.nnz == w.nnz and info.nvalues == len(ref.values)
+
+
+@pytest.mark.parametrize("order", [(0, 1, 2), (2, 0, 1), (1, 2, 0)])
+def test_rank3(order):
+    rng = np.random.default_rng(3)
+    shape = (13, 7, 29)
+    lin = rng.choice(int(np.prod(shape)), size=400, replace=False)
+    coords = list(np.unravel_index(lin, shape))
+    vals = rng.standard_normal(400)
+    for lt in itertools.product([0, 1], repeat=3):
+        say("case rank3", order, lt)
+        ref = oracle.pack(lt, order, shape, coords, vals, 32, 32)
+        A = gpu_pack(lt, order, shape, coords, vals, 32, 32)
+        assert_storage_equal(A, ref)
+
+
+@pytest.mark.parametrize("maker,name", [
+    (lambda: W.cfg1_uniform_csr(), "cfg1 full"),
+    (lambda: W.cfg2_powerlaw_csr(60000, 50000, cap=9000), "cfg2 scaled"),
+    (lambda: W.cfg4_hypersparse_dcsr(1 << 18, 1 << 18), "cfg4 scaled"),
+    (lambda: W.cfg5_zipf_csc_spmm(40000, 40000, cap=6000), "cfg5 scaled"),
+])
+def test_workload_shapes(maker, name):
+    w = maker()
+    say("case", name, w.stats)
+    ref = oracle.pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    assert_storage_equal(A, ref)
+    assert sp.sp_tensor_info(A).maxSegment == w.stats["max_len"]
+    # back to the coordinate scheme: same entries, level order
+    coords, vals = sp.sp_unpack(A)
+    (r, c), v = ref.unpack()
+    assert np.array_equal(coords[0].cpu().numpy(), r) and np.array_equal(coords[1].cpu().numpy(), c)
+    assert np.array_equal(vals.cpu().numpy().astype(np.float64), v)
+
+
+def test_unpack_with_padding_zeros():
+    w = W.uniform_random(50, 30, 200)
+    for lt, order in [((1, 0), (0, 1)), ((0, 0), (1, 0)), ((1, 0), (1, 0))]:
+        say("case unpack", lt, order)
+        A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals)
+        ref = oracle.pack(lt, order, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+        coords, vals = sp.sp_unpack(A)
+        (r, c), v = ref.unpack()
+        assert np.array_equal(coords[0].cpu().numpy(), r) and np.array_equal(coords[1].cpu().numpy(), c)
+        assert np.array_equal(vals.cpu().numpy(), v)
+
+
+def test_empty_tiny_and_explicit_zero():
+    for lt in [(0, 1), (1, 1), (1, 0), (0, 0)]:
+        say("case empty", lt)
+        z = np.zeros(0, dtype=np.int64)
+        ref = oracle.pack(lt, None, (5, 7), [z, z], np.zeros(0), 32, 32)
+        A = gpu_pack(lt, None, (5, 7), [z, z], np.zeros(0), 32, 32)
+        assert_storage_equal(A, ref)
+    ref = oracle.pack((0, 1), None, (2, 3), [np.array([0, 1]), np.array([2, 1])], np.array([0.0, 4.0]), 32, 32)
+    A = gpu_pack((0, 1), None, (2, 3), [np.array([0, 1]), np.array([2, 1])], np.array([0.0, 4.0]), 32, 32)
+    assert_storage_equal(A, ref)
+    one = gpu_pack((1, 1), (1, 0), (9, 9), [np.array([4]), np.array([6])], np.array([2.5], dtype=np.float32))
+    assert_storage_equal(one, oracle.pack((1, 1), (1, 0), (9, 9), [np.array([4]), np.array([6])], np.array([2.5], dtype=np.float32), 32, 32))
+
+
+def test_input_errors_match_the_checker():
+    w = W.uniform_random(100, 100, 3000)
+    rows, cols = w.rows.copy(), w.cols.copy()
+    rows[1234], cols[1234] = rows[77], cols[77]
+    say("case duplicate")
+    with pytest.raises(sp.SpError) as e:
+        gpu_pack((0, 1), None, w.shape, [rows, cols], w.vals)
+    with pytest.raises(oracle.OracleError) as eo:
+        oracle.pack((0, 1), None, w.shape, [rows, cols], w.vals)
+    assert e.value.code == eo.value.code == oracle.ERR_DUPLICATE
+    say("case range")
+    cols = w.cols.copy()
+    cols[5] = 100
+    with pytest.raises(sp.SpError) as e:
+        gpu_pack((0, 1), None, w.shape, [w.rows, cols], w.vals)
+    assert e.value.code == oracle.ERR_COORD_RANGE
+    rows = w.rows.copy()
+    rows[9] = -1
+    with pytest.raises(sp.SpError) as e:
+        gpu_pack((1, 1), (1, 0), w.shape, [rows, w.cols], w.vals)
+    assert e.value.code == oracle.ERR_COORD_RANGE
+    say("case width")
+    with pytest.raises(sp.SpError) as e:
+        gpu_pack((0, 1), None, (4, 1 << 33), [np.array([0]), np.array([5])], np.array([1.0]), 32, 32)
+    assert e.value.code == oracle.ERR_WIDTH
+    with pytest.raises(sp.SpError) as e:
+        gpu_pack((0, 0, 0), None, (1 << 30,) * 3, [np.array([0])] * 3, np.array([1.0]))
+    assert e.value.code == oracle.ERR_TOO_LARGE
+    # the library must still work after errors
+    A = gpu_pack((0, 1), None, w.shape, [w.rows, w.cols], w.vals)
+    assert_storage_equal(A, oracle.pack((0, 1), None, w.shape, [w.rows, w.cols], w.vals, 32, 32))
