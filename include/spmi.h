@@ -121,8 +121,15 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *   SP_TUNE_SPMV_KERNEL: 0 = automatic, 1 = lanes-per-row, 2 = row-block streaming
  *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
-enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3 };
+enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4 };
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);
+
+/* Kernel timing for measurements.  After sp_tensor_tune(t, SP_TUNE_PROFILE, 1) every sp_matmul on
+ * t brackets its main kernel (the one that streams A; not the zero fill, not the fix-up) with a
+ * pair of HIP events on the caller's stream.  sp_profile_read waits for those events, returns
+ * the summed kernel time in milliseconds and the number of launches, and clears the record.
+ * Profiling costs two event records per call; leave it off in production. */
+sp_status sp_profile_read(sp_tensor *t, double *ms_total /* HOST */, int64_t *launches /* HOST */);
 
 /* dst[i] = src[i] for `bytes` bytes (multiple of 16), a plain streaming copy kernel: the
  * yardstick the benchmark scales its bandwidth figures and hardware counters by. */

@@ -8,7 +8,7 @@ from . import build as _build
 
 SP_DENSE, SP_COMPRESSED = 0, 1
 SP_F32, SP_F64 = 0, 1
-SP_TUNE_SPMV_KERNEL, SP_TUNE_CSC_MODE, SP_TUNE_SPMM_KERNEL = 1, 2, 3
+SP_TUNE_SPMV_KERNEL, SP_TUNE_CSC_MODE, SP_TUNE_SPMM_KERNEL, SP_TUNE_PROFILE = 1, 2, 3, 4
 SP_MAX_RANK = 8
 
 STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_ERR_ORDERING", "SP_ERR_WIDTH",
@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_tensor_info", "sp_tensor_tune", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -72,6 +72,8 @@ def load_library():
     L.sp_tensor_info.argtypes = [vp, ctypes.POINTER(SpInfo)]
     L.sp_tensor_tune.restype = ci
     L.sp_tensor_tune.argtypes = [vp, ci, i64]
+    L.sp_profile_read.restype = ci
+    L.sp_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     L.sp_stream_copy.restype = ci
     L.sp_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.sp_status_str.restype = ctypes.c_char_p
@@ -239,6 +241,13 @@ def sp_unpack(A):
 
 def sp_tensor_tune(A, key, value):
     _check(load_library().sp_tensor_tune(A._h, key, value), "in sp_tensor_tune")
+
+
+def sp_profile_read(A):
+    """(total milliseconds, launches) of the main kernels recorded since the last read."""
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    _check(load_library().sp_profile_read(A._h, ctypes.byref(ms), ctypes.byref(n)), "in sp_profile_read")
+    return ms.value, n.value
 
 
 def sp_stream_copy(dst, src):

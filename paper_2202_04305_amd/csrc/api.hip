@@ -121,12 +121,38 @@ extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
         if (value < 0 || value > 2) return SP_ERR_UNSUPPORTED;
         t->tune_csc = (int)value;
         return SP_OK;
+    case SP_TUNE_PROFILE:
+        if (value != 0 && value != 1) return SP_ERR_UNSUPPORTED;
+        if (value && !t->prof_events) t->prof_events = new std::vector<hipEvent_t>();
+        t->profile = (int)value;
+        if (t->transposed) return sp_tensor_tune(t->transposed, key, value);
+        return SP_OK;
     case SP_TUNE_SPMM_KERNEL:
         if (value != 0) return SP_ERR_UNSUPPORTED;
         t->tune_spmm = (int)value;
         return SP_OK;
     }
     return SP_ERR_UNSUPPORTED;
+}
+
+extern "C" sp_status sp_profile_read(sp_tensor *t, double *ms_total, int64_t *launches)
+{
+    if (!t || !ms_total || !launches) return SP_ERR_NULL;
+    *ms_total = 0.0;
+    *launches = 0;
+    sp_tensor *src = (t->transposed && t->transposed->prof_events && !t->transposed->prof_events->empty()) ? t->transposed : t;
+    if (!src->prof_events) return SP_OK;
+    std::vector<hipEvent_t> &ev = *src->prof_events;
+    sp_status s = SP_OK;
+    for (size_t i = 0; i + 1 < ev.size(); i += 2) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ev[i + 1]) != hipSuccess || hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) s = SP_ERR_HIP;
+        else { *ms_total += (double)ms; *launches += 1; }
+        (void)hipEventDestroy(ev[i]);
+        (void)hipEventDestroy(ev[i + 1]);
+    }
+    ev.clear();
+    return s;
 }
 
 // Row-major copy of a column-major tensor, through the coordinate scheme (the paper's route for
@@ -153,6 +179,7 @@ static sp_status build_transposed(sp_tensor *A, hipStream_t st)
     }
     if (s != SP_OK) return s;
     T->tune_spmv = A->tune_spmv;
+    if (A->profile) (void)sp_tensor_tune(T, SP_TUNE_PROFILE, 1);
     A->transposed = T;
     return SP_OK;
 }

@@ -245,8 +245,11 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
         if (kernel == 2 && !A->rowblocks.start) return SP_ERR_UNSUPPORTED;
         if (kernel == 2) {
             const int64_t nb = A->rowblocks.nblocks;
+            {
+            sp_prof_scope prof(A, st);
             hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,
                                (const int32_t *)A->rowblocks.start, nrows, nnz, B, ldb, C, ldc, (VT *)A->rowblocks.carry, accumulate);
+            }
             SP_HIP(hipGetLastError());
             if (nb > 1) {
                 hipLaunchKernelGGL((spmv_stream_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads)), dim3(kThreads), 0, st, pos,
@@ -256,6 +259,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             return SP_OK;
         }
         const double avg = (double)nnz / (double)nrows;
+        sp_prof_scope prof(A, st);
 #define SPMI_ROWS(G)                                                                                                          \
     hipLaunchKernelGGL((spmv_rows_kernel<PT, CT, VT, G>), dim3(grid_for(nrows * G, kThreads)), dim3(kThreads), 0, st, pos, crd, \
                        val, rowid, nrows, B, ldb, C, ldc, accumulate)
@@ -269,6 +273,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
         SP_HIP(hipGetLastError());
         return SP_OK;
     }
+    sp_prof_scope prof(A, st);
 #define SPMI_SPMM(CG)                                                                                                         \
     hipLaunchKernelGGL((spmm_rows_kernel<PT, CT, VT, CG>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, crd, \
                        val, rowid, nrows, B, N, ldb, C, ldc, accumulate)
@@ -292,6 +297,7 @@ sp_status scatter_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT 
     const int64_t ncols = A->npos[1] - 1;
     if (!accumulate) SP_TRY((zero_c<PT, CT, VT>(C, A->shape[0], N, ldc, st)));
     if (ncols == 0) return SP_OK;
+    sp_prof_scope prof(A, st);
 #define SPMI_SCAT(CG)                                                                                                         \
     hipLaunchKernelGGL((spmm_scatter_kernel<PT, CT, VT, CG>), dim3(grid_for(ncols, kThreads / 64)), dim3(kThreads), 0, st, pos, \
                        crd, val, colid, ncols, B, N, ldb, C, ldc)

@@ -422,6 +422,10 @@ extern "C" void sp_tensor_free(sp_tensor *t)
     if (!t) return;
     if (t->transposed) sp_tensor_free(t->transposed);
     release_tensor_arrays(t);
+    if (t->prof_events) {
+        for (hipEvent_t e : *t->prof_events) (void)hipEventDestroy(e);
+        delete t->prof_events;
+    }
     delete t;
 }
 

@@ -43,6 +43,8 @@ struct sp_tensor {
     sp_rowblocks rowblocks;
     sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
     int tune_spmv, tune_csc, tune_spmm;
+    int profile;
+    std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
 };
 
 extern thread_local int g_last_hip_error;
@@ -61,6 +63,21 @@ extern thread_local int g_last_hip_error;
         sp_status s__ = (call);                                 \
         if (s__ != SP_OK) return s__;                           \
     } while (0)
+
+// Brackets the main kernel of a product with events when profiling is on.
+struct sp_prof_scope {
+    const sp_tensor *t; hipStream_t st; hipEvent_t stop = nullptr;
+    sp_prof_scope(const sp_tensor *t_, hipStream_t st_) : t(t_), st(st_) {
+        if (!t->profile || !t->prof_events) return;
+        hipEvent_t a = nullptr;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(a); stop = nullptr; return; }
+        (void)hipEventRecord(a, st);
+        t->prof_events->push_back(a);
+        t->prof_events->push_back(stop);
+    }
+    ~sp_prof_scope() { if (stop) (void)hipEventRecord(stop, st); }
+};
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
