@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--copies", type=int, default=6, help="independent copies of A, x, y rotated through (cold regime)")
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
-    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 lanes-per-row, 2 streaming")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
     ap.add_argument("--small", action="store_true", help="1/16-size matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     args = ap.parse_args()
@@ -150,9 +150,9 @@ def main():
                "sample": "the whole workload (%d stored entries, one y = A.x), median of 3, %.3f s per product" % (nnz, cpu_s),
                "gflops": flops / cpu_s / 1e9}
 
-    kernel_name = {0: "auto", 1: "spmv_rows_kernel", 2: "spmv_stream_kernel"}[args.kernel]
+    kernel_name = {0: "auto", 1: "spmv_rows_kernel", 2: "spmv_stream_kernel<carry>", 3: "spmv_stream_kernel<atomic> x panels"}[args.kernel]
     if args.kernel == 0:
-        kernel_name = "spmv_stream_kernel"
+        kernel_name = "spmv_stream_kernel<atomic> x panels"
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     wl = "cfg2: CSR SpMV y=A.x, A %dx%d f64, lognormal row lengths (mean 16, sigma 1.5, clip [1,20000]), %d stored entries, pos/crd %d-bit" % (
         m, n, nnz, wbits)

@@ -20,9 +20,11 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kStreamT = 2048;      // stored entries per block of the stream kernel (matches the row blocks built at pack)
+constexpr int kST = kSpmiStreamThreads;        // threads per block of the stream kernel, 8 stored entries each
+constexpr int kStreamT = (int)kSpmiStreamT;   // stored entries per block of the stream kernel (the row blocks are built for it)
 constexpr int kLongRow = 64;        // in-window row length above which a wave reduces the row
 constexpr int kQueue = 64;
+constexpr int kPre = 3;             // rounds of the row loop whose pos entries are fetched ahead
 static_assert(kStreamT / (kLongRow + 1) < kQueue, "queue of long rows too small");
 
 template <typename T>
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void spmv_rows_kernel(const PT *__restric
 
 // ---- stream kernel ----------------------------------------------------------------------
 template <typename PT, typename CT, typename VT>
-__global__ __launch_bounds__(kThreads) void spmv_stream_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+__global__ __launch_bounds__(kST) void spmv_stream_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
                                                                const VT *__restrict__ val, const CT *__restrict__ rowid,
                                                                const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
                                                                const VT *__restrict__ x, int64_t ldb, VT *__restrict__ y, int64_t ldc,
@@ -80,13 +82,26 @@ __global__ __launch_bounds__(kThreads) void spmv_stream_kernel(const PT *__restr
     const int64_t e = (s + kStreamT < nnz) ? s + kStreamT : nnz;
     if (tid == 0) qn = 0;
 
+    // rows lo..hi meet this window (see phase B).  Their pos entries are fetched now, for the first kPre
+    // rounds of the row loop, so that this latency overlaps the entry stream instead of following it.
+    const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
+    const int64_t last = hi < nrows ? hi : nrows - 1;
+    PT pre_a[kPre], pre_b[kPre];
+#pragma unroll
+    for (int k = 0; k < kPre; ++k) {
+        const int64_t r = lo + tid + (int64_t)k * kST;
+        pre_a[k] = r <= last ? pos[r] : (PT)0;
+        pre_b[k] = r <= last ? pos[r + 1] : (PT)0;
+    }
+    const int64_t pos_lo = (int64_t)pos[lo];
+
     // phase A: products of this block's entries into LDS (two consecutive entries per lane and step)
     if (e - s == kStreamT) {
         CT k[8];
         VT v[8];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int64_t p = s + (int64_t)(t * kThreads + tid) * 2;
+            const int64_t p = s + (int64_t)(t * kST + tid) * 2;
             k[2 * t] = crd[p]; k[2 * t + 1] = crd[p + 1];
             v[2 * t] = val[p]; v[2 * t + 1] = val[p + 1];
         }
@@ -95,49 +110,48 @@ __global__ __launch_bounds__(kThreads) void spmv_stream_kernel(const PT *__restr
         for (int i = 0; i < 8; ++i) xv[i] = x[(int64_t)k[i] * ldb];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            prods[(t * kThreads + tid) * 2] = v[2 * t] * xv[2 * t];
-            prods[(t * kThreads + tid) * 2 + 1] = v[2 * t + 1] * xv[2 * t + 1];
+            prods[(t * kST + tid) * 2] = v[2 * t] * xv[2 * t];
+            prods[(t * kST + tid) * 2 + 1] = v[2 * t + 1] * xv[2 * t + 1];
         }
     } else {
-        for (int i = tid; i < (int)(e - s); i += kThreads) prods[i] = val[s + i] * x[(int64_t)crd[s + i] * ldb];
+        for (int i = tid; i < (int)(e - s); i += kST) prods[i] = val[s + i] * x[(int64_t)crd[s + i] * ldb];
     }
     __syncthreads();
 
     // phase B: rows lo..hi meet this window.  Rows lo..hi-1 end here and are written; row hi only
     // starts here (its head goes to y, the rest arrives through later blocks' carries); if row lo
     // began in an earlier window its part goes to this block's carry.
-    const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
-    const bool lo_carried = (int64_t)pos[lo] < s;
-    const int64_t last = hi < nrows ? hi : nrows - 1;
-    for (int64_t r = lo + tid; r <= last; r += kThreads) {
-        const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
+    const bool lo_carried = pos_lo < s;
+    auto emit = [&](int64_t r, VT sum) {
+        if (r == lo && lo_carried) { carry[blockIdx.x] = sum; return; }
+        VT *dst = y + (rowid ? (int64_t)rowid[r] : r) * ldc;
+        *dst = accumulate ? *dst + sum : sum;
+    };
+    auto short_row = [&](int64_t r, int64_t pa, int64_t pb) {
         const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
-        if (r == hi && b <= a) continue;             // row hi starts at the next window: not ours
-        if (b - a > kLongRow) { queue[atomicAdd(&qn, 1)] = (int)(r - lo); continue; }
+        if (r == hi && b <= a) return;               // row hi starts at the next window: not ours
+        if (b - a > kLongRow) { queue[atomicAdd(&qn, 1)] = (int)(r - lo); return; }
         VT sum = 0;
         for (int i = a; i < b; ++i) sum += prods[i];
-        if (r == lo && lo_carried) carry[blockIdx.x] = sum;
-        else {
-            const int64_t row = rowid ? (int64_t)rowid[r] : r;
-            y[row * ldc] = accumulate ? y[row * ldc] + sum : sum;
-        }
+        emit(r, sum);
+    };
+#pragma unroll
+    for (int k = 0; k < kPre; ++k) {
+        const int64_t r = lo + tid + (int64_t)k * kST;
+        if (r <= last) short_row(r, (int64_t)pre_a[k], (int64_t)pre_b[k]);
     }
+    for (int64_t r = lo + tid + (int64_t)kPre * kST; r <= last; r += kST)
+        short_row(r, (int64_t)pos[r], (int64_t)pos[r + 1]);
     __syncthreads();
     const int nq = qn;
-    for (int q = wave; q < nq; q += kThreads / 64) {
+    for (int q = wave; q < nq; q += kST / 64) {
         const int64_t r = lo + queue[q];
         const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
         const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
         VT sum = 0;
         for (int i = a + lane; i < b; i += 64) sum += prods[i];
         sum = wave_sum(sum);
-        if (lane == 0) {
-            if (r == lo && lo_carried) carry[blockIdx.x] = sum;
-            else {
-                const int64_t row = rowid ? (int64_t)rowid[r] : r;
-                y[row * ldc] = accumulate ? y[row * ldc] + sum : sum;
-            }
-        }
+        if (lane == 0) emit(r, sum);
     }
 }
 
@@ -157,6 +171,18 @@ __global__ __launch_bounds__(kThreads) void spmv_stream_fixup_kernel(const PT *_
     for (int64_t bb = b; bb < nblocks && rowblk[bb] == r; ++bb) sum += carry[bb];
     const int64_t row = rowid ? (int64_t)rowid[r] : r;
     y[row * ldc] += sum;
+}
+
+// Column-segmented SpMV, last step: y[r] = (y[r]) + sum over panels of the per-panel partial results.
+template <typename VT>
+__global__ __launch_bounds__(kThreads) void spmv_panel_sum_kernel(const VT *__restrict__ part, int64_t nrows, int panels,
+                                                                  VT *__restrict__ y, int64_t ldc, int accumulate)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r >= nrows) return;
+    VT sum = accumulate ? y[r * ldc] : (VT)0;
+    for (int p = 0; p < panels; ++p) sum += part[(int64_t)p * nrows + r];
+    y[r * ldc] = sum;
 }
 
 // ---- SpMM: a wave per stored row, CG lanes across a tile of B's columns, 64/CG entries in flight ----
@@ -241,13 +267,45 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     if (nrows == 0) return SP_OK;
     if (N == 1) {
         int kernel = A->tune_spmv;
-        if (kernel == 0) kernel = (A->rowblocks.start && nnz >= 8 * kStreamT) ? 2 : 1;
+        if (kernel == 0) {
+            kernel = (A->rowblocks.start && nnz >= 8 * kStreamT) ? 2 : 1;
+            // a large x with a large matrix: gather from L2-sized column panels instead
+            if (kernel == 2 && !dcsr && nnz >= ((int64_t)1 << 22) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) kernel = 3;
+        }
+        if (kernel == 3) {
+            if (dcsr) return SP_ERR_UNSUPPORTED;
+            sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(A), st);      // first use: builds, allocates, synchronises
+            if (sb == SP_ERR_UNSUPPORTED && A->tune_spmv == 0) kernel = 2;
+            else if (sb != SP_OK) return sb;
+        }
+        if (kernel == 3) {
+            // the segmented copy is an ordinary CSR over panels*nrows virtual rows: stream it into the per-panel
+            // partial vector (consecutive blocks gather from the same <= 2 MB slice of x), then add the panels up
+            const sp_segments *g = A->segments;
+            const sp_tensor *S = g->seg;
+            const int64_t nb = S->rowblocks.nblocks, vrows = (int64_t)g->panels * g->nrows;
+            sp_prof_scope prof(A, st);
+            hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kST), 0, st, (const PT *)S->pos[1],
+                               (const CT *)S->crd[1], (const VT *)S->values, (const CT *)nullptr, (const int32_t *)S->rowblocks.start,
+                               vrows, S->ncrd[1], B, ldb, (VT *)g->partial, (int64_t)1, (VT *)S->rowblocks.carry, 0);
+            SP_HIP(hipGetLastError());
+            if (nb > 1) {
+                hipLaunchKernelGGL((spmv_stream_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads)), dim3(kThreads), 0, st,
+                                   (const PT *)S->pos[1], (const CT *)nullptr, (const int32_t *)S->rowblocks.start, nb,
+                                   (const VT *)S->rowblocks.carry, (VT *)g->partial, (int64_t)1);
+                SP_HIP(hipGetLastError());
+            }
+            hipLaunchKernelGGL((spmv_panel_sum_kernel<VT>), dim3(grid_for(g->nrows, kThreads)), dim3(kThreads), 0, st,
+                               (const VT *)g->partial, g->nrows, g->panels, C, ldc, accumulate);
+            SP_HIP(hipGetLastError());
+            return SP_OK;
+        }
         if (kernel == 2 && !A->rowblocks.start) return SP_ERR_UNSUPPORTED;
         if (kernel == 2) {
             const int64_t nb = A->rowblocks.nblocks;
             {
             sp_prof_scope prof(A, st);
-            hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,
+            hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kST), 0, st, pos, crd, val, rowid,
                                (const int32_t *)A->rowblocks.start, nrows, nnz, B, ldb, C, ldc, (VT *)A->rowblocks.carry, accumulate);
             }
             SP_HIP(hipGetLastError());

@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kThreads) void max_segment_kernel(const PT *__restr
     if ((threadIdx.x & 63) == 0 && len) atomicMax(out, len);
 }
 
-// row containing stored entry b*T (largest r with pos[r] <= b*T); block 0 starts at row 0 and the
+// start[b] = row holding stored entry b*T (largest r with pos[r] <= b*T); block 0 starts at row 0 and the
 // sentinel is the row count, so that leading and trailing empty rows belong to some block.
 template <typename PT>
 __global__ __launch_bounds__(kThreads) void rowblocks_kernel(const PT *__restrict__ pos, int64_t nrows, int64_t nblocks, int64_t T,
@@ -284,12 +284,19 @@ __global__ __launch_bounds__(kThreads) void rowblocks_kernel(const PT *__restric
     if (b == 0) { start[0] = 0; return; }
     if (b == nblocks) { start[b] = (int32_t)nrows; return; }
     const int64_t target = b * T;
-    int64_t lo = 0, hi = nrows;            // invariant: pos[lo] <= target, pos[hi] > target or hi == nrows
+    int64_t lo = 0, hi = nrows;            // invariant: pos[lo] <= target; pos[hi] > target or hi == nrows
     while (hi - lo > 1) {
         const int64_t mid = (lo + hi) >> 1;
         if ((int64_t)pos[mid] <= target) lo = mid; else hi = mid;
     }
     start[b] = (int32_t)lo;
+}
+
+__global__ __launch_bounds__(kThreads) void virtual_rows_kernel(int64_t *__restrict__ rows, const int64_t *__restrict__ cols, int64_t n,
+                                                                int shift, int64_t nrows)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e < n) rows[e] += (cols[e] >> shift) * nrows;
 }
 
 template <typename PT, typename CT>
@@ -387,24 +394,64 @@ sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st)
 {
     // only for rank 2 with a compressed innermost level
     if (t->enc.rank != 2 || t->enc.lt[1] != SP_COMPRESSED || t->rowblocks.start) return SP_OK;
-    const int64_t T = 2048;
     const int64_t nrows = t->npos[1] - 1;
-    if (nrows >= ((int64_t)1 << 31)) return SP_OK;        // the streaming kernel keeps 32-bit row ids
-    const int64_t nb = ceil_div(t->ncrd[1], T);
+    if (nrows >= ((int64_t)1 << 31) - 1) return SP_OK;    // the streaming kernel keeps 32-bit row ids
+    const int64_t nb = ceil_div(t->ncrd[1], kSpmiStreamT);
     if (nb == 0) return SP_OK;
     sp_mem mem{t->alloc, t->free_, t->ctx};
     void *start = mem.get(pad16((size_t)(nb + 1) * 4));
     void *carry = mem.get(pad16((size_t)nb * 8));
     if (!start || !carry) { mem.put(start); mem.put(carry); return SP_ERR_ALLOC; }
     if (t->enc.pw == 32)
-        hipLaunchKernelGGL(rowblocks_kernel<int32_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, nb, T, (int32_t *)start);
+        hipLaunchKernelGGL(rowblocks_kernel<int32_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, nb,
+                           kSpmiStreamT, (int32_t *)start);
     else
-        hipLaunchKernelGGL(rowblocks_kernel<int64_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, nb, T, (int32_t *)start);
+        hipLaunchKernelGGL(rowblocks_kernel<int64_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, nb,
+                           kSpmiStreamT, (int32_t *)start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { mem.put(start); mem.put(carry); g_last_hip_error = (int)e; return SP_ERR_HIP; }
     t->rowblocks.start = start;
     t->rowblocks.carry = carry;
     t->rowblocks.nblocks = nb;
+    return SP_OK;
+}
+
+// Column-segmented copy of a CSR tensor (see sp_segments): entries keyed by (panel, row, column) and packed
+// again as a CSR over panels*nrows virtual rows, through the coordinate scheme like any other conversion.
+sp_status spmi_build_segments(sp_tensor *A, hipStream_t st)
+{
+    if (A->segments) return SP_OK;
+    if (A->enc.rank != 2 || A->enc.lt[0] != SP_DENSE || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
+    const int64_t nrows = A->shape[0], n = A->shape[1];
+    const int vbytes = A->dtype == SP_F64 ? 8 : 4;
+    int shift = 0;
+    while (((int64_t)2 << shift) * vbytes <= ((int64_t)2 << 20)) ++shift;      // widest power-of-two panel whose x slice is <= 2 MB
+    const int64_t panels = ceil_div(n, (int64_t)1 << shift);
+    if (panels < 2 || panels * nrows >= ((int64_t)1 << 31) - 1) return SP_ERR_UNSUPPORTED;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    sp_tensor *S = nullptr;
+    {
+        sp_scratch tmp(mem);
+        const size_t cnt = (size_t)(A->nvalues > 0 ? A->nvalues : 1);
+        int64_t *rows = (int64_t *)tmp.get(cnt * 8);
+        int64_t *cols = (int64_t *)tmp.get(cnt * 8);
+        void *vals = tmp.get(cnt * 8);
+        if (!rows || !cols || !vals) return SP_ERR_ALLOC;
+        int64_t *coords[2] = {rows, cols};
+        SP_TRY(sp_unpack(A, coords, vals, st));
+        hipLaunchKernelGGL(virtual_rows_kernel, dim3(blocks_for(A->nvalues)), dim3(kThreads), 0, st, rows, (const int64_t *)cols,
+                           A->nvalues, shift, nrows);
+        SP_HIP(hipGetLastError());
+        sp_encoding enc = A->enc;
+        const int64_t shape[2] = {panels * nrows, n};
+        const int64_t *ccoords[2] = {rows, cols};
+        SP_TRY(sp_pack(&enc, shape, A->nvalues, ccoords, vals, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, st, &S));
+    }
+    void *partial = mem.get(pad16((size_t)(panels * nrows) * vbytes));
+    if (!partial) { sp_tensor_free(S); return SP_ERR_ALLOC; }
+    sp_segments *g = new sp_segments();
+    g->seg = S; g->panels = (int)panels; g->shift = shift; g->nrows = nrows; g->partial = partial;
+    A->segments = g;
     return SP_OK;
 }
 
@@ -421,6 +468,12 @@ extern "C" void sp_tensor_free(sp_tensor *t)
 {
     if (!t) return;
     if (t->transposed) sp_tensor_free(t->transposed);
+    if (t->segments) {
+        sp_mem mem{t->alloc, t->free_, t->ctx};
+        mem.put(t->segments->partial);
+        sp_tensor_free(t->segments->seg);
+        delete t->segments;
+    }
     release_tensor_arrays(t);
     if (t->prof_events) {
         for (hipEvent_t e : *t->prof_events) (void)hipEventDestroy(e);

@@ -23,6 +23,16 @@ struct sp_rowblocks {
     int64_t nblocks = 0;
 };
 
+// Column-segmented copy for SpMV with a large x: the stored entries regrouped by column panel
+// (panel = column >> shift), each panel a CSR over all rows, so that the x slice a panel gathers
+// from stays in the per-XCD L2.  `seg` is a CSR tensor over panels*nrows virtual rows.
+struct sp_segments {
+    sp_tensor *seg = nullptr;
+    int panels = 0, shift = 0;
+    int64_t nrows = 0;
+    void *partial = nullptr;          // DEVICE value-typed[panels * nrows]: per-panel results before they are added up
+};
+
 struct sp_tensor {
     sp_encoding enc;
     int dtype;
@@ -42,6 +52,7 @@ struct sp_tensor {
     // derived, built lazily by sp_matmul or eagerly by sp_pack
     sp_rowblocks rowblocks;
     sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
+    sp_segments *segments;           // owned, built on first use
     int tune_spmv, tune_csc, tune_spmm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
@@ -110,6 +121,9 @@ sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int k
                                 sp_scratch &tmp, hipStream_t st);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
+sp_status spmi_build_segments(sp_tensor *A, hipStream_t st);
+constexpr int kSpmiStreamThreads = 128;
+constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * 8;     // stored entries per block of the stream kernel
 
 // ---- matmul.hip --------------------------------------------------------------------------
 sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,

@@ -54,6 +54,53 @@ def test_csr_spmv(name, maker, kernel, widths):
     assert_product_close(y, ref, mag, w.dtype, name + " accumulate")
 
 
+WIDE_CASES = [
+    ("wide, 3 column panels", lambda: W.cfg2_powerlaw_csr(50000, 600000, mean=24.0, cap=9000)),
+    ("wide, rows crossing several blocks inside a panel", lambda: W.cfg2_powerlaw_csr(64, 600000, mean=20000.0, sigma=0.3, cap=60000)),
+    ("wide, many empty rows", lambda: W.cfg4_hypersparse_dcsr(1 << 19, 1 << 19, frac=0.05, per_row=40)),
+]
+
+
+@pytest.mark.parametrize("name,maker", WIDE_CASES)
+@pytest.mark.parametrize("widths", [(32, 32), (64, 64)])
+def test_csr_spmv_column_segmented(name, maker, widths):
+    """Kernel 3 (x gathered from L2-sized column panels; rows that cross blocks use atomic adds)."""
+    w = maker()
+    say("case segmented spmv", name, widths, w.stats)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, *widths)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 3)
+    x = w.dense_operand(1)
+    y, ref, mag = run(A, w, x)
+    assert_product_close(y, ref, mag, w.dtype, name)
+    y0 = prng.uniform_pm1(5, 5, w.shape[0])
+    y, ref, mag = run(A, w, x, accumulate=True, C0=y0)
+    assert_product_close(y, ref, mag, w.dtype, name + " accumulate")
+    # exact integers: the order of the atomic adds cannot matter
+    vals = w.exact_values()
+    A2 = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], vals, *widths)
+    sp.sp_tensor_tune(A2, sp.SP_TUNE_SPMV_KERNEL, 3)
+    y, ref, mag = run(A2, w, w.dense_operand(1, exact=True), vals=vals)
+    assert np.array_equal(y.cpu().numpy(), ref)
+
+
+def test_csr_spmv_column_segmented_empty_first_panel_and_fallback():
+    w = W.cfg2_powerlaw_csr(20000, 300000, mean=10.0, cap=2000)
+    w.cols = w.cols + 300000            # every entry in the upper panels of a 600000-column matrix
+    w.shape = (20000, 600000)
+    say("case segmented, empty first panel")
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 3)
+    y, ref, mag = run(A, w, w.dense_operand(1))
+    assert_product_close(y, ref, mag, w.dtype, "empty first panel")
+    say("case segmented, x too small for panels")
+    w2 = W.cfg2_powerlaw_csr(3000, 3000, cap=500)
+    A2 = gpu_pack((0, 1), (0, 1), w2.shape, [w2.rows, w2.cols], w2.vals)
+    sp.sp_tensor_tune(A2, sp.SP_TUNE_SPMV_KERNEL, 3)
+    with pytest.raises(sp.SpError) as e:
+        sp.sp_matmul(A2, dev(w2.dense_operand(1)), torch.empty(3000, dtype=torch.float64, device=DEV))
+    assert e.value.code == oracle.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("kernel", [1, 2])
 def test_exact_integer_inputs_bit_exact(kernel):
     w = W.cfg2_powerlaw_csr(30000, 30000, mean=20.0, cap=7000)
