@@ -1,12 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse x dense hot path on one MI355X.
 
-Default workload: f64 CSR SpMV on the 1M x 1M matrix with lognormal row lengths (~16.8M stored
-entries), 32-bit pos/crd.  One step = one sp_matmul (y = A.x) through the C ABI.  The matrix, x
-and y are resident in HBM before the timed region; the step rotates over several independent
-copies so that no step finds its operands in the 256 MB last-level cache ("cold").  Prints one JSON
-line: effective GB/s on the algorithmic bytes, the roofline of the dominant kernel (timed with
-HIP events recorded by the library around that kernel), and the CPU checker timed on the host.
+Default workload (the one the headline metric is quoted on): f64 CSR SpMV on the 1M x 1M matrix
+with lognormal row lengths (~16.8M stored entries), 32-bit pos/crd.  One step = one sp_matmul
+through the C ABI.  A, B and C are resident in HBM before the timed region; the steps rotate over
+several independent copies so that no step finds its operands in the 256 MB last-level cache
+("cold"); the same-buffers ("warm") figure is reported next to it.  Prints one JSON line: effective
+GB/s on the algorithmic bytes, the roofline of the dominant kernel (timed with HIP events that the
+library records around it), and the CPU checker timed on the host.
+
+Other workloads (--workload cfg1|cfg3|cfg4|cfg5) print the same line for the other configurations.
 """
 import argparse
 import json
@@ -22,25 +25,59 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
-# scaled by the same counters on the plain copy kernel; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per product (bytes) from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# same counter reads for the plain copy kernel of known size); the summaries are under profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2", 32): None,
+}
 
 
-def algorithmic_bytes_spmv(nnz, m, n, vbytes, wp, wc):
-    """Compulsory bytes of y = A.x in CSR: values + crd + pos + x once + y once."""
-    return nnz * (vbytes + wc) + (m + 1) * wp + vbytes * n + vbytes * m
+def make_workload(name, small):
+    from gen import workloads as W
+    if name == "cfg1":
+        return W.cfg1_uniform_csr()
+    if name == "cfg2":
+        return W.cfg2_powerlaw_csr(1 << 16, 1 << 16) if small else W.cfg2_powerlaw_csr()
+    if name == "cfg3":
+        return W.cfg3_powerlaw_csr_spmm(1 << 16, 1 << 16) if small else W.cfg3_powerlaw_csr_spmm()
+    if name == "cfg4":
+        return W.cfg4_hypersparse_dcsr(1 << 19, 1 << 19) if small else W.cfg4_hypersparse_dcsr()
+    if name == "cfg5":
+        return W.cfg5_zipf_csc_spmm(1 << 17, 1 << 17) if small else W.cfg5_zipf_csc_spmm()
+    raise SystemExit("unknown workload " + name)
+
+
+DESCRIPTIONS = {
+    "cfg1": "cfg1: CSR SpMV y=A.x, A %(m)dx%(n)d f64, exactly 8 stored entries per row, %(nnz)d stored entries",
+    "cfg2": "cfg2: CSR SpMV y=A.x, A %(m)dx%(n)d f64, lognormal row lengths (mean 16, sigma 1.5, clip [1,20000]), %(nnz)d stored entries",
+    "cfg3": "cfg3: CSR SpMM C=A.B, A as cfg2 (%(m)dx%(n)d f64, %(nnz)d stored entries), B %(n)dx%(N)d f64 row-major",
+    "cfg4": "cfg4: DCSR SpMV y=A.x, A %(m)dx%(n)d f64, 1%% of rows stored, 32 entries each, %(nnz)d stored entries",
+    "cfg5": "cfg5: CSC SpMM C=A.B, A %(m)dx%(n)d f32, rank-size Zipf(1.2) column lengths capped at 50000, %(nnz)d stored entries, B %(n)dx%(N)d f32",
+}
+
+
+def algorithmic_bytes(name, w, info, N, vbytes):
+    """Compulsory bytes of one product: the storage arrays once, B (x) once, C (y) once."""
+    m, n = w.shape
+    a = int(info.storageBytes)
+    if name == "cfg4":
+        # x: only the touched elements; y: the whole vector is written in overwrite mode
+        return a + w.nnz * vbytes + m * vbytes
+    return a + n * N * vbytes + m * N * vbytes
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--copies", type=int, default=6, help="independent copies of A, x, y rotated through (cold regime)")
+    ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--copies", type=int, default=0, help="independent copies of A, B, C rotated through (cold regime)")
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
-    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
-    ap.add_argument("--small", action="store_true", help="1/16-size matrix (for quick checks)")
+    ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
+    ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
+    ap.add_argument("--accumulate", action="store_true", help="C += A.B instead of C = A.B")
+    ap.add_argument("--small", action="store_true", help="scaled-down matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -50,17 +87,23 @@ def main():
 
     import torch
     import paper_2202_04305_amd as sp
-    from gen import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    name = args.workload
     t0 = time.time()
-    w = W.cfg2_powerlaw_csr(1 << 16, 1 << 16) if args.small else W.cfg2_powerlaw_csr()
+    w = make_workload(name, args.small)
     gen_s = time.time() - t0
     m, n = w.shape
-    nnz = w.nnz
+    nnz, N = w.nnz, w.N
     wbits = args.width
-    x_host = w.dense_operand(1)
+    tdtype = torch.float64 if w.dtype == np.float64 else torch.float32
+    vbytes = 8 if w.dtype == np.float64 else 4
+    B_host = w.dense_operand(N)
+    spmv = N == 1
+    steps = args.steps or (300 if spmv else 20)
+    warmup = args.warmup or (30 if spmv else 3)
+    ncopies = args.copies or (6 if spmv else 2)
 
     rows_d = torch.from_numpy(w.rows).to(dev)
     cols_d = torch.from_numpy(w.cols).to(dev)
@@ -68,7 +111,7 @@ def main():
     enc = sp.sp_encode(w.level_types, w.dim_ordering, wbits, wbits)
     copies = []
     pack_ms = []
-    for c in range(args.copies):
+    for c in range(ncopies):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         A = sp.sp_pack(enc, w.shape, [rows_d, cols_d], vals_d)
@@ -76,18 +119,20 @@ def main():
         torch.cuda.synchronize()
         pack_ms.append(e0.elapsed_time(e1))
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, args.kernel)
-        x = torch.from_numpy(x_host[:, 0].copy()).to(dev)
-        y = torch.zeros(m, dtype=torch.float64, device=dev)
-        copies.append((A, x, y))
+        sp.sp_tensor_tune(A, sp.SP_TUNE_CSC_MODE, args.csc_mode)
+        Bd = torch.from_numpy(B_host[:, 0].copy() if spmv else B_host).to(dev)
+        Cd = torch.zeros(m if spmv else (m, N), dtype=tdtype, device=dev)
+        copies.append((A, Bd, Cd))
     del rows_d, cols_d, vals_d
     info = sp.sp_tensor_info(copies[0][0])
-    abytes = algorithmic_bytes_spmv(nnz, m, n, 8, wbits // 8, wbits // 8)
-    flops = 2.0 * nnz
+    abytes = algorithmic_bytes(name, w, info, N, vbytes)
+    flops = 2.0 * nnz * N
+    acc = bool(args.accumulate)
 
     def run_steps(k, rotate=True):
         for i in range(k):
-            A, x, y = copies[i % len(copies)] if rotate else copies[0]
-            sp.sp_matmul(A, x, y)
+            A, Bd, Cd = copies[i % len(copies)] if rotate else copies[0]
+            sp.sp_matmul(A, Bd, Cd, accumulate=acc)
 
     def timed(k, rotate=True):
         torch.cuda.synchronize()
@@ -98,15 +143,15 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / k
 
-    run_steps(args.warmup)
-    ms_cold = timed(args.steps)
-    run_steps(args.warmup, rotate=False)
-    ms_warm = timed(args.steps, rotate=False)
+    run_steps(warmup)          # also builds whatever the first product of a tensor builds and keeps
+    ms_cold = timed(steps)
+    run_steps(warmup, rotate=False)
+    ms_warm = timed(steps, rotate=False)
 
-    # dominant kernel alone, timed by the library's own event pairs around it (separate pass)
+    # the kernels that stream A, timed by the library's own event pairs around them (separate pass)
     for A, _, _ in copies:
         sp.sp_tensor_tune(A, sp.SP_TUNE_PROFILE, 1)
-    run_steps(args.steps)
+    run_steps(steps)
     torch.cuda.synchronize()
     tot_ms, launches = 0.0, 0
     for A, _, _ in copies:
@@ -115,6 +160,12 @@ def main():
         launches += b
         sp.sp_tensor_tune(A, sp.SP_TUNE_PROFILE, 0)
     kernel_ms = tot_ms / max(launches, 1)
+
+    # one clean product on copy 0 for the parity check below
+    if acc:
+        copies[0][2].zero_()
+    sp.sp_matmul(copies[0][0], copies[0][1], copies[0][2], accumulate=False)
+    torch.cuda.synchronize()
 
     # yardstick: plain copy kernel on 1 GiB (read + write = 2 GiB of traffic)
     nbytes = 1 << 30
@@ -137,48 +188,54 @@ def main():
     parity = None
     if not args.no_cpu:
         import oracle
+        reps = 3 if spmv else 1
         times = []
-        for _ in range(3):
+        for _ in range(reps):
             t0 = time.time()
-            yref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x_host)
+            Cref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B_host)
             times.append(time.time() - t0)
-        cpu_s = sorted(times)[1]
-        ygpu = copies[0][2].cpu().numpy()
-        err = np.abs(ygpu - yref[:, 0])
-        parity = bool(np.all(err <= 1e-12 * mag[:, 0]))
+        cpu_s = sorted(times)[len(times) // 2]
+        Cg = copies[0][2].cpu().numpy().reshape(m, N).astype(np.float64)
+        tol = 1e-12 if vbytes == 8 else 1e-5
+        parity = bool(np.all(np.abs(Cg - Cref) <= tol * mag))
         cpu = {"value": abytes / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "sample": "the whole workload (%d stored entries, one y = A.x), median of 3, %.3f s per product" % (nnz, cpu_s),
+               "sample": "the whole workload (%d stored entries x %d columns, one product), median of %d, %.3f s per product" % (
+                   nnz, N, reps, cpu_s),
                "gflops": flops / cpu_s / 1e9}
 
-    kernel_name = {0: "auto", 1: "spmv_rows_kernel", 2: "spmv_stream_kernel<carry>", 3: "spmv_stream_kernel<atomic> x panels"}[args.kernel]
-    if args.kernel == 0:
-        kernel_name = "spmv_stream_kernel<atomic> x panels"
+    if spmv:
+        kk = args.kernel
+        if kk == 0:
+            kk = 3 if (name == "cfg2" and not args.small) else 2
+        kernel_name = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
+                       3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel"}[kk]
+    else:
+        kernel_name = "spmm_rows_kernel" if (name == "cfg3" or args.csc_mode != 1) else "spmm_scatter_kernel"
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
-    wl = "cfg2: CSR SpMV y=A.x, A %dx%d f64, lognormal row lengths (mean 16, sigma 1.5, clip [1,20000]), %d stored entries, pos/crd %d-bit" % (
-        m, n, nnz, wbits)
+    wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits
     out = {
-        "metric": "effective HBM GB/s for f64 CSR SpMV (algorithmic bytes / time per product)",
+        "metric": "effective HBM GB/s for f64 CSR SpMV/SpMM (algorithmic bytes / time per product)",
         "value": abytes / (ms_cold * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_cold,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f64",
+        "dtype": "f64" if vbytes == 8 else "f32",
         "data": "synthetic",
-        "config": {"workload": wl, "regime": "cold: rotating over %d copies of A, x, y (%.2f GB)" % (
-            args.copies, args.copies * abytes / 1e9), "kernel": kernel_name, "small": bool(args.small)},
+        "config": {"workload": wl, "regime": "cold: rotating over %d copies of A, B, C (%.2f GB)" % (
+            ncopies, ncopies * abytes / 1e9), "kernel": kernel_name, "accumulate": acc, "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((kernel_name, wbits)),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((name, wbits)),
                      "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
         "cpu_baseline": cpu,
         "gflops": flops / (ms_cold * 1e-3) / 1e9,
         "frac_of_peak": abytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "warm": {"ms_per_step": ms_warm, "value": abytes / (ms_warm * 1e-3) / 1e9,
-                 "note": "same buffers every step: the 222-294 MB working set partly lives in the last-level cache"},
+                 "note": "same buffers every step: part of the working set stays in the last-level cache"},
         "copy_kernel_gbs": copy_gbs,
         "frac_of_copy": abytes / (ms_cold * 1e-3) / 1e9 / copy_gbs,
         "pack": {"ms": sorted(pack_ms)[len(pack_ms) // 2], "mnnz_per_s": nnz / (sorted(pack_ms)[len(pack_ms) // 2] * 1e-3) / 1e6},

@@ -1,0 +1,147 @@
+"""The benchmark configurations at their full sizes, in the launch configuration bench.py times.
+
+Storage arrays are compared with the CPU checker bit for bit where the checker finishes in seconds (the 16.8M-entry
+CSR matrix), otherwise through the storage invariants plus sampled segments rebuilt by the checker.  Products are
+compared on every element for SpMV and on sampled rows for the 64- and 32-column SpMM (the checker computes exactly
+those rows from the sub-COO that holds them).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_04305_amd as sp
+from gen import workloads as W, prng
+from gpu_util import say, dev, gpu_pack, assert_storage_equal, assert_product_close, DEV
+
+pytestmark = pytest.mark.gpu
+
+_cache = {}
+
+
+def workload(name):
+    if name not in _cache:
+        _cache.clear()                     # one full-size workload in host memory at a time
+        say("generating", name)
+        _cache[name] = {"cfg2": W.cfg2_powerlaw_csr, "cfg4": W.cfg4_hypersparse_dcsr, "cfg5": W.cfg5_zipf_csc_spmm}[name]()
+        say(_cache[name].stats)
+    return _cache[name]
+
+
+def check_storage_invariants(A, w):
+    """pos[0] = 0, pos monotone, pos[last] = len(crd), crd in range and strictly increasing inside each segment."""
+    info = sp.sp_tensor_info(A)
+    P = 1
+    for l in range(2):
+        size = w.shape[info.dimOrdering[l]]
+        if info.levelTypes[l] == 0:
+            P *= size
+            continue
+        pos, crd = sp.sp_pos(A, l).long(), sp.sp_crd(A, l).long()
+        assert pos.numel() == P + 1 and int(pos[0]) == 0 and int(pos[-1]) == crd.numel()
+        assert bool(torch.all(pos[1:] >= pos[:-1]))
+        assert bool(torch.all((crd >= 0) & (crd < size)))
+        inner = torch.ones(crd.numel(), dtype=torch.bool, device=DEV)
+        starts = pos[:-1][pos[:-1] < crd.numel()]
+        inner[starts] = False
+        assert bool(torch.all((crd[1:] > crd[:-1]) | ~inner[1:]))
+        P = crd.numel()
+    assert info.nvalues == P
+
+
+def sampled_rows_product(w, rows_pick, B):
+    """(C_ref, mag) for the picked rows only, from the sub-COO holding exactly those rows."""
+    sel = np.isin(w.rows, rows_pick)
+    remap = -np.ones(w.shape[0], dtype=np.int64)
+    remap[rows_pick] = np.arange(len(rows_pick))
+    return oracle.matmul_coo((len(rows_pick), w.shape[1]), remap[w.rows[sel]], w.cols[sel], w.vals[sel], B)
+
+
+def test_cfg2_pack_and_spmv_full_size():
+    w = workload("cfg2")
+    say("case cfg2 full: pack")
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    ref = oracle.pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    assert_storage_equal(A, ref)
+    del ref
+    x = w.dense_operand(1)
+    yref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
+    xd = dev(x[:, 0].copy())
+    for kernel in (0, 2, 3, 1):            # 0 = what bench.py times (the column-segmented kernel at this size)
+        say("case cfg2 full: spmv kernel", kernel)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+        y = torch.full((w.shape[0],), float("nan"), dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, xd, y)
+        assert_product_close(y, yref, mag, np.float64, "cfg2 kernel %d" % kernel)
+    # closed form at full size: all-ones values and x give the row lengths, exactly
+    say("case cfg2 full: row lengths")
+    A1 = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], np.ones(w.nnz), 32, 32)
+    y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A1, torch.ones(w.shape[1], dtype=torch.float64, device=DEV), y)
+    assert torch.equal(y, (sp.sp_pos(A1, 1)[1:] - sp.sp_pos(A1, 1)[:-1]).double())
+
+
+def test_cfg3_spmm_full_size_sampled_rows():
+    w = workload("cfg2")
+    N = 64
+    say("case cfg3 full: spmm, 64 columns")
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    B = w.dense_operand(N)
+    C = torch.full((w.shape[0], N), float("nan"), dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, dev(B), C)
+    lens = np.bincount(w.rows, minlength=w.shape[0])
+    pick = np.unique(np.concatenate([prng.below(11, 1, 3000, w.shape[0]), np.argsort(-lens)[:20], [0, w.shape[0] - 1]]))
+    ref, mag = sampled_rows_product(w, pick, B)
+    assert_product_close(C[torch.from_numpy(pick).to(DEV)], ref, mag, np.float64, "cfg3 sampled rows")
+    assert not bool(torch.isnan(C).any())
+
+
+def test_cfg4_dcsr_full_size():
+    w = workload("cfg4")
+    say("case cfg4 full: pack")
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    ref = oracle.pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    assert_storage_equal(A, ref)
+    x = w.dense_operand(1)
+    yref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
+    say("case cfg4 full: spmv overwrite")
+    y = torch.full((w.shape[0],), float("nan"), dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, dev(x[:, 0].copy()), y)
+    assert_product_close(y, yref, mag, np.float64, "cfg4")
+    say("case cfg4 full: spmv accumulate")
+    y0 = prng.uniform_pm1(3, 3, w.shape[0])
+    yref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x, True, y0)
+    y = dev(y0)
+    sp.sp_matmul(A, dev(x[:, 0].copy()), y, accumulate=True)
+    assert_product_close(y, yref, mag, np.float64, "cfg4 accumulate")
+
+
+def test_cfg5_csc_full_size():
+    w = workload("cfg5")
+    say("case cfg5 full: pack")
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+    check_storage_invariants(A, w)
+    # sampled columns rebuilt by the checker from the sub-COO of those columns (the longest ones included)
+    lens = np.bincount(w.cols, minlength=w.shape[1])
+    pick = np.unique(np.concatenate([prng.below(12, 1, 2000, w.shape[1]), np.argsort(-lens)[:5]]))
+    sel = np.isin(w.cols, pick)
+    remap = -np.ones(w.shape[1], dtype=np.int64)
+    remap[pick] = np.arange(len(pick))
+    sub = oracle.pack((0, 1), (1, 0), (w.shape[0], len(pick)), [w.rows[sel], remap[w.cols[sel]]], w.vals[sel], 32, 32)
+    pos, crd, val = sp.sp_pos(A, 1).cpu().numpy().astype(np.int64), sp.sp_crd(A, 1), sp.sp_values(A)
+    assert np.array_equal(np.diff(sub.pos[1]), (pos[1:] - pos[:-1])[pick])
+    idx = np.concatenate([np.arange(pos[c], pos[c + 1]) for c in pick])
+    idx_d = torch.from_numpy(idx).to(DEV)
+    assert np.array_equal(crd[idx_d].cpu().numpy(), sub.crd[1])
+    assert val[idx_d].cpu().numpy().tobytes() == sub.values.tobytes()
+    assert pos[-1] == w.nnz and np.array_equal(pos[1:] - pos[:-1], lens)
+    say("case cfg5 full: spmm, 32 columns, f32")
+    N = 32
+    B = w.dense_operand(N)
+    C = torch.full((w.shape[0], N), float("nan"), dtype=torch.float32, device=DEV)
+    sp.sp_matmul(A, dev(B), C)
+    rlens = np.bincount(w.rows, minlength=w.shape[0])
+    rpick = np.unique(np.concatenate([prng.below(13, 1, 3000, w.shape[0]), np.argsort(-rlens)[:20], np.nonzero(rlens == 0)[0][:20]]))
+    ref, mag = sampled_rows_product(w, rpick, B)
+    assert_product_close(C[torch.from_numpy(rpick).to(DEV)], ref, mag, np.float32, "cfg5 sampled rows")
+    assert not bool(torch.isnan(C).any())
