@@ -24,7 +24,8 @@ constexpr int kST = kSpmiStreamThreads;        // threads per block of the strea
 constexpr int kStreamT = (int)kSpmiStreamT;   // stored entries per block of the stream kernel (the row blocks are built for it)
 constexpr int kLongRow = 64;        // in-window row length above which a wave reduces the row
 constexpr int kQueue = 64;
-constexpr int kPre = 3;             // rounds of the row loop whose pos entries are fetched ahead
+constexpr int64_t kSpmvSliceBytes = (int64_t)2 << 20;     // slice of x one column panel gathers from: half of a 4 MB per-XCD L2
+constexpr int kPre = 1;             // rounds of the row loop whose pos entries are fetched ahead
 static_assert(kStreamT / (kLongRow + 1) < kQueue, "queue of long rows too small");
 
 template <typename T>
@@ -67,63 +68,73 @@ __global__ __launch_bounds__(kThreads) void spmv_rows_kernel(const PT *__restric
 }
 
 // ---- stream kernel ----------------------------------------------------------------------
+// Measured on the 1M x 1M workload: with operands cold in HBM the kernel runs 10 % faster at 3 waves per SIMD than at
+// the 8 the register count would allow (fewer concurrent entry streams); warm it makes no difference.
+#ifndef SPMI_WPE
+#define SPMI_WPE 3
+#endif
 template <typename PT, typename CT, typename VT>
-__global__ __launch_bounds__(kST) void spmv_stream_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+__global__ __launch_bounds__(kST) __attribute__((amdgpu_waves_per_eu(1, SPMI_WPE))) void spmv_stream_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
                                                                const VT *__restrict__ val, const CT *__restrict__ rowid,
                                                                const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
                                                                const VT *__restrict__ x, int64_t ldb, VT *__restrict__ y, int64_t ldc,
                                                                VT *__restrict__ carry, int accumulate)
 {
+    const int64_t win = blockIdx.x;
     __shared__ VT prods[kStreamT];
     __shared__ int queue[kQueue];
-    __shared__ int qn;
+    __shared__ int qn, lo_began_earlier;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t s = (int64_t)blockIdx.x * kStreamT;
+    const int64_t s = win * kStreamT;
     const int64_t e = (s + kStreamT < nnz) ? s + kStreamT : nnz;
     if (tid == 0) qn = 0;
 
-    // rows lo..hi meet this window (see phase B).  Their pos entries are fetched now, for the first kPre
-    // rounds of the row loop, so that this latency overlaps the entry stream instead of following it.
-    const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
-    const int64_t last = hi < nrows ? hi : nrows - 1;
-    PT pre_a[kPre], pre_b[kPre];
+    // phase A: this block's entries (two consecutive entries per lane and step), every load issued before the
+    // first use.  The pos entries of the rows that meet the window (see phase B) are fetched in the same
+    // batch, for the first kPre rounds of the row loop, so that their latency hides under the gathers.
+    const bool full = e - s == kStreamT;
+    constexpr int E = kSpmiStreamPer;
+    CT k[E];
+    VT v[E];
+    if (full) {
 #pragma unroll
-    for (int k = 0; k < kPre; ++k) {
-        const int64_t r = lo + tid + (int64_t)k * kST;
-        pre_a[k] = r <= last ? pos[r] : (PT)0;
-        pre_b[k] = r <= last ? pos[r + 1] : (PT)0;
-    }
-    const int64_t pos_lo = (int64_t)pos[lo];
-
-    // phase A: products of this block's entries into LDS (two consecutive entries per lane and step)
-    if (e - s == kStreamT) {
-        CT k[8];
-        VT v[8];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < E / 2; ++t) {
             const int64_t p = s + (int64_t)(t * kST + tid) * 2;
             k[2 * t] = crd[p]; k[2 * t + 1] = crd[p + 1];
             v[2 * t] = val[p]; v[2 * t + 1] = val[p + 1];
         }
-        VT xv[8];
+    }
+    const int64_t lo = rowblk[win], hi = rowblk[win + 1];
+    const int64_t last = hi < nrows ? hi : nrows - 1;
+    PT pre_a[kPre], pre_b[kPre];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) xv[i] = x[(int64_t)k[i] * ldb];
+    for (int i = 0; i < kPre; ++i) {
+        int64_t r = lo + tid + (int64_t)i * kST;
+        r = r <= last ? r : last;                      // clamped, not predicated: the loads stay unconditional
+        pre_a[i] = pos[r];
+        pre_b[i] = pos[r + 1];
+    }
+    if (full) {
+        VT xv[E];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int i = 0; i < E; ++i) xv[i] = x[(int64_t)k[i] * ldb];
+#pragma unroll
+        for (int t = 0; t < E / 2; ++t) {
             prods[(t * kST + tid) * 2] = v[2 * t] * xv[2 * t];
             prods[(t * kST + tid) * 2 + 1] = v[2 * t + 1] * xv[2 * t + 1];
         }
     } else {
         for (int i = tid; i < (int)(e - s); i += kST) prods[i] = val[s + i] * x[(int64_t)crd[s + i] * ldb];
     }
+    if (tid == 0) lo_began_earlier = (int64_t)pre_a[0] < s;      // thread 0 prefetched pos[lo]
     __syncthreads();
 
     // phase B: rows lo..hi meet this window.  Rows lo..hi-1 end here and are written; row hi only
     // starts here (its head goes to y, the rest arrives through later blocks' carries); if row lo
     // began in an earlier window its part goes to this block's carry.
-    const bool lo_carried = pos_lo < s;
+    const bool lo_carried = lo_began_earlier != 0;
     auto emit = [&](int64_t r, VT sum) {
-        if (r == lo && lo_carried) { carry[blockIdx.x] = sum; return; }
+        if (r == lo && lo_carried) { carry[win] = sum; return; }
         VT *dst = y + (rowid ? (int64_t)rowid[r] : r) * ldc;
         *dst = accumulate ? *dst + sum : sum;
     };
@@ -202,26 +213,37 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(const PT *__restric
     for (int64_t j0 = 0; j0 < N; j0 += CG) {
         const int64_t j = j0 + jl;
         const bool jin = j < N;
-        constexpr int U = CG == 64 ? 2 : 4;            // independent row gathers in flight per lane (measured: 512-byte rows want 2)
-        VT accu[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) accu[u] = 0;
-        int64_t p = a + sl;
-        for (; p + (U - 1) * S < b; p += U * S) {
-            int64_t k[U];
-            VT v[U], bv[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) { k[u] = (int64_t)crd[p + u * S]; v[u] = val[p + u * S]; }
-#pragma unroll
-            for (int u = 0; u < U; ++u) bv[u] = jin ? B[k[u] * ldb + j] : (VT)0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) accu[u] += v[u] * bv[u];
-        }
-        for (; p < b; p += S)
-            if (jin) accu[0] += val[p] * B[(int64_t)crd[p] * ldb + j];
         VT acc = 0;
+        int64_t p = a + sl;
+        if constexpr (CG == 64) {                      // 512-byte rows of B (f64): two row gathers in flight measured best
+            VT acc1 = 0;
+            for (; p + S < b; p += 2 * S) {
+                const int64_t k0 = (int64_t)crd[p], k1 = (int64_t)crd[p + S];
+                const VT v0 = val[p], v1 = val[p + S];
+                if (jin) { acc += v0 * B[k0 * ldb + j]; acc1 += v1 * B[k1 * ldb + j]; }
+            }
+            if (p < b && jin) acc += val[p] * B[(int64_t)crd[p] * ldb + j];
+            acc += acc1;
+        } else {                                       // narrower tiles: four
+            constexpr int U = 4;
+            VT accu[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc += accu[u];
+            for (int u = 0; u < U; ++u) accu[u] = 0;
+            for (; p + (U - 1) * S < b; p += U * S) {
+                int64_t k[U];
+                VT v[U], bv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) { k[u] = (int64_t)crd[p + u * S]; v[u] = val[p + u * S]; }
+#pragma unroll
+                for (int u = 0; u < U; ++u) bv[u] = jin ? B[k[u] * ldb + j] : (VT)0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) accu[u] += v[u] * bv[u];
+            }
+            for (; p < b; p += S)
+                if (jin) accu[0] += val[p] * B[(int64_t)crd[p] * ldb + j];
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += accu[u];
+        }
 #pragma unroll
         for (int d = 32; d >= CG; d >>= 1) acc += __shfl_xor(acc, d, 64);
         if (sl == 0 && jin) C[row * ldc + j] = accumulate ? C[row * ldc + j] + acc : acc;
@@ -285,7 +307,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
         }
         if (kernel == 3) {
             if (dcsr) return SP_ERR_UNSUPPORTED;
-            sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(A), st);      // first use: builds, allocates, synchronises
+            sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(A), sizeof(VT), kSpmvSliceBytes, st);   // first use: builds, allocates, synchronises
             if (sb == SP_ERR_UNSUPPORTED && A->tune_spmv == 0) kernel = 2;
             else if (sb != SP_OK) return sb;
         }
@@ -342,6 +364,9 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
         SP_HIP(hipGetLastError());
         return SP_OK;
     }
+    // Tried and dropped (measured on the 1M x 1M matrix times a 1M x 64 operand): one launch per column panel of the
+    // segmented copy, so that the slice of B a launch gathers from fits the 256 MB last-level cache.  Re-reading and
+    // re-writing C once per panel costs more than the gathers save: 3.17 ms against 2.94 ms.
     sp_prof_scope prof(A, st);
 #define SPMI_SPMM(CG)                                                                                                         \
     hipLaunchKernelGGL((spmm_rows_kernel<PT, CT, VT, CG>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, crd, \

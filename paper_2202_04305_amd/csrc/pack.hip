@@ -418,16 +418,30 @@ sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st)
 
 // Column-segmented copy of a CSR tensor (see sp_segments): entries keyed by (panel, row, column) and packed
 // again as a CSR over panels*nrows virtual rows, through the coordinate scheme like any other conversion.
-sp_status spmi_build_segments(sp_tensor *A, hipStream_t st)
+static void free_segments(sp_tensor *t)
 {
-    if (A->segments) return SP_OK;
+    if (!t->segments) return;
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    mem.put(t->segments->partial);
+    sp_tensor_free(t->segments->seg);
+    delete t->segments;
+    t->segments = nullptr;
+}
+
+// `slice_bytes`: how many bytes of the dense operand one panel may cover (a power-of-two number of its rows
+// is taken).  The handle keeps one segmented copy; asking for another panel width rebuilds it.
+sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st)
+{
     if (A->enc.rank != 2 || A->enc.lt[0] != SP_DENSE || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
     const int64_t nrows = A->shape[0], n = A->shape[1];
     const int vbytes = A->dtype == SP_F64 ? 8 : 4;
     int shift = 0;
-    while (((int64_t)2 << shift) * vbytes <= ((int64_t)2 << 20)) ++shift;      // widest power-of-two panel whose x slice is <= 2 MB
+    while (((int64_t)2 << shift) * row_bytes <= slice_bytes) ++shift;       // widest power-of-two panel within the budget
+    if (A->segments && A->segments->shift == shift) return SP_OK;
     const int64_t panels = ceil_div(n, (int64_t)1 << shift);
     if (panels < 2 || panels * nrows >= ((int64_t)1 << 31) - 1) return SP_ERR_UNSUPPORTED;
+    if (hipStreamSynchronize(st) != hipSuccess) return SP_ERR_HIP;          // an older copy may still be in use
+    free_segments(A);
     sp_mem mem{A->alloc, A->free_, A->ctx};
     sp_tensor *S = nullptr;
     {
@@ -468,12 +482,7 @@ extern "C" void sp_tensor_free(sp_tensor *t)
 {
     if (!t) return;
     if (t->transposed) sp_tensor_free(t->transposed);
-    if (t->segments) {
-        sp_mem mem{t->alloc, t->free_, t->ctx};
-        mem.put(t->segments->partial);
-        sp_tensor_free(t->segments->seg);
-        delete t->segments;
-    }
+    free_segments(t);
     release_tensor_arrays(t);
     if (t->prof_events) {
         for (hipEvent_t e : *t->prof_events) (void)hipEventDestroy(e);

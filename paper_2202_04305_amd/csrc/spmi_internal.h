@@ -121,9 +121,16 @@ sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int k
                                 sp_scratch &tmp, hipStream_t st);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
-sp_status spmi_build_segments(sp_tensor *A, hipStream_t st);
-constexpr int kSpmiStreamThreads = 128;
-constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * 8;     // stored entries per block of the stream kernel
+sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
+#ifndef SPMI_ST
+#define SPMI_ST 128
+#endif
+#ifndef SPMI_PER
+#define SPMI_PER 8
+#endif
+constexpr int kSpmiStreamThreads = SPMI_ST;                  // threads per block of the stream kernel
+constexpr int kSpmiStreamPer = SPMI_PER;                     // stored entries per thread (even)
+constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // stored entries per block
 
 // ---- matmul.hip --------------------------------------------------------------------------
 sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
