@@ -28,7 +28,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per product (bytes) from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # same counter reads for the plain copy kernel of known size); the summaries are under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", 32): None,
+    ("cfg2", 32, 3): 378.9e6,      # profiles/spmv_segmented_cfg2_w32_hbm_traffic.txt
+    ("cfg2", 32, 2): 1447.0e6,     # profiles/spmv_stream_cfg2_w32_hbm_traffic.txt
+    ("cfg3", 32, 0): 9.45e9,       # profiles/spmm_rows_cfg3_w32_hbm_traffic.txt
 }
 
 
@@ -203,6 +205,7 @@ def main():
                    nnz, N, reps, cpu_s),
                "gflops": flops / cpu_s / 1e9}
 
+    kk = 0
     if spmv:
         kk = args.kernel
         if kk == 0:
@@ -229,7 +232,7 @@ def main():
         "config": {"workload": wl, "regime": "cold: rotating over %d copies of A, B, C (%.2f GB)" % (
             ncopies, ncopies * abytes / 1e9), "kernel": kernel_name, "accumulate": acc, "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((name, wbits)),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get((name, wbits, kk if spmv else 0)),
                      "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
         "cpu_baseline": cpu,
         "gflops": flops / (ms_cold * 1e-3) / 1e9,
