@@ -26,7 +26,7 @@ typedef enum {
     SP_ERR_RANK = 2,         /* rank outside [1, SP_MAX_RANK], or a rank-2 call on another rank */
     SP_ERR_LEVEL_TYPE = 3,   /* level type not dense/compressed; pos/crd asked of a dense level */
     SP_ERR_ORDERING = 4,     /* dimOrdering is not a permutation                            */
-    SP_ERR_WIDTH = 5,        /* width not in {0,32,64}, or a stored value does not fit it   */
+    SP_ERR_WIDTH = 5,        /* width not in {0,8,16,32,64}, or a stored value does not fit */
     SP_ERR_COORD_RANGE = 6,  /* a coordinate is < 0 or >= its dimension's size              */
     SP_ERR_DUPLICATE = 7,    /* the same coordinate tuple appears twice                     */
     SP_ERR_SHAPE = 8,        /* negative size, ld < N, and the like                         */
@@ -55,8 +55,9 @@ typedef void (*sp_free_fn)(void *ptr, void *ctx);
  * widths).  levelTypes: HOST array of `rank` entries, by level.  dimOrdering: HOST array,
  * dimOrdering[l] = dimension stored at level l (the result list of the paper's affine map
  * read left to right); NULL = identity.  posWidth / crdWidth: bits of the pos and crd
- * arrays; 0 means "native" = 64; this library stores signed integers and supports 32 and
- * 64.  Checks run in the order rank, level type, ordering, width; *out is written only
+ * arrays: 8, 16, 32, 64, or 0 = "native" = 64; the arrays hold signed integers.  (For 8 and
+ * 16 bits the tensor keeps 32-bit working copies for its kernels next to the narrow arrays
+ * it hands out.)  Checks run in the order rank, level type, ordering, width; *out is written only
  * on SP_OK and is released with sp_encoding_free. */
 sp_status sp_encode(int rank, const sp_level_type *levelTypes, const int *dimOrdering,
                     int posWidth, int crdWidth, sp_encoding **out);
@@ -107,7 +108,7 @@ typedef struct {
     int rank;
     int levelTypes[SP_MAX_RANK];
     int dimOrdering[SP_MAX_RANK];
-    int posWidth, crdWidth;          /* resolved: 32 or 64 */
+    int posWidth, crdWidth;          /* resolved: 8, 16, 32 or 64 */
     int dtype;
     int64_t shape[SP_MAX_RANK];
     int64_t nnz;                     /* entries given to sp_pack */

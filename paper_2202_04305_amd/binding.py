@@ -187,7 +187,7 @@ def sp_matmul(A, B, C, accumulate=False, N=None, ldb=None, ldc=None):
     return C
 
 
-_INT = {32: torch.int32, 64: torch.int64}
+_INT = {8: torch.int8, 16: torch.int16, 32: torch.int32, 64: torch.int64}
 
 
 def sp_tensor_info(A):

@@ -41,7 +41,7 @@ extern "C" sp_status sp_encode(int rank, const sp_level_type *levelTypes, const 
         if (d < 0 || d >= rank || seen[d]) return SP_ERR_ORDERING;
         seen[d] = true;
     }
-    auto ok = [](int w) { return w == 0 || w == 32 || w == 64; };
+    auto ok = [](int w) { return w == 0 || w == 8 || w == 16 || w == 32 || w == 64; };
     if (!ok(posWidth) || !ok(crdWidth)) return SP_ERR_WIDTH;
     sp_encoding *e = new sp_encoding();
     memset(e, 0, sizeof(*e));
@@ -50,8 +50,10 @@ extern "C" sp_status sp_encode(int rank, const sp_level_type *levelTypes, const 
         e->lt[l] = (int)levelTypes[l];
         e->perm[l] = dimOrdering ? dimOrdering[l] : l;
     }
-    e->pw = posWidth ? posWidth : 64;
-    e->cw = crdWidth ? crdWidth : 64;
+    e->pw_store = posWidth ? posWidth : 64;
+    e->cw_store = crdWidth ? crdWidth : 64;
+    e->pw = e->pw_store < 32 ? 32 : e->pw_store;       // 8- and 16-bit arrays are kept next to 32-bit working copies
+    e->cw = e->cw_store < 32 ? 32 : e->cw_store;
     *out = e;
     return SP_OK;
 }
@@ -63,7 +65,7 @@ extern "C" sp_status sp_pos(const sp_tensor *t, int level, const void **ptr, int
     if (!t || !ptr || !len) return SP_ERR_NULL;
     if (level < 0 || level >= t->enc.rank) return SP_ERR_RANK;
     if (t->enc.lt[level] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
-    *ptr = t->pos[level];
+    *ptr = t->pos_narrow[level] ? t->pos_narrow[level] : t->pos[level];
     *len = t->npos[level];
     return SP_OK;
 }
@@ -73,7 +75,7 @@ extern "C" sp_status sp_crd(const sp_tensor *t, int level, const void **ptr, int
     if (!t || !ptr || !len) return SP_ERR_NULL;
     if (level < 0 || level >= t->enc.rank) return SP_ERR_RANK;
     if (t->enc.lt[level] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
-    *ptr = t->crd[level];
+    *ptr = t->crd_narrow[level] ? t->crd_narrow[level] : t->crd[level];
     *len = t->ncrd[level];
     return SP_OK;
 }
@@ -96,10 +98,10 @@ extern "C" sp_status sp_tensor_info(const sp_tensor *t, sp_info *info)
         info->levelTypes[l] = t->enc.lt[l];
         info->dimOrdering[l] = t->enc.perm[l];
         info->shape[l] = t->shape[l];
-        if (t->enc.lt[l] == SP_COMPRESSED) bytes += t->npos[l] * (t->enc.pw / 8) + t->ncrd[l] * (t->enc.cw / 8);
+        if (t->enc.lt[l] == SP_COMPRESSED) bytes += t->npos[l] * (t->enc.pw_store / 8) + t->ncrd[l] * (t->enc.cw_store / 8);
     }
-    info->posWidth = t->enc.pw;
-    info->crdWidth = t->enc.cw;
+    info->posWidth = t->enc.pw_store;
+    info->crdWidth = t->enc.cw_store;
     info->dtype = t->dtype;
     info->nnz = t->nnz;
     info->nvalues = t->nvalues;
@@ -173,6 +175,7 @@ static sp_status build_transposed(sp_tensor *A, hipStream_t st)
         SP_TRY(sp_unpack(A, coords, vals, st));
         sp_encoding enc = A->enc;
         enc.perm[0] = 0; enc.perm[1] = 1;
+        enc.pw_store = enc.pw; enc.cw_store = enc.cw;     // an internal copy: working widths only
         const int64_t *ccoords[2] = {rows, cols};
         s = sp_pack(&enc, A->shape, A->nvalues, ccoords, vals, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, st, &T);
     }
@@ -193,7 +196,7 @@ extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int
     if (N == 0 || m == 0) return SP_OK;
     if (!C || (!B && n > 0)) return SP_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
-    if (A->enc.lt[1] != SP_COMPRESSED) return SP_ERR_UNSUPPORTED;     // dense innermost level: no GPU kernel yet
+    if (A->enc.lt[1] != SP_COMPRESSED) return spmi_matmul_dense_inner(A, B, N, ldb, C, ldc, accumulate, st);
     if (A->enc.perm[0] == 0) return spmi_matmul_rowmajor(A, B, N, ldb, C, ldc, accumulate, st);
     int mode = A->tune_csc ? A->tune_csc : 2;
     if (mode == 1) return spmi_matmul_colmajor_scatter(A, B, N, ldb, C, ldc, accumulate, st);

@@ -273,6 +273,59 @@ __global__ __launch_bounds__(kThreads) void spmm_scatter_kernel(const PT *__rest
     }
 }
 
+// ---- dense innermost level (the paper's compressed-then-dense format of Section 4.1 and the all-dense one) ----
+// Row-major: stored row q holds all `n` values of matrix row rowid[q] (or q).  A block per stored row: lanes
+// stride over the row with coalesced loads, LG lanes side by side per tile of CG columns of B.
+template <typename CT, typename VT, int CG>
+__global__ __launch_bounds__(kThreads) void dense_rows_kernel(const VT *__restrict__ val, const CT *__restrict__ rowid, int64_t n,
+                                                              const VT *__restrict__ B, int64_t N, int64_t ldb, VT *__restrict__ C,
+                                                              int64_t ldc, int accumulate)
+{
+    constexpr int KS = kThreads / CG;                 // entries of the row handled side by side
+    __shared__ VT red[kThreads];
+    const int64_t q = blockIdx.x;
+    const int jl = threadIdx.x % CG, kl = threadIdx.x / CG;
+    const VT *__restrict__ vrow = val + q * n;
+    const int64_t row = rowid ? (int64_t)rowid[q] : q;
+    for (int64_t j0 = 0; j0 < N; j0 += CG) {
+        const int64_t j = j0 + jl;
+        VT acc = 0;
+        if (j < N)
+            for (int64_t k = kl; k < n; k += KS) acc += vrow[k] * B[k * ldb + j];
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        for (int stride = kThreads / 2; stride >= CG; stride >>= 1) {
+            if (threadIdx.x < stride) red[threadIdx.x] += red[threadIdx.x + stride];
+            __syncthreads();
+        }
+        if (kl == 0 && j < N) C[row * ldc + j] = accumulate ? C[row * ldc + j] + red[jl] : red[jl];
+        __syncthreads();
+    }
+}
+
+// Column-major: stored column q holds all `m` values of matrix column colid[q] (or q): C[i, j] = sum_q V[q, i] * B[col_q, j].
+// A thread per (i, j); every row of C is written, so no zero fill is needed and no atomics either.
+template <typename CT, typename VT, int CG>
+__global__ __launch_bounds__(kThreads) void dense_cols_kernel(const VT *__restrict__ val, const CT *__restrict__ colid, int64_t ncols,
+                                                              int64_t m, const VT *__restrict__ B, int64_t N, int64_t ldb,
+                                                              VT *__restrict__ C, int64_t ldc, int accumulate)
+{
+    constexpr int IS = kThreads / CG;                 // rows of C per block
+    const int jl = threadIdx.x % CG;
+    const int64_t i = (int64_t)blockIdx.x * IS + threadIdx.x / CG;
+    if (i >= m) return;
+    for (int64_t j0 = 0; j0 < N; j0 += CG) {
+        const int64_t j = j0 + jl;
+        if (j >= N) continue;
+        VT acc = accumulate ? C[i * ldc + j] : (VT)0;
+        for (int64_t q = 0; q < ncols; ++q) {
+            const int64_t k = colid ? (int64_t)colid[q] : q;
+            acc += val[q * m + i] * B[k * ldb + j];
+        }
+        C[i * ldc + j] = acc;
+    }
+}
+
 inline unsigned grid_for(int64_t n, int64_t per_block) { return (unsigned)(n > 0 ? ceil_div(n, per_block) : 1); }
 
 template <typename PT, typename CT, typename VT>
@@ -407,6 +460,39 @@ sp_status scatter_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT 
     return SP_OK;
 }
 
+template <typename PT, typename CT, typename VT>
+sp_status dense_inner_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
+{
+    const VT *val = (const VT *)A->values;
+    const bool outer_compressed = A->enc.lt[0] == SP_COMPRESSED;
+    const CT *outer = outer_compressed ? (const CT *)A->crd[0] : nullptr;
+    const int64_t nstored = outer_compressed ? A->ncrd[0] : A->size[0];        // stored rows (row-major) or columns
+    const int64_t inner = A->size[1];
+    const int64_t m = A->shape[0];
+    const bool rowmajor = A->enc.perm[0] == 0;
+    if (rowmajor && outer_compressed && !accumulate) SP_TRY((zero_c<PT, CT, VT>(C, m, N, ldc, st)));
+    if (!rowmajor && nstored == 0 && !accumulate) return zero_c<PT, CT, VT>(C, m, N, ldc, st);
+    if (nstored == 0 || inner == 0) return SP_OK;
+    if (rowmajor && nstored > 0x7fffffff) return SP_ERR_TOO_LARGE;
+    sp_prof_scope prof(A, st);
+#define SPMI_DENSE(CG)                                                                                                        \
+    do {                                                                                                                      \
+        if (rowmajor)                                                                                                         \
+            hipLaunchKernelGGL((dense_rows_kernel<CT, VT, CG>), dim3((unsigned)nstored), dim3(kThreads), 0, st, val, outer, inner, B, N, \
+                               ldb, C, ldc, accumulate);                                                                       \
+        else                                                                                                                  \
+            hipLaunchKernelGGL((dense_cols_kernel<CT, VT, CG>), dim3(grid_for(m, kThreads / CG)), dim3(kThreads), 0, st, val, outer,    \
+                               nstored, inner, B, N, ldb, C, ldc, accumulate);                                                 \
+    } while (0)
+    if (N > 32) SPMI_DENSE(64);
+    else if (N > 8) SPMI_DENSE(32);
+    else if (N > 1) SPMI_DENSE(8);
+    else SPMI_DENSE(1);
+#undef SPMI_DENSE
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
 }  // namespace
 
 #define SPMI_DISPATCH_TYPES(FN, A, ...)                                                             \
@@ -435,4 +521,10 @@ sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_
                                        int accumulate, hipStream_t st)
 {
     SPMI_DISPATCH_TYPES(scatter_t, A);
+}
+
+sp_status spmi_matmul_dense_inner(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
+                                  hipStream_t st)
+{
+    SPMI_DISPATCH_TYPES(dense_inner_t, A);
 }

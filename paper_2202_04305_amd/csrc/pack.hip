@@ -260,17 +260,27 @@ __global__ __launch_bounds__(kThreads) void gather_values_kernel(const VT *__res
     vout[position ? position[e] : (uint64_t)e] = vin[idx[e]];
 }
 
+// longest pos segment: grid-stride maximum per thread, wave and block reduction, one atomic per block
 template <typename PT>
 __global__ __launch_bounds__(kThreads) void max_segment_kernel(const PT *__restrict__ pos, int64_t nseg, unsigned long long *__restrict__ out)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    unsigned long long len = (i < nseg) ? (unsigned long long)(pos[i + 1] - pos[i]) : 0ull;
+    __shared__ unsigned long long wmax[kThreads / 64];
+    unsigned long long len = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nseg; i += (int64_t)gridDim.x * kThreads) {
+        const unsigned long long l = (unsigned long long)(pos[i + 1] - pos[i]);
+        len = l > len ? l : len;
+    }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
-        unsigned long long o = __shfl_xor(len, d, 64);
+        const unsigned long long o = __shfl_xor(len, d, 64);
         len = o > len ? o : len;
     }
-    if ((threadIdx.x & 63) == 0 && len) atomicMax(out, len);
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = len;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) len = wmax[w] > len ? wmax[w] : len;
+        if (len) atomicMax(out, len);
+    }
 }
 
 // start[b] = row holding stored entry b*T (largest r with pos[r] <= b*T); block 0 starts at row 0 and the
@@ -290,6 +300,13 @@ __global__ __launch_bounds__(kThreads) void rowblocks_kernel(const PT *__restric
         if ((int64_t)pos[mid] <= target) lo = mid; else hi = mid;
     }
     start[b] = (int32_t)lo;
+}
+
+template <typename ST, typename DT>
+__global__ __launch_bounds__(kThreads) void narrow_kernel(const ST *__restrict__ src, int64_t n, DT *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) dst[i] = (DT)src[i];
 }
 
 __global__ __launch_bounds__(kThreads) void virtual_rows_kernel(int64_t *__restrict__ rows, const int64_t *__restrict__ cols, int64_t n,
@@ -457,6 +474,7 @@ sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_byt
                            A->nvalues, shift, nrows);
         SP_HIP(hipGetLastError());
         sp_encoding enc = A->enc;
+        enc.pw_store = enc.pw; enc.cw_store = enc.cw;     // an internal copy: working widths only
         const int64_t shape[2] = {panels * nrows, n};
         const int64_t *ccoords[2] = {rows, cols};
         SP_TRY(sp_pack(&enc, shape, A->nvalues, ccoords, vals, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, st, &S));
@@ -472,7 +490,10 @@ sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_byt
 static void release_tensor_arrays(sp_tensor *t)
 {
     sp_mem mem{t->alloc, t->free_, t->ctx};
-    for (int l = 0; l < SP_MAX_RANK; ++l) { mem.put(t->pos[l]); mem.put(t->crd[l]); t->pos[l] = t->crd[l] = nullptr; }
+    for (int l = 0; l < SP_MAX_RANK; ++l) {
+        mem.put(t->pos[l]); mem.put(t->crd[l]); mem.put(t->pos_narrow[l]); mem.put(t->crd_narrow[l]);
+        t->pos[l] = t->crd[l] = t->pos_narrow[l] = t->crd_narrow[l] = nullptr;
+    }
     mem.put(t->values); t->values = nullptr;
     mem.put(t->rowblocks.start); t->rowblocks.start = nullptr;
     mem.put(t->rowblocks.carry); t->rowblocks.carry = nullptr;
@@ -534,7 +555,10 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
     }
     if (zero_dim && nnz > 0) { delete t; return SP_ERR_COORD_RANGE; }
     for (int l = 0; l < rank; ++l)
-        if (enc->lt[l] == SP_COMPRESSED && enc->cw == 32 && t->size[l] - 1 > INT32_MAX) { delete t; return SP_ERR_WIDTH; }
+        if (enc->lt[l] == SP_COMPRESSED && enc->cw_store < 64 && t->size[l] - 1 > (((int64_t)1 << (enc->cw_store - 1)) - 1)) {
+            delete t;
+            return SP_ERR_WIDTH;
+        }
     int key_bits = 0;
     while (key_bits < 63 && ((unsigned __int128)1 << key_bits) < prod) ++key_bits;
 
@@ -605,7 +629,7 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                         nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
                         child_excl = child;
                     }
-                    if (enc->pw == 32 && nchild > INT32_MAX) { fail(SP_ERR_WIDTH); break; }
+                    if (enc->pw_store < 64 && nchild > (((int64_t)1 << (enc->pw_store - 1)) - 1)) { fail(SP_ERR_WIDTH); break; }
                     const size_t pbytes = pad16((size_t)(P + 1) * (enc->pw / 8));
                     const size_t cbytes = pad16((size_t)(nchild > 0 ? nchild : 1) * (enc->cw / 8));
                     t->pos[l] = mem.get(pbytes);
@@ -626,6 +650,33 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                     P = nchild;
                 }
                 if (nnz > 0) { pin = pout; which ^= 1; }
+            }
+            if (status != SP_OK) break;
+
+            // 8- and 16-bit widths: the arrays handed out are narrowed copies of the 32-bit working arrays
+            for (int l = 0; l < rank && status == SP_OK; ++l) {
+                if (enc->lt[l] != SP_COMPRESSED) continue;
+                if (enc->pw_store < 32) {
+                    t->pos_narrow[l] = mem.get(pad16((size_t)t->npos[l] * (enc->pw_store / 8)));
+                    if (!t->pos_narrow[l]) { fail(SP_ERR_ALLOC); break; }
+                    if (enc->pw_store == 8)
+                        hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
+                                           (const int32_t *)t->pos[l], t->npos[l], (int8_t *)t->pos_narrow[l]);
+                    else
+                        hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
+                                           (const int32_t *)t->pos[l], t->npos[l], (int16_t *)t->pos_narrow[l]);
+                }
+                if (enc->cw_store < 32) {
+                    t->crd_narrow[l] = mem.get(pad16((size_t)(t->ncrd[l] > 0 ? t->ncrd[l] : 1) * (enc->cw_store / 8)));
+                    if (!t->crd_narrow[l]) { fail(SP_ERR_ALLOC); break; }
+                    if (enc->cw_store == 8)
+                        hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
+                                           (const int32_t *)t->crd[l], t->ncrd[l], (int8_t *)t->crd_narrow[l]);
+                    else
+                        hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
+                                           (const int32_t *)t->crd[l], t->ncrd[l], (int16_t *)t->crd_narrow[l]);
+                }
+                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
             }
             if (status != SP_OK) break;
 
@@ -650,10 +701,11 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
             if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
                 unsigned long long *mx = (unsigned long long *)(flags + 4);
                 const int64_t nseg = t->npos[rank - 1] - 1;
+                const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
                 if (enc->pw == 32)
-                    hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(blocks_for(nseg)), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
+                    hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
                 else
-                    hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(blocks_for(nseg)), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
+                    hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
                 if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
                 unsigned long long hmx = 0;
                 if (hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }

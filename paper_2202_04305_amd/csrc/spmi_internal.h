@@ -12,7 +12,8 @@ struct sp_encoding {
     int rank;
     int lt[SP_MAX_RANK];
     int perm[SP_MAX_RANK];   // perm[l] = dimension stored at level l
-    int pw, cw;              // resolved widths: 32 or 64
+    int pw, cw;              // widths the kernels work on: 32 or 64
+    int pw_store, cw_store;  // widths asked for (8, 16, 32, 64): what sp_pos / sp_crd hand out
 };
 
 // Row blocks of the streaming SpMV: block b covers rows [rowblk[b], rowblk[b+1]) of the
@@ -42,6 +43,8 @@ struct sp_tensor {
     int64_t npos[SP_MAX_RANK];
     void *crd[SP_MAX_RANK];
     int64_t ncrd[SP_MAX_RANK];
+    void *pos_narrow[SP_MAX_RANK];   // DEVICE copies in 8 or 16 bits when such a width was asked for, else nullptr
+    void *crd_narrow[SP_MAX_RANK];
     void *values;
     int64_t nvalues;
     int64_t nnz;
@@ -135,5 +138,7 @@ constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // sto
 // ---- matmul.hip --------------------------------------------------------------------------
 sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                                void *C, int64_t ldc, int accumulate, hipStream_t st);
+sp_status spmi_matmul_dense_inner(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc,
+                                  int accumulate, hipStream_t st);
 sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                                        void *C, int64_t ldc, int accumulate, hipStream_t st);

@@ -30,7 +30,9 @@ def test_encode_validation_order():
     assert code([0, 2]) == 3
     assert code([0, 1], [0, 0]) == 4
     assert code([0, 1], [0, 2]) == 4
-    assert code([0, 1], None, 16, 32) == 5       # 8/16-bit arrays: not on the GPU path
+    assert code([0, 1], None, 12, 32) == 5
+    assert code([0, 1], None, 32, 128) == 5
+    assert sp.sp_encode([0, 1], None, 8, 16).rank == 2
     assert code([0, 2], [0, 0], 12, 12) == 3     # level type before ordering before width
     assert code([0, 1], [0, 0], 12, 12) == 4
     e = sp.sp_encode([1, 1], [1, 0], 32, 64)

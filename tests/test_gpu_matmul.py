@@ -217,23 +217,76 @@ def test_column_major(mode, lt, N):
 
 
 def test_result_is_independent_of_the_encoding():
-    """The paper's own check (Section 5.2): the same COO under every supported annotation gives the same C."""
-    w = W.cfg2_powerlaw_csr(5000, 4000, cap=1500)
-    B = w.dense_operand(6)
+    """The paper's own check (Section 5.2): the same COO under every annotation (4 level-type pairs x 2 orderings x
+    widths) gives the same C."""
+    w = W.cfg2_powerlaw_csr(1500, 1200, cap=700)
+    for N in (1, 6, 40):
+        B = w.dense_operand(N)
+        ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B)
+        C0 = prng.uniform_pm1(5, 9, w.shape[0] * N).reshape(-1, N)
+        refa, maga = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B, True, C0)
+        for lt in [(0, 0), (0, 1), (1, 0), (1, 1)]:
+            for order in [(0, 1), (1, 0)]:
+                for pw, cw in [(32, 32), (64, 32), (32, 64), (0, 0)]:
+                    say("case encoding", lt, order, pw, cw, "N", N)
+                    A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
+                    C = torch.full((w.shape[0], N), float("nan"), dtype=torch.float64, device=DEV)
+                    sp.sp_matmul(A, dev(B), C)
+                    assert_product_close(C, ref, mag, np.float64, str((lt, order, pw, cw)))
+                    C = dev(C0)
+                    sp.sp_matmul(A, dev(B), C, accumulate=True)
+                    assert_product_close(C, refa, maga, np.float64, str((lt, order, pw, cw)) + " accumulate")
+
+
+def test_sparse_state_space_200_configurations():
+    """Section 5.2's loop: 4 level-type pairs x 2 orderings x 5 pointer widths x 5 index widths = 200 ways of
+    storing one matrix; every one must hold the checker's arrays bit for bit and give the same SpMM result."""
+    from gpu_util import assert_storage_equal
+    w = W.uniform_random(40, 50, 100)
+    B = w.dense_operand(3)
     ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B)
-    for lt in [(0, 1), (1, 1)]:
+    Bd = dev(B)
+    count = 0
+    for lt in [(0, 0), (0, 1), (1, 0), (1, 1)]:
         for order in [(0, 1), (1, 0)]:
-            for pw, cw in [(32, 32), (64, 32), (32, 64), (0, 0)]:
-                say("case encoding", lt, order, pw, cw)
-                A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
-                C = torch.empty((w.shape[0], 6), dtype=torch.float64, device=DEV)
-                sp.sp_matmul(A, dev(B), C)
-                assert_product_close(C, ref, mag, np.float64, str((lt, order, pw, cw)))
-    for lt in [(1, 0), (0, 0)]:
-        A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], w.vals)
+            for pw in [0, 8, 16, 32, 64]:
+                for cw in [0, 8, 16, 32, 64]:
+                    A = gpu_pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw)
+                    assert_storage_equal(A, oracle.pack(lt, order, w.shape, [w.rows, w.cols], w.vals, pw, cw))
+                    C = torch.full((40, 3), float("nan"), dtype=torch.float64, device=DEV)
+                    sp.sp_matmul(A, Bd, C)
+                    assert_product_close(C, ref, mag, np.float64, str((lt, order, pw, cw)))
+                    count += 1
+    assert count == 200
+    say("case width overflow")
+    w2 = W.uniform_random(40, 300, 200)
+    for pw, cw in [(8, 32), (32, 8)]:          # 200 entries do not fit a signed 8-bit pointer; column 299 no 8-bit index
         with pytest.raises(sp.SpError) as e:
-            sp.sp_matmul(A, dev(B), torch.empty((w.shape[0], 6), dtype=torch.float64, device=DEV))
-        assert e.value.code == oracle.ERR_UNSUPPORTED
+            gpu_pack((0, 1), None, w2.shape, [w2.rows, w2.cols], w2.vals, pw, cw)
+        assert e.value.code == oracle.ERR_WIDTH
+    A = gpu_pack((1, 1), (1, 0), w2.shape, [w2.rows, w2.cols], w2.vals, 16, 16)     # CSC-like, 16-bit: transposed copy inside
+    C = torch.empty((40, 2), dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, dev(w2.dense_operand(2)), C)
+    ref2, mag2 = oracle.matmul_coo(w2.shape, w2.rows, w2.cols, w2.vals, w2.dense_operand(2))
+    assert_product_close(C, ref2, mag2, np.float64, "16-bit DCSC")
+
+
+def test_dense_inner_levels_row_band_shape():
+    """The paper's SpMV experiment shape (Section 6.2): the first rows full, the rest empty, under CSR, DCSR and the
+    compressed-then-dense format, f64 and f32."""
+    for dtype in (np.float64, np.float32):
+        w = W.row_band(2048, 100)
+        w.vals = w.vals.astype(dtype)
+        w.dtype = dtype
+        x = w.dense_operand(1)
+        ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
+        for lt in [(0, 1), (1, 1), (1, 0), (0, 0)]:
+            say("case row band", lt, dtype.__name__)
+            A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], w.vals)
+            y = torch.full((w.shape[0],), float("nan"), dtype=A.dtype, device=DEV)
+            sp.sp_matmul(A, dev(x[:, 0].copy()), y)
+            assert_product_close(y, ref, mag, dtype, "row band " + str(lt))
+            assert torch.all(y[100:] == 0)
 
 
 def test_degenerate_products():
