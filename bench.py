@@ -46,6 +46,8 @@ def make_workload(name, small):
         return W.cfg4_hypersparse_dcsr(1 << 19, 1 << 19) if small else W.cfg4_hypersparse_dcsr()
     if name == "cfg5":
         return W.cfg5_zipf_csc_spmm(1 << 17, 1 << 17) if small else W.cfg5_zipf_csc_spmm()
+    if name == "rowband":
+        return W.row_band(1024 if small else 65536, 100 if small else 1000)
     raise SystemExit("unknown workload " + name)
 
 
@@ -54,6 +56,7 @@ DESCRIPTIONS = {
     "cfg2": "cfg2: CSR SpMV y=A.x, A %(m)dx%(n)d f64, lognormal row lengths (mean 16, sigma 1.5, clip [1,20000]), %(nnz)d stored entries",
     "cfg3": "cfg3: CSR SpMM C=A.B, A as cfg2 (%(m)dx%(n)d f64, %(nnz)d stored entries), B %(n)dx%(N)d f64 row-major",
     "cfg4": "cfg4: DCSR SpMV y=A.x, A %(m)dx%(n)d f64, 1%% of rows stored, 32 entries each, %(nnz)d stored entries",
+    "rowband": "row band (the shape of the paper's SpMV experiment, Section 6.2): SpMV y=A.x, A %(m)dx%(n)d f64, the first rows full, the rest empty, %(nnz)d stored entries",
     "cfg5": "cfg5: CSC SpMM C=A.B, A %(m)dx%(n)d f32, rank-size Zipf(1.2) column lengths capped at 50000, %(nnz)d stored entries, B %(n)dx%(N)d f32",
 }
 
@@ -73,7 +76,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband"])
+    ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense"],
+                    help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table)")
     ap.add_argument("--copies", type=int, default=0, help="independent copies of A, B, C rotated through (cold regime)")
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
@@ -110,6 +115,9 @@ def main():
     rows_d = torch.from_numpy(w.rows).to(dev)
     cols_d = torch.from_numpy(w.cols).to(dev)
     vals_d = torch.from_numpy(w.vals).to(dev)
+    if args.format:
+        w.level_types = {"csr": (0, 1), "dcsr": (1, 1), "cdr": (1, 0), "dense": (0, 0)}[args.format]
+        w.dim_ordering = (0, 1)
     enc = sp.sp_encode(w.level_types, w.dim_ordering, wbits, wbits)
     copies = []
     pack_ms = []
@@ -212,10 +220,14 @@ def main():
             kk = 3 if (name == "cfg2" and not args.small) else 2
         kernel_name = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
                        3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel"}[kk]
+        if w.level_types[1] == 0:
+            kernel_name = "dense_rows_kernel"
     else:
         kernel_name = "spmm_rows_kernel" if (name == "cfg3" or args.csc_mode != 1) else "spmm_scatter_kernel"
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits
+    if args.format:
+        wl += ", stored as " + args.format
     out = {
         "metric": "effective HBM GB/s for f64 CSR SpMV/SpMM (algorithmic bytes / time per product)",
         "value": abytes / (ms_cold * 1e-3) / 1e9,

@@ -326,6 +326,58 @@ __global__ __launch_bounds__(kThreads) void dense_cols_kernel(const VT *__restri
     }
 }
 
+// Row-major dense innermost level, one column (y = A.x with fully stored rows): pure streaming.  Block (c, q) takes
+// 2048 consecutive values of stored row q with 16-byte loads and leaves one partial sum; a second small kernel adds
+// the partial sums of a row in order (deterministic) and writes y.
+constexpr int kDenseChunk = kThreads * 8;
+template <typename VT>
+__global__ __launch_bounds__(kThreads) void dense_rows_spmv_partial_kernel(const VT *__restrict__ val, int64_t n, const VT *__restrict__ x,
+                                                                           int64_t nchunks, VT *__restrict__ partial)
+{
+    constexpr int V = 16 / sizeof(VT);                // elements per 16-byte load
+    typedef VT vec_t __attribute__((ext_vector_type(V)));
+    __shared__ VT wsum[kThreads / 64];
+    const int64_t q = blockIdx.y, c = blockIdx.x;
+    const int64_t k0 = c * kDenseChunk;
+    const VT *__restrict__ vrow = val + q * n;
+    VT acc = 0;
+    if (k0 + kDenseChunk <= n) {
+        vec_t a[8 / V], b[8 / V];
+#pragma unroll
+        for (int t = 0; t < 8 / V; ++t) {
+            const int64_t k = k0 + (int64_t)(t * kThreads + threadIdx.x) * V;
+            a[t] = *(const vec_t *)(vrow + k);
+            b[t] = *(const vec_t *)(x + k);
+        }
+#pragma unroll
+        for (int t = 0; t < 8 / V; ++t)
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc += a[t][e] * b[t][e];
+    } else {
+        for (int64_t k = k0 + threadIdx.x; k < n; k += kThreads) acc += vrow[k] * x[k];
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        VT tot = 0;
+        for (int w = 0; w < kThreads / 64; ++w) tot += wsum[w];
+        partial[q * nchunks + c] = tot;
+    }
+}
+
+template <typename CT, typename VT>
+__global__ __launch_bounds__(kThreads) void dense_rows_spmv_finish_kernel(const VT *__restrict__ partial, int64_t nchunks, const CT *__restrict__ rowid,
+                                                                          int64_t nstored, VT *__restrict__ y, int64_t ldc, int accumulate)
+{
+    const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= nstored) return;
+    VT sum = 0;
+    for (int64_t c = 0; c < nchunks; ++c) sum += partial[q * nchunks + c];
+    const int64_t row = rowid ? (int64_t)rowid[q] : q;
+    y[row * ldc] = accumulate ? y[row * ldc] + sum : sum;
+}
+
 inline unsigned grid_for(int64_t n, int64_t per_block) { return (unsigned)(n > 0 ? ceil_div(n, per_block) : 1); }
 
 template <typename PT, typename CT, typename VT>
@@ -344,9 +396,16 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     const PT *pos = (const PT *)A->pos[1];
     const CT *crd = (const CT *)A->crd[1];
     const VT *val = (const VT *)A->values;
-    const bool dcsr = A->enc.lt[0] == SP_COMPRESSED;
+    // "dcsr": only stored rows are visited, through a row-id list: a compressed outer level, or a dense one that is
+    // mostly empty and therefore carries the list of its non-empty rows
+    bool dcsr = A->enc.lt[0] == SP_COMPRESSED;
     const CT *rowid = dcsr ? (const CT *)A->crd[0] : nullptr;
-    const int64_t nrows = A->npos[1] - 1;              // stored rows
+    int64_t nrows = A->npos[1] - 1;              // stored rows
+    const sp_rowblocks *rowblocks = &A->rowblocks;
+    if (!dcsr && A->nz_pos) {
+        dcsr = true;
+        pos = (const PT *)A->nz_pos; rowid = (const CT *)A->nz_rowid; nrows = A->nz_rows; rowblocks = &A->nz_rowblocks;
+    }
     const int64_t m = A->shape[0];
     const int64_t nnz = A->ncrd[1];
     if (dcsr && !accumulate) SP_TRY((zero_c<PT, CT, VT>(C, m, N, ldc, st)));   // rows that are not stored become zero
@@ -354,12 +413,12 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     if (N == 1) {
         int kernel = A->tune_spmv;
         if (kernel == 0) {
-            kernel = (A->rowblocks.start && nnz >= 8 * kStreamT) ? 2 : 1;
+            kernel = (rowblocks->start && nnz >= 8 * kStreamT) ? 2 : 1;
             // a large x with a large matrix: gather from L2-sized column panels instead
             if (kernel == 2 && !dcsr && nnz >= ((int64_t)1 << 22) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) kernel = 3;
         }
         if (kernel == 3) {
-            if (dcsr) return SP_ERR_UNSUPPORTED;
+            if (A->enc.lt[0] == SP_COMPRESSED) return SP_ERR_UNSUPPORTED;
             sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(A), sizeof(VT), kSpmvSliceBytes, st);   // first use: builds, allocates, synchronises
             if (sb == SP_ERR_UNSUPPORTED && A->tune_spmv == 0) kernel = 2;
             else if (sb != SP_OK) return sb;
@@ -386,18 +445,18 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             SP_HIP(hipGetLastError());
             return SP_OK;
         }
-        if (kernel == 2 && !A->rowblocks.start) return SP_ERR_UNSUPPORTED;
+        if (kernel == 2 && !rowblocks->start) return SP_ERR_UNSUPPORTED;
         if (kernel == 2) {
-            const int64_t nb = A->rowblocks.nblocks;
+            const int64_t nb = rowblocks->nblocks;
             {
             sp_prof_scope prof(A, st);
             hipLaunchKernelGGL((spmv_stream_kernel<PT, CT, VT>), dim3((unsigned)nb), dim3(kST), 0, st, pos, crd, val, rowid,
-                               (const int32_t *)A->rowblocks.start, nrows, nnz, B, ldb, C, ldc, (VT *)A->rowblocks.carry, accumulate);
+                               (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)rowblocks->carry, accumulate);
             }
             SP_HIP(hipGetLastError());
             if (nb > 1) {
                 hipLaunchKernelGGL((spmv_stream_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads)), dim3(kThreads), 0, st, pos,
-                                   rowid, (const int32_t *)A->rowblocks.start, nb, (const VT *)A->rowblocks.carry, C, ldc);
+                                   rowid, (const int32_t *)rowblocks->start, nb, (const VT *)rowblocks->carry, C, ldc);
                 SP_HIP(hipGetLastError());
             }
             return SP_OK;
@@ -475,6 +534,28 @@ sp_status dense_inner_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb,
     if (nstored == 0 || inner == 0) return SP_OK;
     if (rowmajor && nstored > 0x7fffffff) return SP_ERR_TOO_LARGE;
     sp_prof_scope prof(A, st);
+    constexpr int64_t V = 16 / sizeof(VT);
+    if (rowmajor && N == 1 && ldb == 1 && inner >= kDenseChunk && inner % V == 0 && nstored <= 65535 &&
+        (uintptr_t)B % 16 == 0 && (uintptr_t)val % 16 == 0) {
+        // fully stored rows times a vector: the streaming path (16-byte loads need every row 16-byte aligned)
+        const int64_t nchunks = ceil_div(inner, kDenseChunk);
+        const size_t need = (size_t)(nstored * nchunks) * sizeof(VT);
+        sp_tensor *At = const_cast<sp_tensor *>(A);
+        if (At->dense_partial_bytes < need) {
+            sp_mem mem{A->alloc, A->free_, A->ctx};
+            if (At->dense_partial) { SP_HIP(hipStreamSynchronize(st)); mem.put(At->dense_partial); At->dense_partial = nullptr; At->dense_partial_bytes = 0; }
+            At->dense_partial = mem.get((need + 255) & ~(size_t)255);
+            if (!At->dense_partial) return SP_ERR_ALLOC;
+            At->dense_partial_bytes = need;
+        }
+        hipLaunchKernelGGL((dense_rows_spmv_partial_kernel<VT>), dim3((unsigned)nchunks, (unsigned)nstored), dim3(kThreads), 0, st, val, inner,
+                           B, nchunks, (VT *)A->dense_partial);
+        SP_HIP(hipGetLastError());
+        hipLaunchKernelGGL((dense_rows_spmv_finish_kernel<CT, VT>), dim3(grid_for(nstored, kThreads)), dim3(kThreads), 0, st,
+                           (const VT *)A->dense_partial, nchunks, outer, nstored, C, ldc, accumulate);
+        SP_HIP(hipGetLastError());
+        return SP_OK;
+    }
 #define SPMI_DENSE(CG)                                                                                                        \
     do {                                                                                                                      \
         if (rowmajor)                                                                                                         \

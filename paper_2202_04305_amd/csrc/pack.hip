@@ -407,29 +407,93 @@ sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int k
 
 static size_t pad16(size_t b) { return (b + 15) & ~(size_t)15; }
 
+static sp_status build_rowblocks_for(const void *pos, int pw, int64_t nrows, int64_t nnz, const sp_mem &mem, sp_rowblocks *out,
+                                     hipStream_t st)
+{
+    if (nrows >= ((int64_t)1 << 31) - 1) return SP_OK;    // the streaming kernel keeps 32-bit row ids
+    const int64_t nb = ceil_div(nnz, kSpmiStreamT);
+    if (nb == 0) return SP_OK;
+    void *start = mem.get(pad16((size_t)(nb + 1) * 4));
+    void *carry = mem.get(pad16((size_t)nb * 8));
+    if (!start || !carry) { mem.put(start); mem.put(carry); return SP_ERR_ALLOC; }
+    if (pw == 32)
+        hipLaunchKernelGGL(rowblocks_kernel<int32_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int32_t *)pos, nrows, nb,
+                           kSpmiStreamT, (int32_t *)start);
+    else
+        hipLaunchKernelGGL(rowblocks_kernel<int64_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int64_t *)pos, nrows, nb,
+                           kSpmiStreamT, (int32_t *)start);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { mem.put(start); mem.put(carry); g_last_hip_error = (int)e; return SP_ERR_HIP; }
+    out->start = start;
+    out->carry = carry;
+    out->nblocks = nb;
+    return SP_OK;
+}
+
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st)
 {
     // only for rank 2 with a compressed innermost level
     if (t->enc.rank != 2 || t->enc.lt[1] != SP_COMPRESSED || t->rowblocks.start) return SP_OK;
-    const int64_t nrows = t->npos[1] - 1;
-    if (nrows >= ((int64_t)1 << 31) - 1) return SP_OK;    // the streaming kernel keeps 32-bit row ids
-    const int64_t nb = ceil_div(t->ncrd[1], kSpmiStreamT);
-    if (nb == 0) return SP_OK;
     sp_mem mem{t->alloc, t->free_, t->ctx};
-    void *start = mem.get(pad16((size_t)(nb + 1) * 4));
-    void *carry = mem.get(pad16((size_t)nb * 8));
-    if (!start || !carry) { mem.put(start); mem.put(carry); return SP_ERR_ALLOC; }
+    return build_rowblocks_for(t->pos[1], t->enc.pw, t->npos[1] - 1, t->ncrd[1], mem, &t->rowblocks, st);
+}
+
+// A dense outer level with mostly empty segments (a CSR matrix with mostly empty rows): keep the list of the
+// non-empty ones and their pos entries, so that the product kernels visit stored rows only, as they do for a
+// compressed outer level.  crd and values are shared with the tensor's own arrays.
+template <typename PT>
+__global__ __launch_bounds__(kThreads) void mark_nonempty_kernel(const PT *__restrict__ pos, int64_t nrows, uint32_t *__restrict__ mark)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r < nrows) mark[r] = pos[r + 1] > pos[r] ? 1u : 0u;
+}
+
+template <typename PT, typename CT>
+__global__ __launch_bounds__(kThreads) void compact_rows_kernel(const PT *__restrict__ pos, int64_t nrows, const uint32_t *__restrict__ excl,
+                                                                int64_t nz_rows, CT *__restrict__ nz_rowid, PT *__restrict__ nz_pos)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r > nrows) return;
+    if (r == nrows) { nz_pos[nz_rows] = pos[nrows]; return; }
+    if (pos[r + 1] > pos[r]) { nz_rowid[excl[r]] = (CT)r; nz_pos[excl[r]] = pos[r]; }
+}
+
+static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
+{
+    if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
+    const int64_t nrows = t->npos[1] - 1;
+    if (nrows < 4096 || nrows >= ((int64_t)1 << 31) - 1 || t->ncrd[1] == 0) return SP_OK;
+    uint32_t *mark = (uint32_t *)tmp.get((size_t)nrows * 4);
+    if (!mark) return SP_ERR_ALLOC;
     if (t->enc.pw == 32)
-        hipLaunchKernelGGL(rowblocks_kernel<int32_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, nb,
-                           kSpmiStreamT, (int32_t *)start);
+        hipLaunchKernelGGL(mark_nonempty_kernel<int32_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, mark);
     else
-        hipLaunchKernelGGL(rowblocks_kernel<int64_t>, dim3(blocks_for(nb + 1)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, nb,
-                           kSpmiStreamT, (int32_t *)start);
+        hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
+    SP_HIP(hipGetLastError());
+    uint32_t last_mark = 0, last_excl = 0;
+    SP_HIP(hipMemcpyAsync(&last_mark, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    SP_TRY(spmi_exclusive_scan(mark, nrows, 32, tmp, st));
+    SP_HIP(hipMemcpyAsync(&last_excl, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    SP_HIP(hipStreamSynchronize(st));
+    const int64_t nz = (int64_t)last_excl + last_mark;
+    if (nz * 2 > nrows) return SP_OK;                      // not worth it: at least half of the rows hold something
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    const int ps = t->enc.pw / 8, cs = t->enc.cw / 8;
+    void *rid = mem.get(pad16((size_t)(nz > 0 ? nz : 1) * cs));
+    void *npos = mem.get(pad16((size_t)(nz + 1) * ps));
+    if (!rid || !npos) { mem.put(rid); mem.put(npos); return SP_ERR_ALLOC; }
+#define SPMI_COMPACT(PT, CT)                                                                                                  \
+    hipLaunchKernelGGL((compact_rows_kernel<PT, CT>), dim3(blocks_for(nrows + 1)), dim3(kThreads), 0, st, (const PT *)t->pos[1], nrows, \
+                       (const uint32_t *)mark, nz, (CT *)rid, (PT *)npos)
+    if (t->enc.pw == 32 && t->enc.cw == 32) SPMI_COMPACT(int32_t, int32_t);
+    else if (t->enc.pw == 32) SPMI_COMPACT(int32_t, int64_t);
+    else if (t->enc.cw == 32) SPMI_COMPACT(int64_t, int32_t);
+    else SPMI_COMPACT(int64_t, int64_t);
+#undef SPMI_COMPACT
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { mem.put(start); mem.put(carry); g_last_hip_error = (int)e; return SP_ERR_HIP; }
-    t->rowblocks.start = start;
-    t->rowblocks.carry = carry;
-    t->rowblocks.nblocks = nb;
+    sp_status s = e == hipSuccess ? build_rowblocks_for(npos, t->enc.pw, nz, t->ncrd[1], mem, &t->nz_rowblocks, st) : SP_ERR_HIP;
+    if (s != SP_OK) { mem.put(rid); mem.put(npos); if (e != hipSuccess) g_last_hip_error = (int)e; return s; }
+    t->nz_rowid = rid; t->nz_pos = npos; t->nz_rows = nz;
     return SP_OK;
 }
 
@@ -497,6 +561,9 @@ static void release_tensor_arrays(sp_tensor *t)
     mem.put(t->values); t->values = nullptr;
     mem.put(t->rowblocks.start); t->rowblocks.start = nullptr;
     mem.put(t->rowblocks.carry); t->rowblocks.carry = nullptr;
+    mem.put(t->dense_partial); t->dense_partial = nullptr; t->dense_partial_bytes = 0;
+    mem.put(t->nz_rowid); mem.put(t->nz_pos); mem.put(t->nz_rowblocks.start); mem.put(t->nz_rowblocks.carry);
+    t->nz_rowid = t->nz_pos = t->nz_rowblocks.start = t->nz_rowblocks.carry = nullptr;
 }
 
 extern "C" void sp_tensor_free(sp_tensor *t)
@@ -712,6 +779,7 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                 t->max_segment = (int64_t)hmx;
             }
             if (fail(spmi_build_rowblocks(t, st)) != SP_OK) break;
+            if (fail(build_nonempty_rows(t, tmp, st)) != SP_OK) break;
             if (hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
         } while (0);
         if (status == SP_ERR_HIP && g_last_hip_error == 0) g_last_hip_error = (int)hipGetLastError();

@@ -54,8 +54,14 @@ struct sp_tensor {
     void *ctx;
     // derived, built lazily by sp_matmul or eagerly by sp_pack
     sp_rowblocks rowblocks;
+    // a dense outer level whose segments are mostly empty: ids and pos entries of the non-empty ones (else nullptr)
+    void *nz_rowid, *nz_pos;
+    int64_t nz_rows;
+    sp_rowblocks nz_rowblocks;
     sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
     sp_segments *segments;           // owned, built on first use
+    void *dense_partial;             // DEVICE scratch of the dense-row SpMV (per-chunk partial sums), grown on demand
+    size_t dense_partial_bytes;
     int tune_spmv, tune_csc, tune_spmm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned

@@ -151,6 +151,29 @@ def test_csr_spmm(N, dtype):
     assert_product_close(C, ref, mag, dtype, "spmm accumulate")
 
 
+@pytest.mark.parametrize("N", [1, 5])
+@pytest.mark.parametrize("widths", [(32, 32), (64, 32)])
+def test_csr_with_mostly_empty_rows(N, widths):
+    """A CSR tensor whose rows are mostly empty is multiplied through the list of its non-empty rows; the accessors
+    still hand out the plain CSR arrays."""
+    w = W.cfg4_hypersparse_dcsr(1 << 16, 1 << 16, frac=0.03, per_row=50)
+    say("case csr mostly empty", N, widths, w.stats)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, *widths)
+    ref = oracle.pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, *widths)
+    from gpu_util import assert_storage_equal
+    assert_storage_equal(A, ref)
+    B = w.dense_operand(N)
+    for kernel in (0, 1, 2):
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+        C, cref, mag = run(A, w, B)
+        assert_product_close(C, cref, mag, w.dtype, "mostly empty csr")
+        C0 = prng.uniform_pm1(5, 11, w.shape[0] * N).reshape(-1, N)
+        C, cref, mag = run(A, w, B, accumulate=True, C0=C0)
+        assert_product_close(C, cref, mag, w.dtype, "mostly empty csr accumulate")
+        untouched = torch.from_numpy(np.bincount(w.rows, minlength=w.shape[0]) == 0).to(DEV)
+        assert torch.equal(C[untouched], dev(C0)[untouched])
+
+
 def test_leading_dimensions():
     w = W.cfg3_powerlaw_csr_spmm(3000, 2000, N=5, cap=500)
     A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
@@ -274,8 +297,8 @@ def test_sparse_state_space_200_configurations():
 def test_dense_inner_levels_row_band_shape():
     """The paper's SpMV experiment shape (Section 6.2): the first rows full, the rest empty, under CSR, DCSR and the
     compressed-then-dense format, f64 and f32."""
-    for dtype in (np.float64, np.float32):
-        w = W.row_band(2048, 100)
+    for dtype, n, band in ((np.float64, 2048, 100), (np.float32, 2048, 100), (np.float64, 5000, 37), (np.float32, 6148, 3)):
+        w = W.row_band(n, band)
         w.vals = w.vals.astype(dtype)
         w.dtype = dtype
         x = w.dense_operand(1)
@@ -286,7 +309,12 @@ def test_dense_inner_levels_row_band_shape():
             y = torch.full((w.shape[0],), float("nan"), dtype=A.dtype, device=DEV)
             sp.sp_matmul(A, dev(x[:, 0].copy()), y)
             assert_product_close(y, ref, mag, dtype, "row band " + str(lt))
-            assert torch.all(y[100:] == 0)
+            assert torch.all(y[band:] == 0)
+            y0 = prng.uniform_pm1(5, 10, w.shape[0], dtype=dtype)
+            refa, maga = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x, True, y0)
+            ya = dev(y0)
+            sp.sp_matmul(A, dev(x[:, 0].copy()), ya, accumulate=True)
+            assert_product_close(ya, refa, maga, dtype, "row band accumulate " + str(lt))
 
 
 def test_degenerate_products():
