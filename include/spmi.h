@@ -104,6 +104,12 @@ sp_status sp_values(const sp_tensor *t, const void **ptr, int64_t *len);
  * values length; values: DEVICE array of the tensor's dtype, same length.  Asynchronous. */
 sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream);
 
+/* The paper's convert operation between two sparse encodings (Section 4.2: conversions go through an intermediate
+ * coordinate scheme, which avoids one converter per pair of formats).  Every stored position of `from` (explicit and
+ * padding zeros included) becomes a stored entry of the new tensor, which has `from`'s shape, dtype and allocator and
+ * the encoding `to` (same rank).  Synchronises like sp_pack; `from` is left untouched. */
+sp_status sp_convert(const sp_tensor *from, const sp_encoding *to, void *stream, sp_tensor **out);
+
 typedef struct {
     int rank;
     int levelTypes[SP_MAX_RANK];

@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_convert", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -68,6 +68,8 @@ def load_library():
     L.sp_values.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
     L.sp_unpack.restype = ci
     L.sp_unpack.argtypes = [vp, vp, vp, vp]
+    L.sp_convert.restype = ci
+    L.sp_convert.argtypes = [vp, vp, vp, ctypes.POINTER(vp)]
     L.sp_tensor_info.restype = ci
     L.sp_tensor_info.argtypes = [vp, ctypes.POINTER(SpInfo)]
     L.sp_tensor_tune.restype = ci
@@ -237,6 +239,13 @@ def sp_unpack(A):
     carr = (ctypes.c_void_p * info.rank)(*[c.data_ptr() for c in coords])
     _check(L.sp_unpack(A._h, carr, vals.data_ptr(), _stream_ptr()), "in sp_unpack")
     return coords, vals
+
+
+def sp_convert(A, enc):
+    """A new tensor with A's stored entries under another encoding."""
+    h = ctypes.c_void_p()
+    _check(load_library().sp_convert(A._h, enc._h, _stream_ptr(), ctypes.byref(h)), "in sp_convert")
+    return Tensor(h, A._allocator, A.dtype, A.device)
 
 
 def sp_tensor_tune(A, key, value):

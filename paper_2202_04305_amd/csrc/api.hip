@@ -186,6 +186,28 @@ static sp_status build_transposed(sp_tensor *A, hipStream_t st)
     return SP_OK;
 }
 
+extern "C" sp_status sp_convert(const sp_tensor *from, const sp_encoding *to, void *stream, sp_tensor **out)
+{
+    if (!from || !to || !out) return SP_ERR_NULL;
+    *out = nullptr;
+    if (to->rank != from->enc.rank) return SP_ERR_RANK;
+    hipStream_t st = (hipStream_t)stream;
+    sp_mem mem{from->alloc, from->free_, from->ctx};
+    sp_scratch tmp(mem);
+    const int rank = from->enc.rank;
+    const size_t cnt = (size_t)(from->nvalues > 0 ? from->nvalues : 1);
+    int64_t *coords[SP_MAX_RANK] = {nullptr};
+    for (int d = 0; d < rank; ++d) {
+        coords[d] = (int64_t *)tmp.get(cnt * 8);
+        if (!coords[d]) return SP_ERR_ALLOC;
+    }
+    void *vals = tmp.get(cnt * 8);
+    if (!vals) return SP_ERR_ALLOC;
+    SP_TRY(sp_unpack(from, coords, vals, st));
+    return sp_pack(to, from->shape, from->nvalues, (const int64_t *const *)coords, vals, (sp_dtype)from->dtype, from->alloc,
+                   from->free_, from->ctx, st, out);
+}
+
 extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
                                void *stream)
 {

@@ -140,3 +140,23 @@ def test_input_errors_match_the_checker():
     # the library must still work after errors
     A = gpu_pack((0, 1), None, w.shape, [w.rows, w.cols], w.vals)
     assert_storage_equal(A, oracle.pack((0, 1), None, w.shape, [w.rows, w.cols], w.vals, 32, 32))
+
+
+def test_convert_between_encodings():
+    """The paper's convert operation (Section 4.2), through the coordinate scheme: the result must be what the checker
+    packs from the checker's own unpacking of the source, for every pair of rank-2 encodings."""
+    w = W.cfg2_powerlaw_csr(300, 200, cap=80)
+    encs = [(lt, order) for lt in itertools.product([0, 1], repeat=2) for order in [(0, 1), (1, 0)]]
+    for (lt_a, ord_a) in encs:
+        A = gpu_pack(lt_a, ord_a, w.shape, [w.rows, w.cols], w.vals, 32, 64)
+        ref_a = oracle.pack(lt_a, ord_a, w.shape, [w.rows, w.cols], w.vals, 32, 64)
+        (r, c), v = ref_a.unpack()
+        for (lt_b, ord_b) in encs:
+            say("case convert", lt_a, ord_a, "->", lt_b, ord_b)
+            Bt = sp.sp_convert(A, sp.sp_encode(lt_b, ord_b, 64, 32))
+            assert_storage_equal(Bt, oracle.pack(lt_b, ord_b, w.shape, [r, c], v, 64, 32))
+    # the allocator is shared by source and result: both stay usable after the other is freed
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    Bt = sp.sp_convert(A, sp.sp_encode((1, 1), (1, 0), 32, 32))
+    A.free()
+    assert_storage_equal(Bt, oracle.pack((1, 1), (1, 0), w.shape, [w.rows, w.cols], w.vals, 32, 32))
