@@ -413,7 +413,9 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     if (N == 1) {
         int kernel = A->tune_spmv;
         if (kernel == 0) {
-            kernel = (rowblocks->start && nnz >= 8 * kStreamT) ? 2 : 1;
+            // small and even (no row beyond one wave's stride): one launch of the rows kernel beats stream + fix-up
+            const bool small_even = nnz < ((int64_t)1 << 18) && A->max_segment <= 64;
+            kernel = (rowblocks->start && nnz >= 8 * kStreamT && !small_even) ? 2 : 1;
             // a large x with a large matrix: gather from L2-sized column panels instead
             if (kernel == 2 && !dcsr && nnz >= ((int64_t)1 << 22) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) kernel = 3;
         }
