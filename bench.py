@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
     ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
+    ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads")
     ap.add_argument("--accumulate", action="store_true", help="C += A.B instead of C = A.B")
     ap.add_argument("--small", action="store_true", help="scaled-down matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
@@ -130,6 +131,7 @@ def main():
         pack_ms.append(e0.elapsed_time(e1))
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, args.kernel)
         sp.sp_tensor_tune(A, sp.SP_TUNE_CSC_MODE, args.csc_mode)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, args.spmm_kernel)
         Bd = torch.from_numpy(B_host[:, 0].copy() if spmv else B_host).to(dev)
         Cd = torch.zeros(m if spmv else (m, N), dtype=tdtype, device=dev)
         copies.append((A, Bd, Cd))
@@ -217,13 +219,14 @@ def main():
     if spmv:
         kk = args.kernel
         if kk == 0:
-            kk = 3 if (name == "cfg2" and not args.small) else 2
+            kk = 3 if (name == "cfg2" and not args.small) else (1 if name == "cfg1" else 2)
         kernel_name = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
                        3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel"}[kk]
         if w.level_types[1] == 0:
             kernel_name = "dense_rows_kernel"
     else:
-        kernel_name = "spmm_rows_kernel" if (name == "cfg3" or args.csc_mode != 1) else "spmm_scatter_kernel"
+        kernel_name = "spmm_scatter_kernel" if (name == "cfg5" and args.csc_mode == 1) else (
+            "spmm_rows_kernel" if args.spmm_kernel == 1 else "spmm_rows_vec_kernel")
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits
     if args.format:

@@ -130,7 +130,9 @@ extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
         if (t->transposed) return sp_tensor_tune(t->transposed, key, value);
         return SP_OK;
     case SP_TUNE_SPMM_KERNEL:
-        if (value != 0) return SP_ERR_UNSUPPORTED;      // one SpMM kernel so far
+        if (value < 0 || value > 2) return SP_ERR_UNSUPPORTED;
+        t->tune_spmm = (int)value;
+        if (t->transposed) t->transposed->tune_spmm = (int)value;
         return SP_OK;
     }
     return SP_ERR_UNSUPPORTED;
@@ -181,6 +183,7 @@ static sp_status build_transposed(sp_tensor *A, hipStream_t st)
     }
     if (s != SP_OK) return s;
     T->tune_spmv = A->tune_spmv;
+    T->tune_spmm = A->tune_spmm;
     if (A->profile) (void)sp_tensor_tune(T, SP_TUNE_PROFILE, 1);
     A->transposed = T;
     return SP_OK;

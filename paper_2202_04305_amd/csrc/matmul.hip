@@ -250,6 +250,72 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(const PT *__restric
     }
 }
 
+// SpMM with 16-byte loads: LR lanes cover one row of B (N = LR * 16 / sizeof(VT) columns), 64 / LR stored entries of
+// the row of A side by side, two gathers in flight per lane.  Needs N a multiple of the vector width and B, C rows
+// 16-byte aligned; the dispatch checks it.
+template <typename PT, typename CT, typename VT, int LR>
+__global__ __launch_bounds__(kThreads) void spmm_rows_vec_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                                 const VT *__restrict__ val, const CT *__restrict__ rowid, int64_t nrows,
+                                                                 const VT *__restrict__ B, int64_t ldb, VT *__restrict__ C, int64_t ldc,
+                                                                 int accumulate)
+{
+    constexpr int V = 16 / sizeof(VT);
+    constexpr int S = 64 / LR;
+    typedef VT vec_t __attribute__((ext_vector_type(V)));
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= nrows) return;                           // whole wave
+    const int jl = lane % LR, sl = lane / LR;
+    const int64_t a = (int64_t)pos[r], b = (int64_t)pos[r + 1];
+    constexpr int U = S >= 4 ? 2 : 4;                 // row gathers in flight per lane (measured: 8 to 16 entries per step)
+    vec_t accu[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) accu[u] = (vec_t)(0);
+    int64_t p = a + sl;
+    for (; p + (U - 1) * S < b; p += U * S) {
+        int64_t k[U];
+        VT v[U];
+        vec_t bv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { k[u] = (int64_t)crd[p + u * S]; v[u] = val[p + u * S]; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) bv[u] = *(const vec_t *)(B + k[u] * ldb + jl * V);
+#pragma unroll
+        for (int u = 0; u < U; ++u) accu[u] += v[u] * bv[u];
+    }
+    if (p < b) {                                      // the last, partial step: same batch of loads, clamped and masked
+        int64_t k[U];
+        VT v[U];
+        vec_t bv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t pp = p + u * S;
+            const bool in = pp < b;
+            k[u] = (int64_t)crd[in ? pp : p];
+            v[u] = in ? val[pp] : (VT)0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) bv[u] = *(const vec_t *)(B + k[u] * ldb + jl * V);
+#pragma unroll
+        for (int u = 0; u < U; ++u) accu[u] += v[u] * bv[u];
+    }
+    vec_t acc0 = accu[0];
+#pragma unroll
+    for (int u = 1; u < U; ++u) acc0 += accu[u];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        VT x = acc0[e];
+#pragma unroll
+        for (int d = 32; d >= LR; d >>= 1) x += __shfl_xor(x, d, 64);
+        acc0[e] = x;
+    }
+    if (sl == 0) {
+        const int64_t row = rowid ? (int64_t)rowid[r] : r;
+        vec_t *dst = (vec_t *)(C + row * ldc + jl * V);
+        *dst = accumulate ? *dst + acc0 : acc0;
+    }
+}
+
 // ---- column-major storage: a wave per stored column, atomic adds into C ------------------
 template <typename PT, typename CT, typename VT, int CG>
 __global__ __launch_bounds__(kThreads) void spmm_scatter_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
@@ -482,6 +548,25 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     // segmented copy, so that the slice of B a launch gathers from fits the 256 MB last-level cache.  Re-reading and
     // re-writing C once per panel costs more than the gathers save: 3.17 ms against 2.94 ms.
     sp_prof_scope prof(A, st);
+    {
+        constexpr int64_t V = 16 / sizeof(VT);
+        const int64_t lr = N / V;
+        const bool fits = N % V == 0 && (lr == 8 || lr == 16 || lr == 32 || lr == 64) && ldb % V == 0 && ldc % V == 0 &&
+                          (uintptr_t)B % 16 == 0 && (uintptr_t)C % 16 == 0;
+        if (A->tune_spmm == 2 && !fits) return SP_ERR_UNSUPPORTED;
+        if (fits && A->tune_spmm != 1) {
+#define SPMI_SPMM_VEC(LR)                                                                                                     \
+    hipLaunchKernelGGL((spmm_rows_vec_kernel<PT, CT, VT, LR>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, \
+                       crd, val, rowid, nrows, B, ldb, C, ldc, accumulate)
+            if (lr == 8) SPMI_SPMM_VEC(8);
+            else if (lr == 16) SPMI_SPMM_VEC(16);
+            else if (lr == 32) SPMI_SPMM_VEC(32);
+            else SPMI_SPMM_VEC(64);
+#undef SPMI_SPMM_VEC
+            SP_HIP(hipGetLastError());
+            return SP_OK;
+        }
+    }
 #define SPMI_SPMM(CG)                                                                                                         \
     hipLaunchKernelGGL((spmm_rows_kernel<PT, CT, VT, CG>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, crd, \
                        val, rowid, nrows, B, N, ldb, C, ldc, accumulate)
