@@ -128,7 +128,7 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *   SP_TUNE_SPMV_KERNEL: 0 = automatic, 1 = lanes-per-row, 2 = streaming over the CSR arrays (bit-reproducible),
  *                        3 = streaming over a column-segmented copy (built and kept on first use; CSR only)
  *   SP_TUNE_SPMM_KERNEL: 0 = automatic, 1 = one column per lane, 2 = 16 bytes of a row of B per lane (needs N a multiple
- *                        of 16 / element size with 8..64 such vectors per row, and B, C rows 16-byte aligned)
+ *                        of 16 / element size with 1, 2, 4, ... 64 such vectors per row, and B, C rows 16-byte aligned)
  *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
 enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4 };

@@ -551,14 +551,17 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     {
         constexpr int64_t V = 16 / sizeof(VT);
         const int64_t lr = N / V;
-        const bool fits = N % V == 0 && (lr == 8 || lr == 16 || lr == 32 || lr == 64) && ldb % V == 0 && ldc % V == 0 &&
+        const bool fits = N % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && ldb % V == 0 && ldc % V == 0 &&
                           (uintptr_t)B % 16 == 0 && (uintptr_t)C % 16 == 0;
         if (A->tune_spmm == 2 && !fits) return SP_ERR_UNSUPPORTED;
         if (fits && A->tune_spmm != 1) {
 #define SPMI_SPMM_VEC(LR)                                                                                                     \
     hipLaunchKernelGGL((spmm_rows_vec_kernel<PT, CT, VT, LR>), dim3(grid_for(nrows, kThreads / 64)), dim3(kThreads), 0, st, pos, \
                        crd, val, rowid, nrows, B, ldb, C, ldc, accumulate)
-            if (lr == 8) SPMI_SPMM_VEC(8);
+            if (lr == 1) SPMI_SPMM_VEC(1);
+            else if (lr == 2) SPMI_SPMM_VEC(2);
+            else if (lr == 4) SPMI_SPMM_VEC(4);
+            else if (lr == 8) SPMI_SPMM_VEC(8);
             else if (lr == 16) SPMI_SPMM_VEC(16);
             else if (lr == 32) SPMI_SPMM_VEC(32);
             else SPMI_SPMM_VEC(64);

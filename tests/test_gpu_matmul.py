@@ -135,7 +135,7 @@ def test_spmv_is_reproducible_run_to_run(kernel):
     assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[0], ys[2])
 
 
-@pytest.mark.parametrize("N", [2, 3, 8, 16, 32, 64, 70, 128])
+@pytest.mark.parametrize("N", [2, 3, 4, 8, 16, 32, 64, 70, 128])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_csr_spmm(N, dtype):
     w = W.cfg3_powerlaw_csr_spmm(6000, 5000, N=N, cap=2500)
@@ -149,7 +149,7 @@ def test_csr_spmm(N, dtype):
     sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 1)          # one column per lane, whatever N is
     C, ref, mag = run(A, w, B)
     assert_product_close(C, ref, mag, dtype, "spmm, one column per lane")
-    vec_ok = (N * np.dtype(dtype).itemsize) % 16 == 0 and (N * np.dtype(dtype).itemsize) // 16 in (8, 16, 32, 64)
+    vec_ok = (N * np.dtype(dtype).itemsize) % 16 == 0 and (N * np.dtype(dtype).itemsize) // 16 in (1, 2, 4, 8, 16, 32, 64)
     sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 2)          # 16-byte loads: only some N
     if vec_ok:
         C, ref, mag = run(A, w, B)
