@@ -55,6 +55,8 @@ def lib():
         L.oracle_matmul_coo.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, i64, i64, vp, i64, ci, vp]
         L.oracle_matmul_storage.restype = ci
         L.oracle_matmul_storage.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
+        L.oracle_sddmm_coo.restype = ci
+        L.oracle_sddmm_coo.argtypes = [i64, i64, i64, i64, vp, vp, vp, ci, vp, i64, vp, i64, vp, vp]
         L.oracle_matmul_coo_f64seq.restype = ci
         L.oracle_matmul_coo_f64seq.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64]
         _lib = L
@@ -190,3 +192,23 @@ def matmul_coo_f64seq(shape, rows, cols, vals, B):
     C = np.zeros((m, N), dtype=np.float64)
     lib().oracle_matmul_coo_f64seq(m, rows.shape[0], _ptr(rows), _ptr(cols), _ptr(vals), _ptr(B), N, N, _ptr(C), N)
     return C
+
+
+def sddmm_coo(shape, rows, cols, svals, A, B):
+    """(X, mag) per COO triple, caller's order: X = s * (A @ B)[i, j] with A (m, K) and B (K, n) row-major."""
+    m, n = shape
+    svals = np.ascontiguousarray(svals)
+    dt = _dt(svals.dtype)
+    A = np.ascontiguousarray(A, dtype=svals.dtype)
+    B = np.ascontiguousarray(B, dtype=svals.dtype)
+    K = A.shape[1]
+    assert A.shape == (m, K) and B.shape == (K, n)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    cols = np.ascontiguousarray(cols, dtype=np.int64)
+    X = np.zeros(rows.shape[0], dtype=svals.dtype)
+    mag = np.zeros(rows.shape[0], dtype=np.float64)
+    st = lib().oracle_sddmm_coo(m, n, K, rows.shape[0], _ptr(rows), _ptr(cols), _ptr(svals), dt, _ptr(A), max(K, 1), _ptr(B),
+                                max(n, 1), _ptr(X), _ptr(mag))
+    if st != OK:
+        raise OracleError(st)
+    return X, mag

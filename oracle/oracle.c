@@ -365,3 +365,30 @@ int oracle_matmul_coo_f64seq(int64_t m, int64_t nnz, const int64_t *rows, const 
         for (int64_t j = 0; j < N; ++j) C[rows[e] * ldc + j] += vals[e] * B[cols[e] * ldb + j];
     return OR_OK;
 }
+
+/* Sampled dense-dense product (Section 6.2, last experiment): X[i,j] = S[i,j] * sum_k A[i,k] * B[k,j], computed
+ * only where S stores an entry.  S comes as COO triples; X and mag are per triple, in the caller's order.  A is m x K
+ * and B is K x n, both row-major.  Inner sums in long double, rounded once; mag = |s| * sum_k |A[i,k] * B[k,j]|. */
+int oracle_sddmm_coo(int64_t m, int64_t n, int64_t K, int64_t nnz, const int64_t *rows, const int64_t *cols,
+                     const void *svals, int dtype, const void *A, int64_t lda, const void *B, int64_t ldb,
+                     void *X, double *mag)
+{
+    if (nnz > 0 && (!rows || !cols || !svals || !X)) return OR_ERR_NULL;
+    if (K > 0 && nnz > 0 && (!A || !B)) return OR_ERR_NULL;
+    if (m < 0 || n < 0 || K < 0 || lda < K || ldb < n) return OR_ERR_SHAPE;
+    for (int64_t e = 0; e < nnz; ++e)
+        if (rows[e] < 0 || rows[e] >= m || cols[e] < 0 || cols[e] >= n) return OR_ERR_COORD_RANGE;
+    for (int64_t e = 0; e < nnz; ++e) {
+        const int64_t i = rows[e], j = cols[e];
+        long double acc = 0.0L, macc = 0.0L;
+        for (int64_t k = 0; k < K; ++k) {
+            const long double prod = (long double)ldB(A, dtype, i * lda + k) * (long double)ldB(B, dtype, k * ldb + j);
+            acc += prod;
+            macc += fabsl(prod);
+        }
+        const long double s = (long double)ldB(svals, dtype, e);
+        if (dtype == OR_F32) ((float *)X)[e] = (float)(s * acc); else ((double *)X)[e] = (double)(s * acc);
+        if (mag) mag[e] = (double)(fabsl(s) * macc);
+    }
+    return OR_OK;
+}
