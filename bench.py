@@ -46,6 +46,11 @@ def make_workload(name, small):
         return W.cfg4_hypersparse_dcsr(1 << 19, 1 << 19) if small else W.cfg4_hypersparse_dcsr()
     if name == "cfg5":
         return W.cfg5_zipf_csc_spmm(1 << 17, 1 << 17) if small else W.cfg5_zipf_csc_spmm()
+    if name == "sddmm":
+        w = W.cfg2_powerlaw_csr(1 << 16, 1 << 16) if small else W.cfg2_powerlaw_csr()
+        w.N = 64
+        w.name = "sddmm"
+        return w
     if name == "rowband":
         return W.row_band(1024 if small else 65536, 100 if small else 1000)
     raise SystemExit("unknown workload " + name)
@@ -57,6 +62,7 @@ DESCRIPTIONS = {
     "cfg3": "cfg3: CSR SpMM C=A.B, A as cfg2 (%(m)dx%(n)d f64, %(nnz)d stored entries), B %(n)dx%(N)d f64 row-major",
     "cfg4": "cfg4: DCSR SpMV y=A.x, A %(m)dx%(n)d f64, 1%% of rows stored, 32 entries each, %(nnz)d stored entries",
     "rowband": "row band (the shape of the paper's SpMV experiment, Section 6.2): SpMV y=A.x, A %(m)dx%(n)d f64, the first rows full, the rest empty, %(nnz)d stored entries",
+    "sddmm": "SDDMM X=S.*(A.B) (Section 6.2), S = the cfg2 matrix (%(m)dx%(n)d f64 CSR, %(nnz)d stored entries), A %(m)dx%(N)d, B %(N)dx%(n)d f64 row-major (transposed inside every call)",
     "cfg5": "cfg5: CSC SpMM C=A.B, A %(m)dx%(n)d f32, rank-size Zipf(1.2) column lengths capped at 50000, %(nnz)d stored entries, B %(n)dx%(N)d f32",
 }
 
@@ -65,6 +71,8 @@ def algorithmic_bytes(name, w, info, N, vbytes):
     """Compulsory bytes of one product: the storage arrays once, B (x) once, C (y) once."""
     m, n = w.shape
     a = int(info.storageBytes)
+    if name == "sddmm":
+        return a + m * N * vbytes + n * N * vbytes + w.nnz * vbytes      # S, A, B once, X once
     if name == "cfg4":
         # x: only the touched elements; y: the whole vector is written in overwrite mode
         return a + w.nnz * vbytes + m * vbytes
@@ -76,7 +84,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm"])
     ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense"],
                     help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table)")
     ap.add_argument("--copies", type=int, default=0, help="independent copies of A, B, C rotated through (cold regime)")
@@ -107,7 +115,8 @@ def main():
     wbits = args.width
     tdtype = torch.float64 if w.dtype == np.float64 else torch.float32
     vbytes = 8 if w.dtype == np.float64 else 4
-    B_host = w.dense_operand(N)
+    sddmm = name == "sddmm"
+    B_host = w.dense_operand(N)              # n x N; for SDDMM its transpose is the K x n operand B
     spmv = N == 1
     steps = args.steps or (300 if spmv else 20)
     warmup = args.warmup or (30 if spmv else 3)
@@ -132,8 +141,14 @@ def main():
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, args.kernel)
         sp.sp_tensor_tune(A, sp.SP_TUNE_CSC_MODE, args.csc_mode)
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, args.spmm_kernel)
-        Bd = torch.from_numpy(B_host[:, 0].copy() if spmv else B_host).to(dev)
-        Cd = torch.zeros(m if spmv else (m, N), dtype=tdtype, device=dev)
+        if sddmm:
+            from gen import prng
+            A_host = prng.uniform_pm1(w.seed, 8, m * N, dtype=w.dtype).reshape(m, N)
+            Bd = (torch.from_numpy(A_host).to(dev), torch.from_numpy(np.ascontiguousarray(B_host.T)).to(dev))
+            Cd = torch.zeros(nnz, dtype=tdtype, device=dev)
+        else:
+            Bd = torch.from_numpy(B_host[:, 0].copy() if spmv else B_host).to(dev)
+            Cd = torch.zeros(m if spmv else (m, N), dtype=tdtype, device=dev)
         copies.append((A, Bd, Cd))
     del rows_d, cols_d, vals_d
     info = sp.sp_tensor_info(copies[0][0])
@@ -144,7 +159,10 @@ def main():
     def run_steps(k, rotate=True):
         for i in range(k):
             A, Bd, Cd = copies[i % len(copies)] if rotate else copies[0]
-            sp.sp_matmul(A, Bd, Cd, accumulate=acc)
+            if sddmm:
+                sp.sp_sddmm(A, Bd[0], Bd[1], Cd)
+            else:
+                sp.sp_matmul(A, Bd, Cd, accumulate=acc)
 
     def timed(k, rotate=True):
         torch.cuda.synchronize()
@@ -176,7 +194,8 @@ def main():
     # one clean product on copy 0 for the parity check below
     if acc:
         copies[0][2].zero_()
-    sp.sp_matmul(copies[0][0], copies[0][1], copies[0][2], accumulate=False)
+    if not sddmm:
+        sp.sp_matmul(copies[0][0], copies[0][1], copies[0][2], accumulate=False)
     torch.cuda.synchronize()
 
     # yardstick: plain copy kernel on 1 GiB (read + write = 2 GiB of traffic)
@@ -204,10 +223,18 @@ def main():
         times = []
         for _ in range(reps):
             t0 = time.time()
-            Cref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B_host)
+            if sddmm:
+                xref, xmag = oracle.sddmm_coo(w.shape, w.rows, w.cols, w.vals, A_host, np.ascontiguousarray(B_host.T))
+            else:
+                Cref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B_host)
             times.append(time.time() - t0)
         cpu_s = sorted(times)[len(times) // 2]
-        Cg = copies[0][2].cpu().numpy().reshape(m, N).astype(np.float64)
+        if sddmm:     # per-triple results into storage order: the checker packs them under the same encoding
+            Cref = oracle.pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], xref, wbits, wbits).values.reshape(-1, 1)
+            mag = oracle.pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], xmag, wbits, wbits).values.reshape(-1, 1)
+            Cg = copies[0][2].cpu().numpy().reshape(-1, 1).astype(np.float64)
+        else:
+            Cg = copies[0][2].cpu().numpy().reshape(m, N).astype(np.float64)
         tol = 1e-12 if vbytes == 8 else 1e-5
         parity = bool(np.all(np.abs(Cg - Cref) <= tol * mag))
         cpu = {"value": abytes / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
@@ -225,7 +252,7 @@ def main():
         if w.level_types[1] == 0:
             kernel_name = "dense_rows_kernel"
     else:
-        kernel_name = "spmm_scatter_kernel" if (name == "cfg5" and args.csc_mode == 1) else (
+        kernel_name = "sddmm_rows_vec_kernel" if sddmm else "spmm_scatter_kernel" if (name == "cfg5" and args.csc_mode == 1) else (
             "spmm_rows_kernel" if args.spmm_kernel == 1 else "spmm_rows_vec_kernel")
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits

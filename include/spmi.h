@@ -46,8 +46,10 @@ typedef struct sp_tensor sp_tensor;       /* HOST handle that owns DEVICE arrays
 
 /* Device-memory allocator the library uses for everything it allocates (storage arrays and
  * temporaries).  alloc returns a DEVICE pointer aligned to >= 256 bytes or NULL; free_
- * releases one.  Both are called from the thread that calls into the library.  Pass NULL
- * for both to use hipMalloc / hipFree. */
+ * releases one.  Both are called from the thread that calls into the library.  free_ may be
+ * called while kernels that use the block are still queued on the stream of that call, so the
+ * allocator must be stream-ordered with respect to it (torch's caching allocator is, for the
+ * stream that was current at allocation).  Pass NULL for both to use hipMalloc / hipFree. */
 typedef void *(*sp_alloc_fn)(size_t bytes, void *ctx);
 typedef void (*sp_free_fn)(void *ptr, void *ctx);
 
@@ -103,6 +105,20 @@ sp_status sp_values(const sp_tensor *t, const void **ptr, int64_t *len);
  * order.  coords: HOST array of `rank` DEVICE int64 arrays, each with room for the
  * values length; values: DEVICE array of the tensor's dtype, same length.  Asynchronous. */
 sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream);
+
+/* Sampled dense-dense product X[i,j] = S[i,j] * sum_k A[i,k] * B[k,j] (Section 6.2, the SDDMM kernel of the
+ * state-space experiment).  X has S's pattern: the result is one value per stored position of S, in storage order
+ * (the order of sp_values), so it can stand in for S's values array.
+ *   S  packed rank-2 tensor m x n, row-major with a compressed innermost level (CSR or DCSR); other encodings
+ *      give SP_ERR_UNSUPPORTED (convert first).
+ *   A  DEVICE, m x K row-major, leading dimension lda >= K, S's dtype.
+ *   B  DEVICE, S's dtype: K x n row-major with ldb >= n as in the paper's formula (b_is_transposed = 0; the library
+ *      transposes it into scratch from the tensor's allocator on every call), or already n x K row-major with
+ *      ldb >= K (b_is_transposed = 1).
+ *   X  DEVICE, as many elements as sp_values reports, S's dtype.
+ * Enqueues on `stream`; does not synchronise when the allocator is stream-ordered (see sp_alloc_fn). */
+sp_status sp_sddmm(const sp_tensor *S, const void *A, int64_t lda, const void *B, int64_t ldb, int b_is_transposed,
+                   int64_t K, void *X, void *stream);
 
 /* The paper's convert operation between two sparse encodings (Section 4.2: conversions go through an intermediate
  * coordinate scheme, which avoids one converter per pair of formats).  Every stored position of `from` (explicit and

@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_convert", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_convert", "sp_sddmm", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -68,6 +68,8 @@ def load_library():
     L.sp_values.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
     L.sp_unpack.restype = ci
     L.sp_unpack.argtypes = [vp, vp, vp, vp]
+    L.sp_sddmm.restype = ci
+    L.sp_sddmm.argtypes = [vp, vp, i64, vp, i64, ci, i64, vp, vp]
     L.sp_convert.restype = ci
     L.sp_convert.argtypes = [vp, vp, vp, ctypes.POINTER(vp)]
     L.sp_tensor_info.restype = ci
@@ -239,6 +241,19 @@ def sp_unpack(A):
     carr = (ctypes.c_void_p * info.rank)(*[c.data_ptr() for c in coords])
     _check(L.sp_unpack(A._h, carr, vals.data_ptr(), _stream_ptr()), "in sp_unpack")
     return coords, vals
+
+
+def sp_sddmm(S, A, B, X=None, b_is_transposed=False):
+    """X[p] = S.values[p] * (A @ B)[i, j] for every stored position p = (i, j) of S.  A: (m, K); B: (K, n), or (n, K) when
+    b_is_transposed.  Returns X (storage order)."""
+    L = load_library()
+    assert A.is_cuda and B.is_cuda and A.dtype == S.dtype and B.dtype == S.dtype and A.dim() == 2 and B.dim() == 2
+    K = int(A.shape[1])
+    if X is None:
+        X = torch.empty(sp_tensor_info(S).nvalues, dtype=S.dtype, device=S.device)
+    _check(L.sp_sddmm(S._h, A.data_ptr(), int(A.stride(0)), B.data_ptr(), int(B.stride(0)), int(bool(b_is_transposed)), K,
+                      X.data_ptr(), _stream_ptr()), "in sp_sddmm")
+    return X
 
 
 def sp_convert(A, enc):

@@ -1,0 +1,202 @@
+// Sampled dense-dense product X[i,j] = S[i,j] * sum_k A[i,k] * B[k,j] (arXiv 2202.04305, Section 6.2: the kernel of
+// the state-space search experiment).  X has S's sparsity pattern, so the result is one value per stored position
+// of S, in storage order: no insertion into a sparse output is needed.
+//
+// Per stored entry (i, j) the kernel needs row i of A and column j of B.  B is K x n row-major in the paper's
+// formula, so a column is a stride-n walk; it is transposed once per call into an n x K scratch (unless the caller
+// already holds it that way), after which every entry reads one contiguous row of K values, exactly as the SpMM
+// kernel reads rows of its dense operand.  A wave takes one stored row of S: the row of A sits in registers, LR
+// lanes cover one row of the transposed B with 16-byte loads, 64 / LR entries go side by side, and a short
+// shuffle reduction over the LR lanes finishes each dot product.
+#include "spmi_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename VT>
+__global__ __launch_bounds__(256) void transpose_kernel(const VT *__restrict__ B, int64_t K, int64_t n, int64_t ldb,
+                                                        VT *__restrict__ Bt, int64_t ldt)
+{
+    __shared__ VT tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8 threads
+    const int64_t j0 = (int64_t)blockIdx.x * 32, k0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8)
+        if (k0 + r < K && j0 + tx < n) tile[r][tx] = B[(k0 + r) * ldb + j0 + tx];
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8)
+        if (j0 + r < n && k0 + tx < K) Bt[(j0 + r) * ldt + k0 + tx] = tile[tx][r];
+}
+
+// 16-byte loads: K = LR * (16 / sizeof(VT)), rows of A and of the transposed B 16-byte aligned.
+// Work is cut by stored entries, not by rows: block w owns the entries [w*T, (w+1)*T) (T and the table `rowblk` of
+// the row holding every T-th entry are the stream SpMV's), its waves take the rows that meet that window in turn
+// and each handles the part of its row inside the window.  A row of 20,000 entries is thus spread over 20 blocks
+// instead of being walked by one wave; no results need combining because every entry has its own output.
+template <typename PT, typename CT, typename VT, int LR>
+__global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                                     const VT *__restrict__ sval, const CT *__restrict__ rowid,
+                                                                     const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
+                                                                     const VT *__restrict__ A, int64_t lda,
+                                                                     const VT *__restrict__ Bt, int64_t ldt, VT *__restrict__ X)
+{
+    constexpr int V = 16 / sizeof(VT);
+    constexpr int S = 64 / LR;
+    constexpr int U = S >= 4 ? 2 : 4;
+    typedef VT vec_t __attribute__((ext_vector_type(V)));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int jl = lane % LR, sl = lane / LR;
+    const int64_t s = (int64_t)blockIdx.x * kSpmiStreamT;
+    const int64_t e = s + kSpmiStreamT < nnz ? s + kSpmiStreamT : nnz;
+    const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
+    const int64_t last = hi < nrows ? hi : nrows - 1;
+    for (int64_t r = lo + wave; r <= last; r += kThreads / 64) {
+        const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
+        const int64_t a = pa > s ? pa : s, b = pb < e ? pb : e;
+        if (b <= a) continue;                         // wave-uniform
+        const int64_t i = rowid ? (int64_t)rowid[r] : r;
+        const vec_t av = *(const vec_t *)(A + i * lda + jl * V);
+        // the step count is the same for every lane of the wave, so the shuffles run with all lanes active;
+        // entries past the end are clamped and their result dropped
+        const int64_t steps = (b - a + (int64_t)U * S - 1) / ((int64_t)U * S);
+        for (int64_t t = 0; t < steps; ++t) {
+            const int64_t p0 = a + t * U * S + sl;
+            vec_t bv[U];
+            int64_t pp[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                pp[u] = p0 + (int64_t)u * S;
+                const int64_t pc = pp[u] < b ? pp[u] : b - 1;
+                bv[u] = *(const vec_t *)(Bt + (int64_t)crd[pc] * ldt + jl * V);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                VT dot = 0;
+#pragma unroll
+                for (int ee = 0; ee < V; ++ee) dot += av[ee] * bv[u][ee];
+#pragma unroll
+                for (int d = LR / 2; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
+                if (jl == 0 && pp[u] < b) X[pp[u]] = sval[pp[u]] * dot;
+            }
+        }
+    }
+}
+
+// any K: CG lanes per entry, each striding over k
+template <typename PT, typename CT, typename VT, int CG>
+__global__ __launch_bounds__(kThreads) void sddmm_rows_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
+                                                              const VT *__restrict__ sval, const CT *__restrict__ rowid, int64_t nrows,
+                                                              const VT *__restrict__ A, int64_t lda, const VT *__restrict__ Bt,
+                                                              int64_t ldt, int64_t K, VT *__restrict__ X)
+{
+    constexpr int S = 64 / CG;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= nrows) return;
+    const int jl = lane % CG, sl = lane / CG;
+    const int64_t a = (int64_t)pos[r], b = (int64_t)pos[r + 1];
+    if (a == b) return;
+    const int64_t i = rowid ? (int64_t)rowid[r] : r;
+    const int64_t steps = (b - a + S - 1) / S;
+    for (int64_t t = 0; t < steps; ++t) {
+        const int64_t p = a + t * S + sl;
+        const int64_t pc = p < b ? p : b - 1;
+        const int64_t j = (int64_t)crd[pc];
+        VT dot = 0;
+        for (int64_t k = jl; k < K; k += CG) dot += A[i * lda + k] * Bt[j * ldt + k];
+#pragma unroll
+        for (int d = CG / 2; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
+        if (jl == 0 && p < b) X[p] = sval[p] * dot;
+    }
+}
+
+inline unsigned grid_for(int64_t n, int64_t per_block) { return (unsigned)(n > 0 ? ceil_div(n, per_block) : 1); }
+
+template <typename PT, typename CT, typename VT>
+sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int64_t ldb, int b_is_transposed, int64_t K, VT *X,
+                  hipStream_t st)
+{
+    const PT *pos = (const PT *)S->pos[1];
+    const CT *crd = (const CT *)S->crd[1];
+    const VT *sval = (const VT *)S->values;
+    const CT *rowid = S->enc.lt[0] == SP_COMPRESSED ? (const CT *)S->crd[0] : nullptr;
+    int64_t nrows = S->npos[1] - 1;
+    const sp_rowblocks *rowblocks = &S->rowblocks;
+    if (!rowid && S->nz_pos) { pos = (const PT *)S->nz_pos; rowid = (const CT *)S->nz_rowid; nrows = S->nz_rows; rowblocks = &S->nz_rowblocks; }
+    const int64_t n = S->shape[1];
+    if (S->nvalues == 0 || nrows == 0) return SP_OK;
+    if (K == 0) return spmi_fill_zero(X, (size_t)S->nvalues * sizeof(VT), st);   // X was allocated by the caller: exact size, 4-byte multiple
+
+    sp_mem mem{S->alloc, S->free_, S->ctx};
+    sp_scratch tmp(mem);
+    constexpr int64_t V = 16 / sizeof(VT);
+    const VT *Bt = B;
+    int64_t ldt = ldb;
+    if (!b_is_transposed) {
+        ldt = (K + V - 1) / V * V;                         // rows of the scratch start 16-byte aligned
+        VT *scratch = (VT *)tmp.get((size_t)(n > 0 ? n : 1) * ldt * sizeof(VT));
+        if (!scratch) return SP_ERR_ALLOC;
+        hipLaunchKernelGGL(transpose_kernel<VT>, dim3(grid_for(n, 32), grid_for(K, 32)), dim3(256), 0, st, B, K, n, ldb, scratch, ldt);
+        SP_HIP(hipGetLastError());
+        Bt = scratch;
+    }
+    {
+        sp_prof_scope prof(S, st);
+        const int64_t lr = K / V;
+        const bool vec = rowblocks->start && K % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && lda % V == 0 &&
+                         ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0;
+        const dim3 grid(grid_for(nrows, kThreads / 64));
+        if (vec) {
+#define SPMI_SDDMM_VEC(LR)                                                                                                    \
+    hipLaunchKernelGGL((sddmm_windows_vec_kernel<PT, CT, VT, LR>), dim3((unsigned)rowblocks->nblocks), dim3(kThreads), 0, st, pos, crd, \
+                       sval, rowid, (const int32_t *)rowblocks->start, nrows, S->ncrd[1], A, lda, Bt, ldt, X)
+            if (lr == 1) SPMI_SDDMM_VEC(1);
+            else if (lr == 2) SPMI_SDDMM_VEC(2);
+            else if (lr == 4) SPMI_SDDMM_VEC(4);
+            else if (lr == 8) SPMI_SDDMM_VEC(8);
+            else if (lr == 16) SPMI_SDDMM_VEC(16);
+            else if (lr == 32) SPMI_SDDMM_VEC(32);
+            else SPMI_SDDMM_VEC(64);
+#undef SPMI_SDDMM_VEC
+        } else {
+#define SPMI_SDDMM(CG)                                                                                                        \
+    hipLaunchKernelGGL((sddmm_rows_kernel<PT, CT, VT, CG>), grid, dim3(kThreads), 0, st, pos, crd, sval, rowid, nrows, A, lda, Bt, ldt, \
+                       K, X)
+            if (K > 32) SPMI_SDDMM(64);
+            else if (K > 8) SPMI_SDDMM(32);
+            else if (K > 2) SPMI_SDDMM(8);
+            else SPMI_SDDMM(2);
+#undef SPMI_SDDMM
+        }
+        SP_HIP(hipGetLastError());
+    }
+    // the scratch goes back to the allocator when `tmp` leaves scope; with a stream-ordered allocator that is safe,
+    // with hipFree it waits for the device
+    if (!S->alloc && !b_is_transposed) SP_HIP(hipStreamSynchronize(st));
+    return SP_OK;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_sddmm(const sp_tensor *S, const void *A, int64_t lda, const void *B, int64_t ldb, int b_is_transposed,
+                              int64_t K, void *X, void *stream)
+{
+    if (!S) return SP_ERR_NULL;
+    if (S->enc.rank != 2) return SP_ERR_RANK;
+    const int64_t n = S->shape[1];
+    if (K < 0 || lda < K || (b_is_transposed ? ldb < K : ldb < n)) return SP_ERR_SHAPE;
+    if (S->nvalues > 0 && (!X || (K > 0 && (!A || !B)))) return SP_ERR_NULL;
+    if (S->enc.perm[0] != 0 || S->enc.lt[1] != SP_COMPRESSED) return SP_ERR_UNSUPPORTED;   // row-major with a compressed inner level
+    hipStream_t st = (hipStream_t)stream;
+    const int pw = S->enc.pw, cw = S->enc.cw;
+#define SPMI_GO(PT, CT)                                                                                                       \
+    return S->dtype == SP_F64 ? sddmm_t<PT, CT, double>(S, (const double *)A, lda, (const double *)B, ldb, b_is_transposed, K, (double *)X, st) \
+                              : sddmm_t<PT, CT, float>(S, (const float *)A, lda, (const float *)B, ldb, b_is_transposed, K, (float *)X, st)
+    if (pw == 32 && cw == 32) SPMI_GO(int32_t, int32_t);
+    if (pw == 32) SPMI_GO(int32_t, int64_t);
+    if (cw == 32) SPMI_GO(int64_t, int32_t);
+    SPMI_GO(int64_t, int64_t);
+#undef SPMI_GO
+}
