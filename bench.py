@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
     ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
-    ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads")
+    ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads with a wave per row, 3 16-byte loads cut by entries")
     ap.add_argument("--accumulate", action="store_true", help="C += A.B instead of C = A.B")
     ap.add_argument("--small", action="store_true", help="scaled-down matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
@@ -253,7 +253,7 @@ def main():
             kernel_name = "dense_rows_kernel"
     else:
         kernel_name = "sddmm_rows_vec_kernel" if sddmm else "spmm_scatter_kernel" if (name == "cfg5" and args.csc_mode == 1) else (
-            "spmm_rows_kernel" if args.spmm_kernel == 1 else "spmm_rows_vec_kernel")
+            "spmm_rows_kernel" if args.spmm_kernel == 1 else "spmm_rows_vec_kernel" if args.spmm_kernel == 2 else "spmm_windows_vec_kernel (+ fix-up)")
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits
     if args.format:

@@ -143,7 +143,8 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
 /* Kernel choice for sp_matmul on this tensor, for A/B measurements.  key/value pairs:
  *   SP_TUNE_SPMV_KERNEL: 0 = automatic, 1 = lanes-per-row, 2 = streaming over the CSR arrays (bit-reproducible),
  *                        3 = streaming over a column-segmented copy (built and kept on first use; CSR only)
- *   SP_TUNE_SPMM_KERNEL: 0 = automatic, 1 = one column per lane, 2 = 16 bytes of a row of B per lane (needs N a multiple
+ *   SP_TUNE_SPMM_KERNEL: 0 = automatic, 1 = one column per lane, 2 = 16 bytes of a row of B per lane, a wave per row,
+ *                        3 = the same cut by stored entries instead of rows (2 and 3 need N a multiple
  *                        of 16 / element size with 1, 2, 4, ... 64 such vectors per row, and B, C rows 16-byte aligned)
  *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */

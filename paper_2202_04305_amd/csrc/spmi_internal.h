@@ -62,6 +62,8 @@ struct sp_tensor {
     sp_segments *segments;           // owned, built on first use
     void *dense_partial;             // DEVICE scratch of the dense-row SpMV (per-chunk partial sums), grown on demand
     size_t dense_partial_bytes;
+    void *spmm_carry;                // DEVICE scratch of the SpMM cut by entries (N values per block), grown on demand
+    size_t spmm_carry_bytes;
     int tune_spmv, tune_csc, tune_spmm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned

@@ -146,18 +146,22 @@ def test_csr_spmm(N, dtype):
     B = w.dense_operand(N)
     C, ref, mag = run(A, w, B)
     assert_product_close(C, ref, mag, dtype, "spmm")
+    C0 = prng.uniform_pm1(5, 6, w.shape[0] * N).reshape(-1, N)
     sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 1)          # one column per lane, whatever N is
     C, ref, mag = run(A, w, B)
     assert_product_close(C, ref, mag, dtype, "spmm, one column per lane")
     vec_ok = (N * np.dtype(dtype).itemsize) % 16 == 0 and (N * np.dtype(dtype).itemsize) // 16 in (1, 2, 4, 8, 16, 32, 64)
-    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 2)          # 16-byte loads: only some N
-    if vec_ok:
-        C, ref, mag = run(A, w, B)
-        assert_product_close(C, ref, mag, dtype, "spmm, 16-byte loads")
-    else:
-        with pytest.raises(sp.SpError) as e:
-            run(A, w, B)
-        assert e.value.code == oracle.ERR_UNSUPPORTED
+    for kernel in (2, 3):                                     # 16-byte loads, a wave per row / cut by entries: only some N
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, kernel)
+        if vec_ok:
+            C, ref, mag = run(A, w, B)
+            assert_product_close(C, ref, mag, dtype, "spmm, 16-byte loads, kernel %d" % kernel)
+            C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
+            assert_product_close(C, ref, mag, dtype, "spmm accumulate, kernel %d" % kernel)
+        else:
+            with pytest.raises(sp.SpError) as e:
+                run(A, w, B)
+            assert e.value.code == oracle.ERR_UNSUPPORTED
     sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 0)
     C0 = prng.uniform_pm1(5, 6, w.shape[0] * N).reshape(-1, N)
     C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
@@ -185,6 +189,30 @@ def test_csr_with_mostly_empty_rows(N, widths):
         assert_product_close(C, cref, mag, w.dtype, "mostly empty csr accumulate")
         untouched = torch.from_numpy(np.bincount(w.rows, minlength=w.shape[0]) == 0).to(DEV)
         assert torch.equal(C[untouched], dev(C0)[untouched])
+
+
+@pytest.mark.parametrize("lt", [(0, 1), (1, 1)])
+def test_spmm_cut_by_entries_long_rows_and_exact(lt):
+    """Rows much longer than a block's window (several carries per row), empty rows between them, CSR and DCSR."""
+    w = W.cfg2_powerlaw_csr(400, 30000, mean=3000.0, sigma=1.0, cap=25000)
+    w.rows = w.rows * 3                     # two empty rows after every row
+    w.shape = (1200, 30000)
+    vals = w.exact_values()
+    say("case spmm windows", lt, w.stats)
+    A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 3)
+    B = w.dense_operand(8, exact=True)
+    C, ref, mag = run(A, w, B, vals=vals)
+    assert np.array_equal(C.cpu().numpy(), ref)
+    A2 = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    B2 = w.dense_operand(32)
+    for kernel in (0, 3):
+        sp.sp_tensor_tune(A2, sp.SP_TUNE_SPMM_KERNEL, kernel)
+        C, ref, mag = run(A2, w, B2)
+        assert_product_close(C, ref, mag, w.dtype, "spmm windows")
+        C0 = prng.uniform_pm1(5, 12, w.shape[0] * 32).reshape(-1, 32)
+        C, ref, mag = run(A2, w, B2, accumulate=True, C0=C0)
+        assert_product_close(C, ref, mag, w.dtype, "spmm windows accumulate")
 
 
 def test_leading_dimensions():
