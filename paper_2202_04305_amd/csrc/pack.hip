@@ -130,40 +130,75 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
     return m;
 }
 
+// One pass of the sort for one tile of kSortTile keys.  Wave w owns the w-th quarter of the tile (stability: tile
+// order = wave, round, lane).  (1) every key gets its rank among the equal digits of its wave, with ballots and a
+// per-wave running count in LDS; (2) the four waves' counts are combined into where each digit starts inside the
+// tile; (3) keys and payloads are placed in LDS in sorted order; (4) they are copied out, so that neighbouring
+// threads write neighbouring addresses of one digit's run instead of 4096 scattered single stores.
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
                                                                  uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
                                                                  const uint32_t *__restrict__ offs, int64_t n, int shift, int nblocks)
 {
-    __shared__ uint32_t base[256];                    // next output slot of each digit for this block
-    __shared__ uint32_t wcnt[kThreads / 64][256];     // per-wave digit counts of the current round
+    constexpr int W = kThreads / 64, PERW = kSortTile / W;
+    __shared__ uint32_t wrun[W][256];                 // running count of each digit inside each wave's quarter
+    __shared__ uint32_t wbase[W][256];                // where wave w's keys of digit d start inside the sorted tile
+    __shared__ uint32_t gbase[256];                   // global slot of the tile's first key of digit d, minus its tile slot
+    __shared__ uint32_t wsum[W];
+    __shared__ uint64_t skey[kSortTile];
+    __shared__ uint32_t sval[kSortTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    base[tid] = offs[(int64_t)tid * nblocks + blockIdx.x];
     const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
+    const int64_t in_tile = n - tile0 < kSortTile ? n - tile0 : kSortTile;
+#pragma unroll
+    for (int w = 0; w < W; ++w) wrun[w][tid] = 0;
+    uint64_t k[kSortRounds];
+    uint32_t v[kSortRounds], lpos[kSortRounds];
+#pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
-        const int64_t i = tile0 + (int64_t)r * kThreads + tid;
-        if (tile0 + (int64_t)r * kThreads >= n) break;            // uniform across the block
-        const bool valid = i < n;
-        const uint64_t k = valid ? kin[i] : 0;
-        const uint32_t v = valid ? vin[i] : 0;
-        const uint32_t d = (uint32_t)(k >> shift) & 255u;
+        const int64_t i = tile0 + wave * PERW + r * 64 + lane;
+        k[r] = i < n ? kin[i] : 0;
+        v[r] = i < n ? vin[i] : 0;
+    }
+    __syncthreads();
 #pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) wcnt[w][tid] = 0;
-        __syncthreads();
+    for (int r = 0; r < kSortRounds; ++r) {
+        const bool valid = wave * PERW + r * 64 + lane < in_tile;
+        const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
         const uint64_t m = match_digit(d, valid);
-        const uint32_t rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (valid && rank == 0) wcnt[wave][d] = (uint32_t)__popcll(m);
-        __syncthreads();
-        if (valid) {
-            uint32_t p = base[d] + rank;
-            for (int w = 0; w < wave; ++w) p += wcnt[w][d];
-            kout[p] = k;
-            vout[p] = v;
-        }
-        __syncthreads();
-        uint32_t add = 0;
+        const uint32_t before = wrun[wave][d];                    // written by this wave only, in program order
+        lpos[r] = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (valid && (m & ((1ull << lane) - 1ull)) == 0) wrun[wave][d] = before + (uint32_t)__popcll(m);
+    }
+    __syncthreads();
+    {   // thread d: tile count of digit d, exclusive scan over the digits, per-wave starts
+        uint32_t c[W], tot = 0;
 #pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) add += wcnt[w][tid];
-        base[tid] += add;
+        for (int w = 0; w < W; ++w) { c[w] = wrun[w][tid]; tot += c[w]; }
+        const uint32_t incl = wave_inclusive_scan(tot, lane);
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t start = incl - tot;
+        for (int w = 0; w < wave; ++w) start += wsum[w];
+        gbase[tid] = offs[(int64_t)tid * nblocks + blockIdx.x] - start;     // unsigned wrap-around is fine: added back below
+#pragma unroll
+        for (int w = 0; w < W; ++w) { wbase[w][tid] = start; start += c[w]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        if (wave * PERW + r * 64 + lane < in_tile) {
+            const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
+            const uint32_t slot = wbase[wave][d] + lpos[r];
+            skey[slot] = k[r];
+            sval[slot] = v[r];
+        }
+    }
+    __syncthreads();
+    for (int slot = tid; slot < (int)in_tile; slot += kThreads) {
+        const uint64_t key = skey[slot];
+        const uint32_t p = gbase[(uint32_t)(key >> shift) & 255u] + (uint32_t)slot;
+        kout[p] = key;
+        vout[p] = sval[slot];
     }
 }
 
