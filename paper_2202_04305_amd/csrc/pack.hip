@@ -5,7 +5,7 @@
 // sweep per level: a compressed level marks where a new (parent, coordinate) pair starts,
 // prefix-sums the marks into child positions, counts children per parent and prefix-sums
 // the counts into pos; a dense level only folds the coordinate into the position.  The
-// values are gathered last.  Only level sizes and the error flags travel to the host.
+// values travel through the sort as the payload and are put in place last.  Only level sizes and the error flags travel to the host.
 #include "spmi_internal.h"
 
 namespace {
@@ -135,8 +135,9 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
 // per-wave running count in LDS; (2) the four waves' counts are combined into where each digit starts inside the
 // tile; (3) keys and payloads are placed in LDS in sorted order; (4) they are copied out, so that neighbouring
 // threads write neighbouring addresses of one digit's run instead of 4096 scattered single stores.
-__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
-                                                                 uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
+template <typename P>
+__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t *__restrict__ kin, const P *__restrict__ vin,
+                                                                 uint64_t *__restrict__ kout, P *__restrict__ vout,
                                                                  const uint32_t *__restrict__ offs, int64_t n, int shift, int nblocks)
 {
     constexpr int W = kThreads / 64, PERW = kSortTile / W;
@@ -145,14 +146,15 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t 
     __shared__ uint32_t gbase[256];                   // global slot of the tile's first key of digit d, minus its tile slot
     __shared__ uint32_t wsum[W];
     __shared__ uint64_t skey[kSortTile];
-    __shared__ uint32_t sval[kSortTile];
+    __shared__ P sval[kSortTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
     const int64_t in_tile = n - tile0 < kSortTile ? n - tile0 : kSortTile;
 #pragma unroll
     for (int w = 0; w < W; ++w) wrun[w][tid] = 0;
     uint64_t k[kSortRounds];
-    uint32_t v[kSortRounds], lpos[kSortRounds];
+    P v[kSortRounds];
+    uint32_t lpos[kSortRounds];
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = tile0 + wave * PERW + r * 64 + lane;
@@ -218,8 +220,11 @@ struct level_args {
     int rank;
 };
 
-__global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64_t nnz, uint64_t *__restrict__ keys,
-                                                             uint32_t *__restrict__ idx, int *__restrict__ flags)
+// The payload that travels with the key through the sort is the value itself (its bits), so that no gather by
+// entry id is needed afterwards.
+template <typename P>
+__global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64_t nnz, const P *__restrict__ values,
+                                                             uint64_t *__restrict__ keys, P *__restrict__ payload, int *__restrict__ flags)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64
         key = key * (uint64_t)a.size[l] + (uint64_t)c;
     }
     keys[e] = bad ? 0 : key;
-    idx[e] = (uint32_t)e;
+    payload[e] = values[e];
     if (bad) atomicOr(&flags[0], 1);
 }
 
@@ -277,22 +282,24 @@ __global__ __launch_bounds__(kThreads) void emit_level_kernel(const uint64_t *__
     const bool first = (e == 0) || (keys[e - 1] / stride != pre);
     const uint64_t child = child_excl ? (uint64_t)child_excl[e] + (first ? 1u : 0u) - 1u : (uint64_t)e;
     if (first) crd[child] = (CT)(pre % size);
-    const uint64_t par = parent_in ? parent_in[e] : 0ull;
-    const bool head = (e == 0) || (parent_in && parent_in[e - 1] != par);
-    const bool tail = (e == nnz - 1) || (parent_in && parent_in[e + 1] != par);
+    // position of the entry at the level above: carried in parent_in, or, while every level above is dense, simply
+    // the key prefix down to that level (pre / size), which needs no array
+    const uint64_t par = parent_in ? parent_in[e] : pre / size;
+    const bool head = (e == 0) || (parent_in ? parent_in[e - 1] : keys[e - 1] / stride / size) != par;
+    const bool tail = (e == nnz - 1) || (parent_in ? parent_in[e + 1] : keys[e + 1] / stride / size) != par;
     typedef typename std::conditional<sizeof(PT) == 8, unsigned long long, unsigned int>::type UT;
     if (tail) atomicAdd((UT *)&cnt[par], (UT)(child + 1));
     if (head) atomicAdd((UT *)&cnt[par], (UT)(0) - (UT)child);
-    parent_out[e] = child;
+    if (parent_out) parent_out[e] = child;
 }
 
-template <typename VT>
-__global__ __launch_bounds__(kThreads) void gather_values_kernel(const VT *__restrict__ vin, const uint32_t *__restrict__ idx,
-                                                                 const uint64_t *__restrict__ position, int64_t nnz, VT *__restrict__ vout)
+template <typename P>
+__global__ __launch_bounds__(kThreads) void place_values_kernel(const P *__restrict__ sorted, const uint64_t *__restrict__ position,
+                                                                int64_t nnz, P *__restrict__ vout)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
-    vout[position ? position[e] : (uint64_t)e] = vin[idx[e]];
+    vout[position ? position[e] : (uint64_t)e] = sorted[e];
 }
 
 // longest pos segment: grid-stride maximum per thread, wave and block reduction, one atomic per block
@@ -411,33 +418,40 @@ sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, 
     return exclusive_scan_t<unsigned long long>((unsigned long long *)data, n, tmp, st);
 }
 
-sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
+template <typename P>
+static sp_status radix_sort_pairs_t(uint64_t *keys, P *vals, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
 {
     if (n <= 1 || key_bits <= 0) return SP_OK;
     const int passes = (key_bits + 7) / 8;
     const int nblocks = (int)ceil_div(n, kSortTile);
     uint64_t *kalt = (uint64_t *)tmp.get((size_t)n * 8);
-    uint32_t *valt = (uint32_t *)tmp.get((size_t)n * 4);
+    P *valt = (P *)tmp.get((size_t)n * sizeof(P));
     uint32_t *hist = (uint32_t *)tmp.get((size_t)256 * nblocks * 4);
     if (!kalt || !valt || !hist) return SP_ERR_ALLOC;
     uint64_t *kin = keys, *kout = kalt;
-    uint32_t *vin = vals, *vout = valt;
+    P *vin = vals, *vout = valt;
     for (int p = 0; p < passes; ++p) {
         const int shift = 8 * p;
         hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, n, shift, hist, nblocks);
         SP_HIP(hipGetLastError());
         SP_TRY(spmi_exclusive_scan(hist, (int64_t)256 * nblocks, 32, tmp, st));
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, (const uint32_t *)vin,
-                           kout, vout, (const uint32_t *)hist, n, shift, nblocks);
+        hipLaunchKernelGGL(radix_scatter_kernel<P>, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, (const P *)vin, kout, vout,
+                           (const uint32_t *)hist, n, shift, nblocks);
         SP_HIP(hipGetLastError());
         uint64_t *tk = kin; kin = kout; kout = tk;
-        uint32_t *tv = vin; vin = vout; vout = tv;
+        P *tv = vin; vin = vout; vout = tv;
     }
     if (kin != keys) {      // odd number of passes: bring the result home
         SP_HIP(hipMemcpyAsync(keys, kin, (size_t)n * 8, hipMemcpyDeviceToDevice, st));
-        SP_HIP(hipMemcpyAsync(vals, vin, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
+        SP_HIP(hipMemcpyAsync(vals, vin, (size_t)n * sizeof(P), hipMemcpyDeviceToDevice, st));
     }
     return SP_OK;
+}
+
+sp_status spmi_radix_sort_pairs(uint64_t *keys, void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
+{
+    if (payload_bytes == 4) return radix_sort_pairs_t<uint32_t>(keys, (uint32_t *)vals, n, key_bits, tmp, st);
+    return radix_sort_pairs_t<unsigned long long>(keys, (unsigned long long *)vals, n, key_bits, tmp, st);
 }
 
 static size_t pad16(size_t b) { return (b + 15) & ~(size_t)15; }
@@ -671,23 +685,29 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
         sp_scratch tmp(mem);
         const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
         uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
-        uint32_t *idx = (uint32_t *)tmp.get(cnt * 4);
+        const int vsz0 = dt == SP_F64 ? 8 : 4;
+        void *payload = tmp.get(cnt * vsz0);      // the values, carried through the sort
         uint64_t *parentA = (uint64_t *)tmp.get(cnt * 8);
         uint64_t *parentB = (uint64_t *)tmp.get(cnt * 8);
         uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
         int *flags = (int *)tmp.get(64);
         auto fail = [&](sp_status s) { status = s; return s; };
         do {
-            if (!keys || !idx || !parentA || !parentB || !child || !flags) { fail(SP_ERR_ALLOC); break; }
+            if (!keys || !payload || !parentA || !parentB || !child || !flags) { fail(SP_ERR_ALLOC); break; }
             if (spmi_fill_zero(flags, 64, st) != SP_OK) { fail(SP_ERR_HIP); break; }
             if (nnz > 0) {
                 level_args la;
                 memset(&la, 0, sizeof(la));
                 la.rank = rank;
                 for (int l = 0; l < rank; ++l) { la.coord[l] = coords[enc->perm[l]]; la.size[l] = t->size[l]; }
-                hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz, keys, idx, flags);
+                if (dt == SP_F64)
+                    hipLaunchKernelGGL(make_keys_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz,
+                                       (const unsigned long long *)values, keys, (unsigned long long *)payload, flags);
+                else
+                    hipLaunchKernelGGL(make_keys_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz,
+                                       (const uint32_t *)values, keys, (uint32_t *)payload, flags);
                 if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-                if (fail(spmi_radix_sort_pairs(keys, idx, nnz, key_bits, tmp, st)) != SP_OK) break;
+                if (fail(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st)) != SP_OK) break;
                 hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
                 if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
             }
@@ -698,7 +718,8 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
             if (hflags[1]) { fail(SP_ERR_DUPLICATE); break; }
 
             // level sweep
-            const uint64_t *pin = nullptr;      // nullptr = every entry has parent 0
+            const uint64_t *pin = nullptr;      // nullptr = the position at the level above is the key prefix (dense levels so far)
+            bool dense_prefix = true;
             uint64_t *pbuf[2] = {parentA, parentB};
             int which = 0;
             int64_t P = 1;
@@ -707,6 +728,10 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                 for (int k = l + 1; k < rank; ++k) stride *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
                 const uint64_t size = (uint64_t)(t->size[l] > 0 ? t->size[l] : 1);
                 uint64_t *pout = pbuf[which];
+                if (enc->lt[l] == SP_DENSE && dense_prefix) {
+                    P *= t->size[l];                  // nothing to compute: the position at this level is the key prefix
+                    continue;
+                }
                 if (enc->lt[l] == SP_DENSE) {
                     if (nnz > 0) {
                         hipLaunchKernelGGL(dense_level_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz,
@@ -743,16 +768,17 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                     if (spmi_fill_zero(t->pos[l], pbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
                     if (nnz > 0) {
                         sp_status s;
-                        if (enc->pw == 32 && enc->cw == 32) s = launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
-                        else if (enc->pw == 32) s = launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
-                        else if (enc->cw == 32) s = launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
-                        else s = launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st);
+                        if (enc->pw == 32 && enc->cw == 32) s = launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
+                        else if (enc->pw == 32) s = launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
+                        else if (enc->cw == 32) s = launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
+                        else s = launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
                         if (fail(s) != SP_OK) break;
                     }
                     if (fail(spmi_exclusive_scan(t->pos[l], P + 1, enc->pw, tmp, st)) != SP_OK) break;
                     P = nchild;
                 }
-                if (nnz > 0) { pin = pout; which ^= 1; }
+                if (enc->lt[l] == SP_COMPRESSED) dense_prefix = false;
+                if (nnz > 0 && !(enc->lt[l] == SP_COMPRESSED && l == rank - 1)) { pin = pout; which ^= 1; }
             }
             if (status != SP_OK) break;
 
@@ -791,13 +817,15 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
             if (!t->values) { fail(SP_ERR_ALLOC); break; }
             if (P != nnz && spmi_fill_zero(t->values, vbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
             if (nnz > 0) {
-                const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : pin;
+                // where each sorted entry's value goes: its own rank (innermost level compressed), the key itself (every
+                // level dense), or the position carried down from the last compressed level
+                const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : dense_prefix ? (const uint64_t *)keys : pin;
                 if (dt == SP_F64)
-                    hipLaunchKernelGGL(gather_values_kernel<double>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const double *)values,
-                                       (const uint32_t *)idx, position, nnz, (double *)t->values);
+                    hipLaunchKernelGGL(place_values_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                                       (const unsigned long long *)payload, position, nnz, (unsigned long long *)t->values);
                 else
-                    hipLaunchKernelGGL(gather_values_kernel<float>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const float *)values,
-                                       (const uint32_t *)idx, position, nnz, (float *)t->values);
+                    hipLaunchKernelGGL(place_values_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                                       (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
                 if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
             }
             // longest innermost segment (kernel choice) and the row blocks of the streaming kernels

@@ -127,9 +127,8 @@ struct sp_scratch {
 // In-place exclusive prefix sum of n elements of width `bits` (32 or 64); data[n-1] afterwards
 // holds the sum of the first n-1 inputs.
 sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, hipStream_t st);
-// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits; results end in keys/vals.
-sp_status spmi_radix_sort_pairs(uint64_t *keys, uint32_t *vals, int64_t n, int key_bits,
-                                sp_scratch &tmp, hipStream_t st);
+// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits, payload of 4 or 8 bytes; results end in keys/vals.
+sp_status spmi_radix_sort_pairs(uint64_t *keys, void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
 sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
