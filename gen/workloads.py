@@ -173,3 +173,105 @@ def row_band(n=8192, dense_rows=1000, seed=BASE_SEED + 6, lt=(DENSE, COMPRESSED)
     seg = np.repeat(np.arange(dense_rows, dtype=np.int64), n)
     col = np.tile(np.arange(n, dtype=np.int64), dense_rows)
     return _finish("row_band", 6, (n, n), lt, (0, 1), np.float64, True, seg, col, 1, seed)
+
+
+# ---------------------------------------------------------------------------------------
+# rank 3: a synthetic stand-in for the knowledge-base tensor of the paper's MTTKRP experiment
+# ---------------------------------------------------------------------------------------
+@dataclass
+class Tensor3Workload:
+    name: str
+    shape: tuple            # (I, K, L)
+    dtype: type
+    ci: np.ndarray          # int64 coordinates per dimension, seeded shuffled order
+    ck: np.ndarray
+    cl: np.ndarray
+    vals: np.ndarray
+    J: int                  # columns of the factor matrices
+    seed: int
+    stats: dict = field(default_factory=dict)
+
+    @property
+    def nnz(self):
+        return int(self.vals.shape[0])
+
+    def factors(self, J=None, exact=False):
+        """(C, D): K x J and L x J row-major, U[-1,1) (or small integers when `exact`)."""
+        J = self.J if J is None else J
+        _, K, L = self.shape
+        if exact:
+            return (prng.small_ints(self.seed, 81, K * J, lo=-3, hi=3, dtype=self.dtype).reshape(K, J),
+                    prng.small_ints(self.seed, 82, L * J, lo=-3, hi=3, dtype=self.dtype).reshape(L, J))
+        return (prng.uniform_pm1(self.seed, 8, K * J, dtype=self.dtype).reshape(K, J),
+                prng.uniform_pm1(self.seed, 9, L * J, dtype=self.dtype).reshape(L, J))
+
+    def exact_values(self):
+        return prng.small_ints(self.seed, 83, self.nnz, lo=-3, hi=3, dtype=self.dtype)
+
+
+def _distinct_sorted_var(seed, stream, seg_len, bounds):
+    """As distinct_sorted_per_segment with a bound of its own per segment (each seg_len[s] <= bounds[s] / 2)."""
+    seg_len = np.asarray(seg_len, dtype=np.int64)
+    bounds = np.asarray(bounds, dtype=np.int64)
+    assert np.all(seg_len * 2 <= bounds) or seg_len.size == 0
+    S = seg_len.shape[0]
+    top = int(bounds.max(initial=1))
+    seg = np.repeat(np.arange(S, dtype=np.int64), seg_len)
+    total = seg.shape[0]
+    b = bounds[seg]
+    key = seg * top + np.minimum((prng.uniform01(seed, stream, total) * b).astype(np.int64), b - 1)
+    used = total
+    while True:
+        key.sort()
+        dup = np.nonzero(key[1:] == key[:-1])[0] + 1
+        if dup.size == 0:
+            break
+        sd = key[dup] // top
+        bd = bounds[sd]
+        key[dup] = sd * top + np.minimum((prng.uniform01(seed, stream, dup.size, offset=used) * bd).astype(np.int64), bd - 1)
+        used += dup.size
+    return key // top, key % top
+
+
+def tensor3_slices(I=12092, K=9184, L=28818, nnz=76_879_419, J=42, k_mean=500.0, l_mean=1500.0, sigma=1.0,
+                   dtype=np.float64, seed=BASE_SEED + 7, name="mttkrp_tensor3"):
+    """I x K x L tensor with the shape, entry count and output width of the paper's MTTKRP experiment.
+
+    Slice i touches a pool of a_i of the K and b_i of the L coordinates (lognormal sizes, seeded choices) and stores a
+    uniform sample of that a_i x b_i grid; one density for all slices, set so that the total comes to about `nnz`.
+    Both fibre families, (i,k,:) and (i,:,l), therefore have lengths that grow with the slice: the structure the two
+    storage orders of the experiment walk."""
+    mu_k = np.log(k_mean) - 0.5 * sigma * sigma
+    mu_l = np.log(l_mean) - 0.5 * sigma * sigma
+    a = np.clip(np.rint(np.exp(mu_k + sigma * prng.normal(seed, 21, I))), 2, max(2, K // 2)).astype(np.int64)
+    b = np.clip(np.rint(np.exp(mu_l + sigma * prng.normal(seed, 22, I))), 2, max(2, L // 2)).astype(np.int64)
+    cells = a * b
+    rho = min(0.45, nnz / float(cells.sum()))
+    cnt = np.clip(np.rint(rho * cells), 1, cells // 2).astype(np.int64)
+    kseg, kval = distinct_sorted_per_segment(seed, 23, a, K)          # pools, ascending per slice
+    lseg, lval = distinct_sorted_per_segment(seed, 24, b, L)
+    koff = np.concatenate(([0], np.cumsum(a)))
+    loff = np.concatenate(([0], np.cumsum(b)))
+    si, cell = _distinct_sorted_var(seed, 25, cnt, cells)
+    bi = b[si]
+    ck = kval[koff[si] + cell // bi]
+    cl = lval[loff[si] + cell % bi]
+    n = si.shape[0]
+    vals = prng.uniform_pm1(seed, 3, n, dtype=dtype)
+    perm = prng.permutation(seed, 5, n)
+    fib = np.nonzero(np.concatenate(([True], (si[1:] != si[:-1]) | (ck[1:] != ck[:-1]))))[0]
+    flen = np.diff(np.concatenate((fib, [n])))
+    stats = {"nnz": int(n), "slices": int(I), "fibres_ik": int(fib.shape[0]), "mean_fibre_ik": float(flen.mean()) if n else 0.0,
+             "max_fibre_ik": int(flen.max(initial=0)), "max_slice": int(cnt.max(initial=0)), "median_slice": float(np.median(cnt))}
+    return Tensor3Workload(name, (I, K, L), dtype, np.ascontiguousarray(si[perm]), np.ascontiguousarray(ck[perm]),
+                           np.ascontiguousarray(cl[perm]), np.ascontiguousarray(vals[perm]), J, seed, stats)
+
+
+def tensor3_uniform(I, K, L, nnz, J=5, dtype=np.float64, seed=BASE_SEED + 98):
+    """Small uniform random rank-3 tensor (distinct coordinates), for tests."""
+    _, lin = distinct_sorted_per_segment(seed, 26, np.array([nnz], dtype=np.int64), I * K * L)
+    perm = prng.permutation(seed, 5, nnz)
+    lin = lin[perm]
+    vals = prng.uniform_pm1(seed, 3, nnz, dtype=dtype)
+    return Tensor3Workload("tensor3_uniform", (I, K, L), dtype, lin // (K * L), (lin // L) % K, lin % L, vals, J, seed,
+                           {"nnz": int(nnz)})

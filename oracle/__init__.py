@@ -57,6 +57,8 @@ def lib():
         L.oracle_matmul_storage.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
         L.oracle_sddmm_coo.restype = ci
         L.oracle_sddmm_coo.argtypes = [i64, i64, i64, i64, vp, vp, vp, ci, vp, i64, vp, i64, vp, vp]
+        L.oracle_mttkrp_coo.restype = ci
+        L.oracle_mttkrp_coo.argtypes = [i64, i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, i64, vp, i64, vp, i64, ci, vp]
         L.oracle_matmul_coo_f64seq.restype = ci
         L.oracle_matmul_coo_f64seq.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64]
         _lib = L
@@ -212,3 +214,25 @@ def sddmm_coo(shape, rows, cols, svals, A, B):
     if st != OK:
         raise OracleError(st)
     return X, mag
+
+
+def mttkrp_coo(shape, ci, ck, cl, bvals, C, D, accumulate=False, A=None):
+    """(A, mag): A[i,j] = sum_{k,l} B[i,k,l] * D[l,j] * C[k,j] over the COO triples of B (shape I x K x L), C (K, J)
+    and D (L, J) row-major, by the plain definition."""
+    I, K, L = shape
+    bvals = np.ascontiguousarray(bvals)
+    dt = _dt(bvals.dtype)
+    C = np.ascontiguousarray(C, dtype=bvals.dtype)
+    D = np.ascontiguousarray(D, dtype=bvals.dtype)
+    J = C.shape[1]
+    assert C.shape == (K, J) and D.shape == (L, J)
+    ci = np.ascontiguousarray(ci, dtype=np.int64)
+    ck = np.ascontiguousarray(ck, dtype=np.int64)
+    cl = np.ascontiguousarray(cl, dtype=np.int64)
+    Aout = np.zeros((I, J), dtype=bvals.dtype) if A is None else np.array(A, dtype=bvals.dtype).reshape(I, J).copy()
+    mag = np.zeros((I, J), dtype=np.float64)
+    st = lib().oracle_mttkrp_coo(I, K, L, J, ci.shape[0], _ptr(ci), _ptr(ck), _ptr(cl), _ptr(bvals), dt, _ptr(C), max(J, 1),
+                                 _ptr(D), max(J, 1), _ptr(Aout), max(J, 1), int(accumulate), _ptr(mag))
+    if st != OK:
+        raise OracleError(st)
+    return Aout, mag

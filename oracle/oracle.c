@@ -392,3 +392,45 @@ int oracle_sddmm_coo(int64_t m, int64_t n, int64_t K, int64_t nnz, const int64_t
     }
     return OR_OK;
 }
+
+/* Matricized tensor times Khatri-Rao product (Section 6.3): A[i,j] = sum_{k,l} B[i,k,l] * D[l,j] * C[k,j] for a
+ * rank-3 tensor B of shape I x K x L given as COO triples (any order), C of K x J and D of L x J, both row-major.
+ * Plain definition: one pass over the triples, every term formed and added in long double, rounded once at the
+ * end; mag[i,j] = sum of the terms' absolute values.  With accumulate != 0 the sums start from A's contents. */
+int oracle_mttkrp_coo(int64_t I, int64_t K, int64_t L, int64_t J, int64_t nnz, const int64_t *ci, const int64_t *ck,
+                      const int64_t *cl, const void *bvals, int dtype, const void *C, int64_t ldc, const void *D,
+                      int64_t ldd, void *A, int64_t lda, int accumulate, double *mag)
+{
+    if (nnz > 0 && (!ci || !ck || !cl || !bvals)) return OR_ERR_NULL;
+    if (I > 0 && J > 0 && !A) return OR_ERR_NULL;
+    if (nnz > 0 && J > 0 && (!C || !D)) return OR_ERR_NULL;
+    if (I < 0 || K < 0 || L < 0 || J < 0 || ldc < J || ldd < J || lda < J) return OR_ERR_SHAPE;
+    if (dtype != OR_F32 && dtype != OR_F64) return OR_ERR_DTYPE;
+    for (int64_t e = 0; e < nnz; ++e)
+        if (ci[e] < 0 || ci[e] >= I || ck[e] < 0 || ck[e] >= K || cl[e] < 0 || cl[e] >= L) return OR_ERR_COORD_RANGE;
+    if (I == 0 || J == 0) return OR_OK;
+    long double *acc = (long double *)calloc((size_t)(I * J), sizeof(long double));
+    long double *macc = (long double *)calloc((size_t)(I * J), sizeof(long double));
+    if (!acc || !macc) { free(acc); free(macc); return OR_ERR_ALLOC; }
+    if (accumulate)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t j = 0; j < J; ++j) acc[i * J + j] = (long double)ldB(A, dtype, i * lda + j);
+    for (int64_t e = 0; e < nnz; ++e) {
+        const int64_t i = ci[e], k = ck[e], l = cl[e];
+        const long double b = (long double)ldB(bvals, dtype, e);
+        for (int64_t j = 0; j < J; ++j) {
+            const long double term = b * (long double)ldB(D, dtype, l * ldd + j) * (long double)ldB(C, dtype, k * ldc + j);
+            acc[i * J + j] += term;
+            macc[i * J + j] += fabsl(term);
+        }
+    }
+    for (int64_t i = 0; i < I; ++i)
+        for (int64_t j = 0; j < J; ++j) {
+            if (dtype == OR_F32) ((float *)A)[i * lda + j] = (float)acc[i * J + j];
+            else ((double *)A)[i * lda + j] = (double)acc[i * J + j];
+            if (mag) mag[i * J + j] = (double)macc[i * J + j];
+        }
+    free(acc);
+    free(macc);
+    return OR_OK;
+}
