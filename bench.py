@@ -9,7 +9,7 @@ several independent copies so that no step finds its operands in the 256 MB last
 GB/s on the algorithmic bytes, the roofline of the dominant kernel (timed with HIP events that the
 library records around it), and the CPU checker timed on the host.
 
-Other workloads (--workload cfg1|cfg3|cfg4|cfg5) print the same line for the other configurations.
+Other workloads (--workload cfg1|cfg3|cfg4|cfg5|rowband|sddmm|mttkrp) print the same line for the other configurations.
 """
 import argparse
 import json
@@ -79,14 +79,121 @@ def algorithmic_bytes(name, w, info, N, vbytes):
     return a + n * N * vbytes + m * N * vbytes
 
 
+def bench_mttkrp(args, torch, sp, dev):
+    """A[i,j] = B[i,k,l] * D[l,j] * C[k,j] (Section 6.3) on a synthetic tensor with the shape, entry count and output
+    width of the paper's experiment; one step = one sp_mttkrp."""
+    from gen import workloads as W
+    t0 = time.time()
+    w = (W.tensor3_slices(I=1200, K=900, L=2800, nnz=760_000, k_mean=120, l_mean=300) if args.small else W.tensor3_slices())
+    gen_s = time.time() - t0
+    fmt = args.format or "dss"
+    lt = (0, 1, 1) if fmt.startswith("dss") else (1, 1, 1)
+    order = (0, 2, 1) if fmt.endswith("-alt") else (0, 1, 2)
+    I, K, L = w.shape
+    J, nnz = w.J, w.nnz
+    steps = args.steps or 20
+    warmup = args.warmup or 3
+    ncopies = args.copies or 2
+    C_host, D_host = w.factors()
+    coords = [torch.from_numpy(c).to(dev) for c in (w.ci, w.ck, w.cl)]
+    vals_d = torch.from_numpy(w.vals).to(dev)
+    enc = sp.sp_encode(lt, order, args.width, args.width)
+    copies, pack_ms = [], []
+    for c in range(ncopies):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B = sp.sp_pack(enc, w.shape, coords, vals_d)
+        e1.record()
+        torch.cuda.synchronize()
+        pack_ms.append(e0.elapsed_time(e1))
+        copies.append((B, torch.from_numpy(C_host).to(dev), torch.from_numpy(D_host).to(dev),
+                       torch.zeros((I, J), dtype=torch.float64, device=dev)))
+    del coords, vals_d
+    info = sp.sp_tensor_info(copies[0][0])
+    nfib = int(sp.sp_crd(copies[0][0], 1).shape[0])
+    abytes = int(info.storageBytes) + (K + L + I) * J * 8          # the storage, C, D and A once each
+    flops = 2.0 * J * (nnz + nfib)                                 # a multiply-add per entry and per fibre and column
+    acc = bool(args.accumulate)
+
+    def run_steps(k, rotate=True):
+        for i in range(k):
+            B, Cd, Dd, Ad = copies[i % len(copies)] if rotate else copies[0]
+            sp.sp_mttkrp(B, Cd, Dd, Ad, accumulate=acc)
+
+    def timed(k, rotate=True):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run_steps(k, rotate)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / k
+
+    run_steps(warmup)
+    ms_cold = timed(steps)
+    run_steps(warmup, rotate=False)
+    ms_warm = timed(steps, rotate=False)
+    for c in copies:
+        sp.sp_tensor_tune(c[0], sp.SP_TUNE_PROFILE, 1)
+    run_steps(steps)
+    torch.cuda.synchronize()
+    tot_ms, launches = 0.0, 0
+    for c in copies:
+        a, b = sp.sp_profile_read(c[0])
+        tot_ms += a
+        launches += b
+        sp.sp_tensor_tune(c[0], sp.SP_TUNE_PROFILE, 0)
+    kernel_ms = tot_ms / max(launches, 1)
+    copies[0][3].zero_()
+    sp.sp_mttkrp(*copies[0], accumulate=False)
+    torch.cuda.synchronize()
+
+    cpu, parity = None, None
+    if not args.no_cpu:
+        import oracle
+        t0 = time.time()
+        ref, mag = oracle.mttkrp_coo(w.shape, w.ci, w.ck, w.cl, w.vals, C_host, D_host)
+        cpu_s = time.time() - t0
+        parity = bool(np.all(np.abs(copies[0][3].cpu().numpy() - ref) <= 1e-12 * mag))
+        cpu = {"value": abytes / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "the whole workload (%d stored entries x %d columns, one product), one run, %.3f s" % (nnz, J, cpu_s),
+               "gflops": flops / cpu_s / 1e9}
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    kernel_name = "mttkrp_windows_kernel (+ fix-up)"
+    out = {
+        "metric": "effective HBM GB/s (algorithmic bytes / time per product)",
+        "value": abytes / (ms_cold * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_cold, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "MTTKRP A[i,j]=B[i,k,l]*D[l,j]*C[k,j] (Section 6.3), B %dx%dx%d f64 synthetic with %d stored entries "
+                               "(shape, entry count and J=%d of the paper's experiment), stored as %s, pos/crd %d-bit" % (
+                                   I, K, L, nnz, J, fmt, args.width),
+                   "regime": "cold: rotating over %d copies (%.2f GB)" % (ncopies, ncopies * abytes / 1e9), "kernel": kernel_name,
+                   "accumulate": acc, "small": bool(args.small)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
+        "cpu_baseline": cpu,
+        "gflops": flops / (ms_cold * 1e-3) / 1e9,
+        "frac_of_peak": abytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "warm": {"ms_per_step": ms_warm, "value": abytes / (ms_warm * 1e-3) / 1e9},
+        "pack": {"ms": sorted(pack_ms)[len(pack_ms) // 2], "mnnz_per_s": nnz / (sorted(pack_ms)[len(pack_ms) // 2] * 1e-3) / 1e6},
+        "tensor": dict(w.stats, storage_bytes=int(info.storageBytes), fibres=nfib),
+        "parity_ok": parity,
+        "gen_s": gen_s,
+        "paper_ms": {"note": "the paper's table for its tensor on one Xeon W2135 core, for context only",
+                     "DSS": 2340.82, "DSS-alt": 1754.98, "DSS-vec": 1299.97},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm"])
-    ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense"],
-                    help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table)")
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm", "mttkrp"])
+    ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense", "dss", "dss-alt", "sss", "sss-alt"],
+                    help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table); "
+                         "mttkrp: dss (default) / dss-alt as in the paper's table, sss / sss-alt with a compressed outer level")
     ap.add_argument("--copies", type=int, default=0, help="independent copies of A, B, C rotated through (cold regime)")
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
@@ -107,6 +214,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     name = args.workload
+    if name == "mttkrp":
+        return bench_mttkrp(args, torch, sp, dev)
     t0 = time.time()
     w = make_workload(name, args.small)
     gen_s = time.time() - t0

@@ -120,6 +120,20 @@ sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, vo
 sp_status sp_sddmm(const sp_tensor *S, const void *A, int64_t lda, const void *B, int64_t ldb, int b_is_transposed,
                    int64_t K, void *X, void *stream);
 
+/* Matricized tensor times Khatri-Rao product A[i,j] = sum_{k,l} B[i,k,l] * D[l,j] * C[k,j] (Section 6.3, the MTTKRP
+ * kernel), B a packed rank-3 tensor of shape I x K x L.
+ *   B  stored with dimension i at the outermost level (dense or compressed) and two compressed inner levels in
+ *      either order of k and l: the two formats of the paper's experiment and their all-compressed variants.
+ *      Other encodings give SP_ERR_UNSUPPORTED (convert first).
+ *   C  DEVICE, K x J row-major, leading dimension ldc >= J, B's dtype.
+ *   D  DEVICE, L x J row-major, leading dimension ldd >= J, B's dtype.
+ *   A  DEVICE, I x J row-major, leading dimension lda >= J, B's dtype; must not overlap C or D.
+ *   accumulate = 0: A is overwritten (slices of B without stored entries become zero rows); 1: A += the product.
+ * Enqueues on `stream`; does not synchronise when the allocator is stream-ordered (the first call on a tensor
+ * allocates a small table and a scratch buffer through it).  Results are bit-reproducible from call to call. */
+sp_status sp_mttkrp(const sp_tensor *B, const void *C, int64_t ldc, const void *D, int64_t ldd, int64_t J,
+                    void *A, int64_t lda, int accumulate, void *stream);
+
 /* The paper's convert operation between two sparse encodings (Section 4.2: conversions go through an intermediate
  * coordinate scheme, which avoids one converter per pair of formats).  Every stored position of `from` (explicit and
  * padding zeros included) becomes a stored entry of the new tensor, which has `from`'s shape, dtype and allocator and

@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_convert", "sp_sddmm", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -68,6 +68,8 @@ def load_library():
     L.sp_values.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
     L.sp_unpack.restype = ci
     L.sp_unpack.argtypes = [vp, vp, vp, vp]
+    L.sp_mttkrp.restype = ci
+    L.sp_mttkrp.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, ci, vp]
     L.sp_sddmm.restype = ci
     L.sp_sddmm.argtypes = [vp, vp, i64, vp, i64, ci, i64, vp, vp]
     L.sp_convert.restype = ci
@@ -254,6 +256,22 @@ def sp_sddmm(S, A, B, X=None, b_is_transposed=False):
     _check(L.sp_sddmm(S._h, A.data_ptr(), int(A.stride(0)), B.data_ptr(), int(B.stride(0)), int(bool(b_is_transposed)), K,
                       X.data_ptr(), _stream_ptr()), "in sp_sddmm")
     return X
+
+
+def sp_mttkrp(B, C, D, A=None, accumulate=False):
+    """A[i,j] = sum_{k,l} B[i,k,l] * D[l,j] * C[k,j] for a packed rank-3 tensor B.  C: (K, J), D: (L, J); returns A (I, J)."""
+    L = load_library()
+    assert C.is_cuda and D.is_cuda and C.dtype == B.dtype and D.dtype == B.dtype and C.dim() == 2 and D.dim() == 2
+    assert C.shape[1] == D.shape[1] and C.stride(1) == 1 and D.stride(1) == 1
+    J = int(C.shape[1])
+    info = sp_tensor_info(B)
+    if A is None:
+        assert not accumulate
+        A = torch.empty((info.shape[0], J), dtype=B.dtype, device=B.device)
+    assert A.is_cuda and A.dtype == B.dtype and A.shape == (info.shape[0], J) and (J == 0 or A.stride(1) == 1)
+    _check(L.sp_mttkrp(B._h, C.data_ptr(), int(C.stride(0)), D.data_ptr(), int(D.stride(0)), J,
+                       A.data_ptr(), int(A.stride(0)), int(bool(accumulate)), _stream_ptr()), "in sp_mttkrp")
+    return A
 
 
 def sp_convert(A, enc):

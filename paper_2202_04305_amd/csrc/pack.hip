@@ -612,6 +612,8 @@ static void release_tensor_arrays(sp_tensor *t)
     mem.put(t->rowblocks.carry); t->rowblocks.carry = nullptr;
     mem.put(t->dense_partial); t->dense_partial = nullptr; t->dense_partial_bytes = 0;
     mem.put(t->spmm_carry); t->spmm_carry = nullptr; t->spmm_carry_bytes = 0;
+    mem.put(t->mttkrp_windows); t->mttkrp_windows = nullptr;
+    mem.put(t->mttkrp_carry); t->mttkrp_carry = nullptr; t->mttkrp_carry_bytes = 0;
     mem.put(t->nz_rowid); mem.put(t->nz_pos); mem.put(t->nz_rowblocks.start); mem.put(t->nz_rowblocks.carry);
     t->nz_rowid = t->nz_pos = t->nz_rowblocks.start = t->nz_rowblocks.carry = nullptr;
 }

@@ -64,6 +64,9 @@ struct sp_tensor {
     size_t dense_partial_bytes;
     void *spmm_carry;                // DEVICE scratch of the SpMM cut by entries (N values per block), grown on demand
     size_t spmm_carry_bytes;
+    void *mttkrp_windows;            // DEVICE int32[2 * windows]: fibre and slice holding the first entry of each window (rank 3)
+    void *mttkrp_carry;              // DEVICE scratch of the MTTKRP (J values per window), grown on demand
+    size_t mttkrp_carry_bytes;
     int tune_spmv, tune_csc, tune_spmm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
