@@ -20,7 +20,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int64_t kTW = 512;                  // stored entries per wave
+constexpr int64_t kTW = 256;                  // stored entries per wave
 
 __global__ __launch_bounds__(kThreads) void zero_rows_kernel(char *__restrict__ A, int64_t rows, int64_t row_bytes, int64_t ld_bytes)
 {
@@ -31,11 +31,15 @@ __global__ __launch_bounds__(kThreads) void zero_rows_kernel(char *__restrict__ 
 }
 
 // wfib[w] = level-1 fibre holding entry w*TW, wslc[w] = level-0 position holding that fibre (largest index whose
-// pos entry is <= the target: empty slices are skipped by construction)
+// pos entry is <= the target: empty slices are skipped by construction).  A window boundary w that is the first one
+// its slice crosses (the slice begins inside window w - 1) is appended to `cross` (count in cross[-1]); the order of
+// that list does not matter, every entry is an independent piece of work for the fix-up kernel.  An entry is the
+// pair (w, last window that begins inside the same slice).
 template <typename PT>
 __global__ __launch_bounds__(kThreads) void mttkrp_windows_table_kernel(const PT *__restrict__ pos1, int64_t nslc,
                                                                         const PT *__restrict__ pos2, int64_t nfib, int64_t nwin,
-                                                                        int32_t *__restrict__ wfib, int32_t *__restrict__ wslc)
+                                                                        int32_t *__restrict__ wfib, int32_t *__restrict__ wslc,
+                                                                        int32_t *__restrict__ cross)
 {
     const int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (w >= nwin) return;
@@ -53,13 +57,27 @@ __global__ __launch_bounds__(kThreads) void mttkrp_windows_table_kernel(const PT
     }
     wfib[w] = (int32_t)f;
     wslc[w] = (int32_t)lo;
+    if (w >= 1) {
+        const int64_t start = (int64_t)pos2[(int64_t)pos1[lo]];
+        if (start < s && start >= s - kTW) {
+            const int64_t end = (int64_t)pos2[(int64_t)pos1[lo + 1]];      // first entry past the slice
+            const int64_t a = (end - 1) / kTW;                             // last window that begins inside the slice
+            const int at = atomicAdd(&cross[-1], 1);
+            cross[2 * at] = (int32_t)w;
+            cross[2 * at + 1] = (int32_t)a;
+        }
+    }
 }
 
 template <typename VT, int V>
 struct vec_of { typedef VT type __attribute__((ext_vector_type(V))); };
 
-// grid = (windows / waves per block, column tiles of 64 * V columns)
-template <typename PT, typename CT, typename VT, int V, int U>
+// grid = (windows / waves per block rounded up to a multiple of 8, column tiles of 64 * V columns).  Each wave first
+// copies its window into LDS with coalesced loads that are all in flight together: the values, and instead of the
+// coordinates the byte offsets of the rows they select (crd2 -> row of the inner factor, crd1 -> row of the mid
+// factor, of type OT: 32 bits when both matrices are below 4 GB), plus the fibres' bounds relative to the window.
+// The walk over the fibres afterwards does no index arithmetic beyond one add per gather.
+template <typename PT, typename CT, typename VT, int V, int U, typename OT>
 __global__ __launch_bounds__(kThreads) void mttkrp_windows_kernel(const PT *__restrict__ pos1, const CT *__restrict__ crd0,
                                                                   const CT *__restrict__ crd1, const PT *__restrict__ pos2,
                                                                   const CT *__restrict__ crd2, const VT *__restrict__ val,
@@ -70,21 +88,54 @@ __global__ __launch_bounds__(kThreads) void mttkrp_windows_kernel(const PT *__re
                                                                   VT *__restrict__ carry, int64_t J, int accumulate)
 {
     typedef typename vec_of<VT, V>::type vec_t;
+    __shared__ VT s_val[kWaves][kTW];
+    __shared__ OT s_xoff[kWaves][kTW];
+    __shared__ OT s_moff[kWaves][kTW + 1];      // at most TW + 1 fibres meet a window (the last may only touch its end)
+    __shared__ int32_t s_off[kWaves][kTW + 2];
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (w >= nwin) return;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // Workgroups go to the 8 XCDs in turn, each with an L2 of its own.  Block b therefore takes the (b / 8)-th block of
+    // the (b % 8)-th eighth of the windows: an XCD walks a contiguous range of entries, so the rows of the factor
+    // matrices that a slice keeps coming back to are found in that XCD's L2.  (Only the mapping depends on this.)
+    const int64_t per = gridDim.x / 8;
+    const int64_t w = ((int64_t)(blockIdx.x % 8) * per + blockIdx.x / 8) * kWaves + wave;
+    const bool active = w < nwin;
+    const int64_t s = w * kTW;
+    const int64_t e = s + kTW < nnz ? s + kTW : nnz;
+    int64_t f0 = 0, q = 0, qend = 0;
+    int nf = 0;
+    bool cont = false;
+    if (active) {
+        f0 = wfib[w];
+        q = wslc[w];
+        nf = (int)((w + 1 < nwin ? (int64_t)wfib[w + 1] : nfib - 1) - f0) + 1;
+        const OT xrow = (OT)(ldx * (int64_t)sizeof(VT)), mrow = (OT)(ldm * (int64_t)sizeof(VT));
+        for (int64_t p = s + lane; p < e; p += 64) {
+            s_xoff[wave][p - s] = (OT)crd2[p] * xrow;
+            s_val[wave][p - s] = val[p];
+        }
+        for (int fi = lane; fi <= nf; fi += 64) {
+            int64_t o = (int64_t)pos2[f0 + fi] - s;
+            o = o < 0 ? 0 : o > e - s ? e - s : o;
+            s_off[wave][fi] = (int32_t)o;
+            if (fi < nf) s_moff[wave][fi] = (OT)crd1[f0 + fi] * mrow;
+        }
+        qend = (int64_t)pos1[q + 1];
+        cont = (int64_t)pos2[(int64_t)pos1[q]] < s;                // the first slice began in an earlier window
+    }
+    __syncthreads();
+    if (!active) return;
     const int64_t j0 = (int64_t)blockIdx.y * 64 * V;
     const int64_t jw = J - j0 < 64 * V ? J - j0 : 64 * V;          // columns of this tile (a multiple of V)
     const int LR = (int)(jw / V);                                  // lanes per row, 1..64
     const int S = 64 / LR;                                         // entries side by side
     const int jl = lane % LR, sl = lane / LR;
-    const bool live = sl < S;
     const int64_t col = j0 + (int64_t)jl * V;
-    const int64_t s = w * kTW;
-    const int64_t e = s + kTW < nnz ? s + kTW : nnz;
-    int64_t f = wfib[w], q = wslc[w];
-    int64_t qend = (int64_t)pos1[q + 1];
-    bool cont = (int64_t)pos2[(int64_t)pos1[q]] < s;               // the first slice began in an earlier window
+    const OT colb = (OT)(col * (int64_t)sizeof(VT));
+    int slot[U];                                                   // this lane's place in a group of S * U entries
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot[u] = sl < S ? sl + u * S : (1 << 24);   // lanes beyond LR * S never take an entry
+    const char *Xb = (const char *)X, *Mb = (const char *)M;
     vec_t acc = (vec_t)(0);
 
     auto flush = [&](int64_t slice) {
@@ -105,64 +156,85 @@ __global__ __launch_bounds__(kThreads) void mttkrp_windows_kernel(const PT *__re
         acc = (vec_t)(0);
     };
 
-    int64_t pa = (int64_t)pos2[f];
-    while (pa < e) {                                               // wave-uniform throughout
-        const int64_t pb = (int64_t)pos2[f + 1];
+    vec_t c_next = *(const vec_t *)(Mb + (s_moff[wave][0] + colb));
+    int b = s_off[wave][0];
+    for (int fi = 0; fi < nf; ++fi) {                              // wave-uniform throughout
+        const vec_t c = c_next;
+        const int a = b;
+        b = s_off[wave][fi + 1];
+        if (fi + 1 < nf) c_next = *(const vec_t *)(Mb + (s_moff[wave][fi + 1] + colb));
+        if (b <= a) continue;                                      // only the last fibre, when it begins where the window ends
+        const int64_t f = f0 + fi;
         if (f >= qend) {
             flush(q);
             do { ++q; qend = (int64_t)pos1[q + 1]; } while (f >= qend);
         }
-        const int64_t a = pa > s ? pa : s, b = pb < e ? pb : e;
-        const vec_t c = *(const vec_t *)(M + (int64_t)crd1[f] * ldm + col);
         vec_t t[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) t[u] = (vec_t)(0);
-        for (int64_t p0 = a; p0 < b; p0 += (int64_t)S * U) {
-            int64_t l[U];
+        for (int p0 = a; p0 < b; p0 += S * U) {
             VT v[U];
             vec_t xv[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t pp = p0 + sl + (int64_t)u * S;
-                const bool in = live && pp < b;
-                l[u] = (int64_t)crd2[in ? pp : a];
-                v[u] = in ? val[pp] : (VT)0;
+                if (p0 + u * S < b) {                              // wave-uniform: no gather for a slot group past the fibre's end
+                    const int pp = p0 + slot[u];
+                    const int idx = pp < b ? pp : b - 1;
+                    v[u] = s_val[wave][idx];
+                    xv[u] = *(const vec_t *)(Xb + (s_xoff[wave][idx] + colb));
+                }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) xv[u] = *(const vec_t *)(X + l[u] * ldx + col);
-#pragma unroll
-            for (int u = 0; u < U; ++u) t[u] += v[u] * xv[u];
+            for (int u = 0; u < U; ++u) {
+                if (p0 + u * S < b) {
+                    if (p0 + slot[u] < b) t[u] += v[u] * xv[u];
+                }
+            }
         }
 #pragma unroll
         for (int u = 1; u < U; ++u) t[0] += t[u];
         acc += c * t[0];
-        ++f;
-        pa = pb;
-        if (f >= nfib) break;
     }
     flush(q);
 }
 
-// A wave per window boundary: the first boundary a slice crosses adds all of that slice's carries, in window order.
-template <typename PT, typename CT, typename VT>
-__global__ __launch_bounds__(kThreads) void mttkrp_fixup_kernel(const PT *__restrict__ pos1, const CT *__restrict__ crd0,
-                                                                const PT *__restrict__ pos2, const int32_t *__restrict__ wslc,
-                                                                int64_t nwin, int64_t J, const VT *__restrict__ carry,
-                                                                VT *__restrict__ A, int64_t lda)
+// A block per listed window boundary (the first one a slice crosses): adds all of that slice's carries to A.  The
+// carries are summed in a fixed pattern (four strided partial sums per column, combined in order), so the result is
+// the same on every call.
+constexpr int kFixThreads = 1024, kFixGroups = kFixThreads / 64;
+template <typename CT, typename VT>
+__global__ __launch_bounds__(kFixThreads) void mttkrp_fixup_kernel(const CT *__restrict__ crd0, const int32_t *__restrict__ wslc,
+                                                                   const int32_t *__restrict__ cross, int64_t nwin, int64_t J,
+                                                                   const VT *__restrict__ carry, VT *__restrict__ A, int64_t lda)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t b = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6) + 1;
-    if (b >= nwin) return;
-    const int64_t q = wslc[b];
-    const int64_t start = (int64_t)pos2[(int64_t)pos1[q]];
-    if (start >= b * kTW || start < (b - 1) * kTW) return;        // not crossed here, or crossed earlier already
-    const int64_t i = crd0 ? (int64_t)crd0[q] : q;
-    int64_t last = b;
-    while (last + 1 < nwin && wslc[last + 1] == q) ++last;
-    for (int64_t j = lane; j < J; j += 64) {
-        VT sum = 0;
-        for (int64_t bb = b; bb <= last; ++bb) sum += carry[bb * J + j];
-        A[i * lda + j] += sum;
+    __shared__ VT part[kFixGroups][64];
+    if ((int)blockIdx.x >= cross[-1]) return;                      // block-uniform
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int64_t b = cross[2 * blockIdx.x], last = cross[2 * blockIdx.x + 1];
+    const int32_t q = wslc[b];
+    const int64_t i = crd0 ? (int64_t)crd0[q] : (int64_t)q;
+    for (int64_t jb = 0; jb < J; jb += 64) {                       // block-uniform
+        const int64_t j = jb + lane;
+        VT s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+        if (j < J) {
+            int64_t bb = b + g;
+            for (; bb + 3 * kFixGroups <= last; bb += 4 * kFixGroups) {
+                s0 += carry[bb * J + j];
+                s1 += carry[(bb + kFixGroups) * J + j];
+                s2 += carry[(bb + 2 * kFixGroups) * J + j];
+                s3 += carry[(bb + 3 * kFixGroups) * J + j];
+            }
+            for (; bb <= last; bb += kFixGroups) s0 += carry[bb * J + j];
+        }
+        part[g][lane] = (s0 + s1) + (s2 + s3);
+        __syncthreads();
+        if (g == 0 && j < J) {
+            VT tot = part[0][lane];
+#pragma unroll
+            for (int k = 1; k < kFixGroups; ++k) tot += part[k][lane];
+            A[i * lda + j] += tot;
+        }
+        __syncthreads();
     }
 }
 
@@ -185,12 +257,15 @@ sp_status mttkrp_t(const sp_tensor *B, const VT *M, int64_t ldm, const VT *X, in
     const int64_t nwin = ceil_div(nnz, kTW);
     sp_tensor *Bt = const_cast<sp_tensor *>(B);
     sp_mem mem{B->alloc, B->free_, B->ctx};
+    const int64_t ncross = nslc < nwin - 1 ? nslc : nwin - 1;        // a slice has at most one first crossing
+    const size_t table_bytes = (size_t)(2 * nwin + 4 + (ncross > 0 ? 2 * ncross : 0)) * 4;
     if (!Bt->mttkrp_windows) {
-        Bt->mttkrp_windows = mem.get((size_t)nwin * 8);
+        Bt->mttkrp_windows = mem.get(table_bytes);
         if (!Bt->mttkrp_windows) return SP_ERR_ALLOC;
-        int32_t *wfib = (int32_t *)Bt->mttkrp_windows, *wslc = wfib + nwin;
+        int32_t *wfib = (int32_t *)Bt->mttkrp_windows, *wslc = wfib + nwin, *cross = wslc + nwin + 4;
+        SP_TRY(spmi_fill_zero(wslc + nwin, 16, st));               // cross[-1] = 0: the length of the list
         hipLaunchKernelGGL(mttkrp_windows_table_kernel<PT>, dim3((unsigned)ceil_div(nwin, kThreads)), dim3(kThreads), 0, st, pos1, nslc,
-                           pos2, nfib, nwin, wfib, wslc);
+                           pos2, nfib, nwin, wfib, wslc, cross);
         SP_HIP(hipGetLastError());
     }
     const size_t need = (size_t)nwin * J * sizeof(VT);
@@ -200,32 +275,36 @@ sp_status mttkrp_t(const sp_tensor *B, const VT *M, int64_t ldm, const VT *X, in
         if (!Bt->mttkrp_carry) return SP_ERR_ALLOC;
         Bt->mttkrp_carry_bytes = need;
     }
-    const int32_t *wfib = (const int32_t *)B->mttkrp_windows, *wslc = wfib + nwin;
+    const int32_t *wfib = (const int32_t *)B->mttkrp_windows, *wslc = wfib + nwin, *cross = wslc + nwin + 4;
     constexpr int VV = 16 / sizeof(VT);
     const bool vec = J % VV == 0 && ldm % VV == 0 && ldx % VV == 0 && lda % VV == 0 && (uintptr_t)M % 16 == 0 && (uintptr_t)X % 16 == 0 &&
                      (uintptr_t)A % 16 == 0 && (uintptr_t)B->mttkrp_carry % 16 == 0;
+    // byte offsets into the factor matrices fit 32 bits when both are below 4 GB
+    const int64_t K = B->shape[1], L = B->shape[2];
+    const int64_t rows_m = B->enc.perm[1] == 1 ? K : L, rows_x = B->enc.perm[1] == 1 ? L : K;
+    const bool small = (uint64_t)rows_m * (uint64_t)ldm * sizeof(VT) < ((uint64_t)1 << 32) && (uint64_t)rows_x * (uint64_t)ldx * sizeof(VT) < ((uint64_t)1 << 32);
     {
         sp_prof_scope prof(B, st);
-        const unsigned gx = (unsigned)ceil_div(nwin, kWaves);
-#define SPMI_MTTKRP(V, U)                                                                                                              \
-    hipLaunchKernelGGL((mttkrp_windows_kernel<PT, CT, VT, V, U>), dim3(gx, (unsigned)ceil_div(J, 64 * V)), dim3(kThreads), 0, st, pos1, crd0, \
+        const unsigned gx = (unsigned)(ceil_div(ceil_div(nwin, kWaves), 8) * 8);   // a multiple of 8: see the block mapping in the kernel
+#define SPMI_MTTKRP(V, U, OT)                                                                                                          \
+    hipLaunchKernelGGL((mttkrp_windows_kernel<PT, CT, VT, V, U, OT>), dim3(gx, (unsigned)ceil_div(J, 64 * V)), dim3(kThreads), 0, st, pos1, crd0, \
                        crd1, pos2, crd2, (const VT *)B->values, wfib, wslc, nwin, nfib, nnz, M, ldm, X, ldx, A, lda,                    \
                        (VT *)B->mttkrp_carry, J, accumulate)
-        const int64_t lanes = vec ? J / VV : J;                 // lanes a row of the (first) column tile takes
-        const bool few_side_by_side = 64 / (lanes < 64 ? lanes : 64) < 4;
-        if (vec) {
-            if (few_side_by_side) SPMI_MTTKRP(VV, 4);
-            else SPMI_MTTKRP(VV, 2);
-        } else {
-            if (few_side_by_side) SPMI_MTTKRP(1, 4);
-            else SPMI_MTTKRP(1, 2);
-        }
+#define SPMI_MTTKRP_V(V)                                                        \
+    do {                                                                        \
+        const int64_t lanes = J / V < 64 ? J / V : 64;                          \
+        if (64 / lanes < 4) { if (small) SPMI_MTTKRP(V, 4, uint32_t); else SPMI_MTTKRP(V, 4, uint64_t); } \
+        else { if (small) SPMI_MTTKRP(V, 2, uint32_t); else SPMI_MTTKRP(V, 2, uint64_t); }               \
+    } while (0)
+        if (vec) SPMI_MTTKRP_V(VV);
+        else SPMI_MTTKRP_V(1);
+#undef SPMI_MTTKRP_V
 #undef SPMI_MTTKRP
         SP_HIP(hipGetLastError());
     }
-    if (nwin > 1) {
-        hipLaunchKernelGGL((mttkrp_fixup_kernel<PT, CT, VT>), dim3((unsigned)ceil_div(nwin - 1, kWaves)), dim3(kThreads), 0, st, pos1, crd0,
-                           pos2, wslc, nwin, J, (const VT *)B->mttkrp_carry, A, lda);
+    if (ncross > 0) {
+        hipLaunchKernelGGL((mttkrp_fixup_kernel<CT, VT>), dim3((unsigned)ncross), dim3(kFixThreads), 0, st, crd0, wslc, cross, nwin, J,
+                           (const VT *)B->mttkrp_carry, A, lda);
         SP_HIP(hipGetLastError());
     }
     return SP_OK;
