@@ -31,6 +31,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg2", 32, 3): 378.9e6,      # profiles/spmv_segmented_cfg2_w32_hbm_traffic.txt
     ("cfg2", 32, 2): 1447.0e6,     # profiles/spmv_stream_cfg2_w32_hbm_traffic.txt
     ("cfg3", 32, 0): 9.65e9,       # profiles/spmm_windows_cfg3_w32_profile.txt
+    ("mttkrp", 32, "dss"): 16.06e9,  # profiles/mttkrp_windows_tensor3_w32_profile.txt
 }
 
 
@@ -77,6 +78,23 @@ def algorithmic_bytes(name, w, info, N, vbytes):
         # x: only the touched elements; y: the whole vector is written in overwrite mode
         return a + w.nnz * vbytes + m * vbytes
     return a + n * N * vbytes + m * N * vbytes
+
+
+def copy_yardstick(torch, sp, dev):
+    """GB/s of the library's plain copy kernel on 1 GiB (read + write = 2 GiB of traffic)."""
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        sp.sp_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        sp.sp_stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def bench_mttkrp(args, torch, sp, dev):
@@ -147,6 +165,7 @@ def bench_mttkrp(args, torch, sp, dev):
     copies[0][3].zero_()
     sp.sp_mttkrp(*copies[0], accumulate=False)
     torch.cuda.synchronize()
+    copy_gbs = copy_yardstick(torch, sp, dev)
 
     cpu, parity = None, None
     if not args.no_cpu:
@@ -170,11 +189,12 @@ def bench_mttkrp(args, torch, sp, dev):
                    "regime": "cold: rotating over %d copies (%.2f GB)" % (ncopies, ncopies * abytes / 1e9), "kernel": kernel_name,
                    "accumulate": acc, "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
+                     "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("mttkrp", args.width, fmt)), "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
         "cpu_baseline": cpu,
         "gflops": flops / (ms_cold * 1e-3) / 1e9,
         "frac_of_peak": abytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "warm": {"ms_per_step": ms_warm, "value": abytes / (ms_warm * 1e-3) / 1e9},
+        "copy_kernel_gbs": copy_gbs,
         "pack": {"ms": sorted(pack_ms)[len(pack_ms) // 2], "mnnz_per_s": nnz / (sorted(pack_ms)[len(pack_ms) // 2] * 1e-3) / 1e6},
         "tensor": dict(w.stats, storage_bytes=int(info.storageBytes), fibres=nfib),
         "parity_ok": parity,
@@ -307,21 +327,7 @@ def main():
         sp.sp_matmul(copies[0][0], copies[0][1], copies[0][2], accumulate=False)
     torch.cuda.synchronize()
 
-    # yardstick: plain copy kernel on 1 GiB (read + write = 2 GiB of traffic)
-    nbytes = 1 << 30
-    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
-    dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    for _ in range(3):
-        sp.sp_stream_copy(dst, src)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
-        sp.sp_stream_copy(dst, src)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 2.0 * nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
+    copy_gbs = copy_yardstick(torch, sp, dev)
 
     # CPU checker on the same input, one host core; also the parity check of this very run
     cpu = None

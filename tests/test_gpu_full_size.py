@@ -145,3 +145,42 @@ def test_cfg5_csc_full_size():
     ref, mag = sampled_rows_product(w, rpick, B)
     assert_product_close(C[torch.from_numpy(rpick).to(DEV)], ref, mag, np.float32, "cfg5 sampled rows")
     assert not bool(torch.isnan(C).any())
+
+
+def test_full_size_mttkrp_both_storage_orders():
+    """The 12092 x 9184 x 28818 tensor with 76.9M entries and 42 columns (the shape of the paper's MTTKRP experiment):
+    sampled output rows (the heaviest slices, the lightest, and seeded others), each computed by the checker from
+    exactly the entries of its slice; the rank-3 storage through its invariants and the same slices' values."""
+    say("generating mttkrp tensor")
+    w = W.tensor3_slices()
+    say(w.stats)
+    C, D = w.factors()
+    I = w.shape[0]
+    per_slice = np.bincount(w.ci, minlength=I)
+    order_by_size = np.argsort(per_slice, kind="stable")
+    sample = np.unique(np.concatenate([order_by_size[:20], order_by_size[-6:], prng.below(W.BASE_SEED + 70, 1, 120, I)]))
+    sel = np.isin(w.ci, sample)
+    say("checker on", int(sel.sum()), "entries of", sample.size, "slices")
+    ref, mag = oracle.mttkrp_coo(w.shape, w.ci[sel], w.ck[sel], w.cl[sel], w.vals[sel], C, D)
+    coords = [dev(c) for c in (w.ci, w.ck, w.cl)]
+    vals = dev(w.vals)
+    for order in [(0, 1, 2), (0, 2, 1)]:
+        say("case full-size mttkrp", order)
+        B = sp.sp_pack(sp.sp_encode((0, 1, 1), order, 32, 32), w.shape, coords, vals)
+        info = sp.sp_tensor_info(B)
+        assert info.nvalues == w.nnz
+        pos1, pos2 = sp.sp_pos(B, 1).long(), sp.sp_pos(B, 2).long()
+        crd1, crd2 = sp.sp_crd(B, 1).long(), sp.sp_crd(B, 2).long()
+        assert pos1.numel() == I + 1 and int(pos1[0]) == 0 and int(pos1[-1]) == crd1.numel() == pos2.numel() - 1
+        assert int(pos2[0]) == 0 and int(pos2[-1]) == crd2.numel() == w.nnz
+        assert bool(torch.all(pos1[1:] >= pos1[:-1])) and bool(torch.all(pos2[1:] > pos2[:-1]))     # no empty fibre
+        assert bool(torch.all((crd1 >= 0) & (crd1 < w.shape[order[1]]))) and bool(torch.all((crd2 >= 0) & (crd2 < w.shape[order[2]])))
+        got_per_slice = (pos2[pos1[1:]] - pos2[pos1[:-1]]).cpu().numpy()
+        assert np.array_equal(got_per_slice, per_slice)
+        A = torch.full((I, w.J), float("nan"), dtype=torch.float64, device=DEV)
+        sp.sp_mttkrp(B, dev(C), dev(D), A)
+        Ah = A.cpu().numpy()
+        err = np.abs(Ah[sample] - ref[sample])
+        assert np.all(err <= 1e-12 * mag[sample]), float(np.max(err / np.maximum(mag[sample], 1e-300)))
+        assert np.all(Ah[per_slice == 0] == 0.0) and not np.isnan(Ah).any()
+        B.free()
