@@ -57,6 +57,8 @@ def lib():
         L.oracle_matmul_storage.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
         L.oracle_sddmm_coo.restype = ci
         L.oracle_sddmm_coo.argtypes = [i64, i64, i64, i64, vp, vp, vp, ci, vp, i64, vp, i64, vp, vp]
+        L.oracle_spgemm_coo.restype = i64
+        L.oracle_spgemm_coo.argtypes = [i64, i64, i64, i64, vp, vp, vp, i64, vp, vp, vp, ci, vp, vp, vp, vp]
         L.oracle_mttkrp_coo.restype = ci
         L.oracle_mttkrp_coo.argtypes = [i64, i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, i64, vp, i64, vp, i64, ci, vp]
         L.oracle_matmul_coo_f64seq.restype = ci
@@ -236,3 +238,24 @@ def mttkrp_coo(shape, ci, ck, cl, bvals, C, D, accumulate=False, A=None):
     if st != OK:
         raise OracleError(st)
     return Aout, mag
+
+
+def spgemm_coo(shape_a, ra, ca, va, shape_b, rb, cb, vb):
+    """(rows, cols, vals, mag) of C = A.B for two sparse matrices given as COO triples, in row-major order: every (i, j)
+    for which a pair A[i,k], B[k,j] of stored entries exists, by the plain definition."""
+    m, kdim = shape_a
+    k2, n = shape_b
+    assert kdim == k2
+    va = np.ascontiguousarray(va)
+    dt = _dt(va.dtype)
+    vb = np.ascontiguousarray(vb, dtype=va.dtype)
+    ra, ca, rb, cb = [np.ascontiguousarray(x, dtype=np.int64) for x in (ra, ca, rb, cb)]
+    args = (m, kdim, n, ra.shape[0], _ptr(ra), _ptr(ca), _ptr(va), rb.shape[0], _ptr(rb), _ptr(cb), _ptr(vb), dt)
+    cnt = lib().oracle_spgemm_coo(*args, None, None, None, None)
+    if cnt < 0:
+        raise OracleError(int(-cnt))
+    ci, cj = np.empty(cnt, dtype=np.int64), np.empty(cnt, dtype=np.int64)
+    cv, mag = np.empty(cnt, dtype=va.dtype), np.empty(cnt, dtype=np.float64)
+    got = lib().oracle_spgemm_coo(*args, _ptr(ci), _ptr(cj), _ptr(cv), _ptr(mag))
+    assert got == cnt
+    return ci, cj, cv, mag

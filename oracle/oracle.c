@@ -434,3 +434,60 @@ int oracle_mttkrp_coo(int64_t I, int64_t K, int64_t L, int64_t J, int64_t nnz, c
     free(macc);
     return OR_OK;
 }
+
+/* Sparse times sparse with a sparse result (Sections 4.2 and 4.4, the SpMSpM kernel): C[i,j] = sum_k A[i,k] * B[k,j]
+ * with A (m x kdim) and B (kdim x n) given as COO triples in any order.  The result is what the paper's row-wise
+ * loop with a workspace inserts: an entry (i,j) is stored as soon as one pair A[i,k], B[k,j] of stored entries
+ * exists, whatever its sum comes to (explicit zeros and cancellations stay stored).  Plain definition on a dense
+ * m x n accumulator in long double (this is a checker for moderate sizes: 25 bytes per element of C), every pair
+ * taken in the order of A's triples, then of B's triples within row k; each sum is rounded once at the end.
+ * Output in row-major lexicographic order: first call with ci = NULL to get the count, then with arrays of that
+ * length.  mag[e] = sum of |a * b| over the pairs of entry e. */
+int64_t oracle_spgemm_coo(int64_t m, int64_t kdim, int64_t n, int64_t nnzA, const int64_t *ra, const int64_t *ca,
+                          const void *va, int64_t nnzB, const int64_t *rb, const int64_t *cb, const void *vb, int dtype,
+                          int64_t *ci, int64_t *cj, void *cv, double *mag)
+{
+    if ((nnzA > 0 && (!ra || !ca || !va)) || (nnzB > 0 && (!rb || !cb || !vb))) return -OR_ERR_NULL;
+    if (m < 0 || kdim < 0 || n < 0) return -OR_ERR_SHAPE;
+    if (dtype != OR_F32 && dtype != OR_F64) return -OR_ERR_DTYPE;
+    for (int64_t e = 0; e < nnzA; ++e)
+        if (ra[e] < 0 || ra[e] >= m || ca[e] < 0 || ca[e] >= kdim) return -OR_ERR_COORD_RANGE;
+    for (int64_t e = 0; e < nnzB; ++e)
+        if (rb[e] < 0 || rb[e] >= kdim || cb[e] < 0 || cb[e] >= n) return -OR_ERR_COORD_RANGE;
+    if (m == 0 || n == 0) return 0;
+    if ((long double)m * (long double)n > 268435456.0L) return -OR_ERR_TOO_LARGE;
+    /* B's triples grouped by row k, keeping their order: start[k] .. start[k+1] index into `by_row` */
+    int64_t *start = (int64_t *)calloc((size_t)kdim + 2, sizeof(int64_t));
+    int64_t *by_row = (int64_t *)malloc((size_t)(nnzB > 0 ? nnzB : 1) * sizeof(int64_t));
+    long double *acc = (long double *)calloc((size_t)(m * n), sizeof(long double));
+    double *macc = (double *)calloc((size_t)(m * n), sizeof(double));
+    unsigned char *filled = (unsigned char *)calloc((size_t)(m * n), 1);
+    if (!start || !by_row || !acc || !macc || !filled) { free(start); free(by_row); free(acc); free(macc); free(filled); return -OR_ERR_ALLOC; }
+    for (int64_t e = 0; e < nnzB; ++e) start[rb[e] + 2]++;
+    for (int64_t k = 0; k < kdim; ++k) start[k + 2] += start[k + 1];
+    for (int64_t e = 0; e < nnzB; ++e) by_row[start[rb[e] + 1]++] = e;      /* afterwards start[k+1] = end of row k */
+    for (int64_t e = 0; e < nnzA; ++e) {
+        const int64_t i = ra[e], k = ca[e];
+        const long double a = (long double)ldB(va, dtype, e);
+        for (int64_t t = start[k]; t < start[k + 1]; ++t) {
+            const int64_t eb = by_row[t], j = cb[eb];
+            const long double prod = a * (long double)ldB(vb, dtype, eb);
+            acc[i * n + j] += prod;
+            macc[i * n + j] += (double)fabsl(prod);
+            filled[i * n + j] = 1;
+        }
+    }
+    int64_t count = 0;
+    for (int64_t x = 0; x < m * n; ++x)
+        if (filled[x]) {
+            if (ci) {
+                ci[count] = x / n;
+                cj[count] = x % n;
+                if (dtype == OR_F32) ((float *)cv)[count] = (float)acc[x]; else ((double *)cv)[count] = (double)acc[x];
+                if (mag) mag[count] = macc[x];
+            }
+            ++count;
+        }
+    free(start); free(by_row); free(acc); free(macc); free(filled);
+    return count;
+}
