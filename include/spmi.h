@@ -134,6 +134,16 @@ sp_status sp_sddmm(const sp_tensor *S, const void *A, int64_t lda, const void *B
 sp_status sp_mttkrp(const sp_tensor *B, const void *C, int64_t ldc, const void *D, int64_t ldd, int64_t J,
                     void *A, int64_t lda, int accumulate, void *stream);
 
+/* Sparse times sparse with a sparse result: C[i,j] = sum_k A[i,k] * B[k,j] (Section 4.2, the SpMSpM kernel; Section 4.4
+ * describes the generated loop with its workspace; Section 6.2 measures it).  A: packed rank-2 tensor m x k of any
+ * encoding; B: packed k x n with a compressed inner level (CSR, DCSR as they are; CSC, DCSC through a row-major copy
+ * that the tensor builds on first use and keeps); a B with a dense inner level gives SP_ERR_UNSUPPORTED (convert
+ * first).  *C is a new tensor m x n under `encC` with A's dtype and allocator: it stores every (i,j) for which a pair of
+ * stored entries A[i,k], B[k,j] exists, whatever the sum comes to, and each sum runs over k in A's storage order, so
+ * the result is the same bits on every call.  Synchronises like sp_pack.  Errors: NULL, RANK, SHAPE (inner sizes
+ * differ), DTYPE (A and B differ), TOO_LARGE (2^31 or more pairs), WIDTH (C does not fit encC's widths), ALLOC, HIP. */
+sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C);
+
 /* The paper's convert operation between two sparse encodings (Section 4.2: conversions go through an intermediate
  * coordinate scheme, which avoids one converter per pair of formats).  Every stored position of `from` (explicit and
  * padding zeros included) becomes a stored entry of the new tensor, which has `from`'s shape, dtype and allocator and

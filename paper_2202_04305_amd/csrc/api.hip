@@ -160,7 +160,7 @@ extern "C" sp_status sp_profile_read(sp_tensor *t, double *ms_total, int64_t *la
 
 // Row-major copy of a column-major tensor, through the coordinate scheme (the paper's route for
 // conversions, Section 4.2).  Built on first use and kept by the handle.
-static sp_status build_transposed(sp_tensor *A, hipStream_t st)
+sp_status spmi_build_transposed(sp_tensor *A, hipStream_t st)
 {
     if (A->transposed) return SP_OK;
     sp_mem mem{A->alloc, A->free_, A->ctx};
@@ -225,7 +225,7 @@ extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int
     if (A->enc.perm[0] == 0) return spmi_matmul_rowmajor(A, B, N, ldb, C, ldc, accumulate, st);
     int mode = A->tune_csc ? A->tune_csc : 2;
     if (mode == 1) return spmi_matmul_colmajor_scatter(A, B, N, ldb, C, ldc, accumulate, st);
-    SP_TRY(build_transposed(const_cast<sp_tensor *>(A), st));
+    SP_TRY(spmi_build_transposed(const_cast<sp_tensor *>(A), st));
     return spmi_matmul_rowmajor(A->transposed, B, N, ldb, C, ldc, accumulate, st);
 }
 

@@ -641,6 +641,256 @@ static sp_status launch_emit(const uint64_t *keys, int64_t nnz, uint64_t stride,
     return SP_OK;
 }
 
+// Everything after the keys exist: sort, duplicates (an error, or summed in sorted order when `sum_duplicates`), the
+// level sweep, narrow copies, values, and the tables the product kernels want.  keys / payload: nnz entries in
+// temporaries of `tmp` (the payload is the value's bits); flags: 64 zeroed bytes, flags[0] != 0 afterwards on the
+// device means a coordinate was out of range.  t->size[] and t->enc are set.  On success t->nnz is the number of
+// distinct entries.
+template <typename VT>
+__global__ __launch_bounds__(kThreads) void sum_runs_kernel(const uint64_t *__restrict__ keys, const VT *__restrict__ vals, int64_t n,
+                                                            const uint32_t *__restrict__ head_excl, uint64_t *__restrict__ keys_out,
+                                                            VT *__restrict__ vals_out)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    const uint64_t k = keys[e];
+    if (e > 0 && keys[e - 1] == k) return;            // not the head of its run
+    VT sum = vals[e];
+    for (int64_t x = e + 1; x < n && keys[x] == k; ++x) sum += vals[x];     // sorted order = the order the entries came in
+    const uint32_t u = head_excl[e];
+    keys_out[u] = k;
+    vals_out[u] = sum;
+}
+
+__global__ __launch_bounds__(kThreads) void mark_heads_kernel(const uint64_t *__restrict__ keys, int64_t n, uint32_t *__restrict__ mark)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e < n) mark[e] = (e == 0 || keys[e] != keys[e - 1]) ? 1u : 0u;
+}
+
+static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payload, int key_bits, bool sum_duplicates, int *flags,
+                           sp_scratch &tmp, const sp_mem &mem, hipStream_t st)
+{
+    const sp_encoding *enc = &t->enc;
+    const int rank = enc->rank;
+    const sp_dtype dt = (sp_dtype)t->dtype;
+    const int vsz0 = dt == SP_F64 ? 8 : 4;
+    const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
+    uint64_t *parentA = nullptr, *parentB = nullptr;      // allocated when a level needs them
+    uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
+    if (!child) return SP_ERR_ALLOC;
+    if (nnz > 0) {
+        SP_TRY(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st));
+        if (!sum_duplicates) {
+            hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
+            SP_HIP(hipGetLastError());
+        }
+    }
+    int hflags[2] = {0, 0};
+    SP_HIP(hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
+    SP_HIP(hipStreamSynchronize(st));
+    if (hflags[0]) return SP_ERR_COORD_RANGE;
+    if (hflags[1]) return SP_ERR_DUPLICATE;
+    if (sum_duplicates && nnz > 1) {
+        hipLaunchKernelGGL(mark_heads_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, child);
+        SP_HIP(hipGetLastError());
+        SP_TRY(spmi_exclusive_scan(child, nnz, 32, tmp, st));
+        uint32_t last_excl = 0;
+        SP_HIP(hipMemcpyAsync(&last_excl, child + (nnz - 1), 4, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipStreamSynchronize(st));
+        // the last entry is a head exactly when its exclusive count differs from that of a head before it: recount it
+        uint64_t lastk[2] = {0, 0};
+        SP_HIP(hipMemcpyAsync(lastk, keys + (nnz - 2), 16, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipStreamSynchronize(st));
+        const int64_t distinct = (int64_t)last_excl + (lastk[0] != lastk[1] ? 1 : 0);
+        if (distinct != nnz) {
+            uint64_t *k2 = (uint64_t *)tmp.get((size_t)distinct * 8);
+            void *v2 = tmp.get((size_t)distinct * vsz0);
+            if (!k2 || !v2) return SP_ERR_ALLOC;
+            if (dt == SP_F64)
+                hipLaunchKernelGGL(sum_runs_kernel<double>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys,
+                                   (const double *)payload, nnz, (const uint32_t *)child, k2, (double *)v2);
+            else
+                hipLaunchKernelGGL(sum_runs_kernel<float>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys,
+                                   (const float *)payload, nnz, (const uint32_t *)child, k2, (float *)v2);
+            SP_HIP(hipGetLastError());
+            keys = k2;
+            payload = v2;
+            nnz = distinct;
+        }
+    }
+    t->nnz = nnz;
+
+    // level sweep
+    const uint64_t *pin = nullptr;      // nullptr = the position at the level above is the key prefix (dense levels so far)
+    bool dense_prefix = true;
+    int which = 0;
+    int64_t P = 1;
+    for (int l = 0; l < rank; ++l) {
+        uint64_t stride = 1;
+        for (int k = l + 1; k < rank; ++k) stride *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
+        const uint64_t size = (uint64_t)(t->size[l] > 0 ? t->size[l] : 1);
+        if (enc->lt[l] == SP_DENSE && dense_prefix) {
+            P *= t->size[l];                  // nothing to compute: the position at this level is the key prefix
+            continue;
+        }
+        const bool last_compressed = enc->lt[l] == SP_COMPRESSED && l == rank - 1;
+        uint64_t *pout = nullptr;
+        if (!last_compressed && nnz > 0) {
+            uint64_t *&buf = which ? parentB : parentA;
+            if (!buf) { buf = (uint64_t *)tmp.get(cnt * 8); if (!buf) return SP_ERR_ALLOC; }
+            pout = buf;
+        }
+        if (enc->lt[l] == SP_DENSE) {
+            if (nnz > 0) {
+                hipLaunchKernelGGL(dense_level_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz,
+                                   stride, size, pin, pout);
+                SP_HIP(hipGetLastError());
+            }
+            P *= t->size[l];
+        } else {
+            int64_t nchild = nnz;
+            const uint32_t *child_excl = nullptr;
+            if (l != rank - 1 && nnz > 0) {
+                hipLaunchKernelGGL(mark_children_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, stride, child);
+                SP_HIP(hipGetLastError());
+                SP_TRY(spmi_exclusive_scan(child, nnz, 32, tmp, st));
+                // children = exclusive[nnz-1] + mark[nnz-1]; the last mark is recomputed from the two last keys
+                uint32_t last_excl = 0;
+                uint64_t lastk[2] = {0, 0};
+                SP_HIP(hipMemcpyAsync(&last_excl, child + (nnz - 1), 4, hipMemcpyDeviceToHost, st));
+                const int64_t from = nnz >= 2 ? nnz - 2 : 0;
+                SP_HIP(hipMemcpyAsync(lastk, keys + from, (size_t)(nnz - from) * 8, hipMemcpyDeviceToHost, st));
+                SP_HIP(hipStreamSynchronize(st));
+                const bool last_mark = nnz == 1 || (lastk[0] / stride != lastk[1] / stride);
+                nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
+                child_excl = child;
+            }
+            if (enc->pw_store < 64 && nchild > (((int64_t)1 << (enc->pw_store - 1)) - 1)) return SP_ERR_WIDTH;
+            const size_t pbytes = pad16((size_t)(P + 1) * (enc->pw / 8));
+            const size_t cbytes = pad16((size_t)(nchild > 0 ? nchild : 1) * (enc->cw / 8));
+            t->pos[l] = mem.get(pbytes);
+            t->crd[l] = mem.get(cbytes);
+            t->npos[l] = P + 1;
+            t->ncrd[l] = nchild;
+            if (!t->pos[l] || !t->crd[l]) return SP_ERR_ALLOC;
+            SP_TRY(spmi_fill_zero(t->pos[l], pbytes, st));
+            if (nnz > 0) {
+                if (enc->pw == 32 && enc->cw == 32) SP_TRY((launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
+                else if (enc->pw == 32) SP_TRY((launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
+                else if (enc->cw == 32) SP_TRY((launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
+                else SP_TRY((launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
+            }
+            SP_TRY(spmi_exclusive_scan(t->pos[l], P + 1, enc->pw, tmp, st));
+            P = nchild;
+        }
+        if (enc->lt[l] == SP_COMPRESSED) dense_prefix = false;
+        if (nnz > 0 && !last_compressed) { pin = pout; which ^= 1; }
+    }
+
+    // 8- and 16-bit widths: the arrays handed out are narrowed copies of the 32-bit working arrays
+    for (int l = 0; l < rank; ++l) {
+        if (enc->lt[l] != SP_COMPRESSED) continue;
+        if (enc->pw_store < 32) {
+            t->pos_narrow[l] = mem.get(pad16((size_t)t->npos[l] * (enc->pw_store / 8)));
+            if (!t->pos_narrow[l]) return SP_ERR_ALLOC;
+            if (enc->pw_store == 8)
+                hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
+                                   (const int32_t *)t->pos[l], t->npos[l], (int8_t *)t->pos_narrow[l]);
+            else
+                hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
+                                   (const int32_t *)t->pos[l], t->npos[l], (int16_t *)t->pos_narrow[l]);
+        }
+        if (enc->cw_store < 32) {
+            t->crd_narrow[l] = mem.get(pad16((size_t)(t->ncrd[l] > 0 ? t->ncrd[l] : 1) * (enc->cw_store / 8)));
+            if (!t->crd_narrow[l]) return SP_ERR_ALLOC;
+            if (enc->cw_store == 8)
+                hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
+                                   (const int32_t *)t->crd[l], t->ncrd[l], (int8_t *)t->crd_narrow[l]);
+            else
+                hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
+                                   (const int32_t *)t->crd[l], t->ncrd[l], (int16_t *)t->crd_narrow[l]);
+        }
+        SP_HIP(hipGetLastError());
+    }
+
+    // values: zero padding only where a dense level sits below a compressed one
+    const size_t vsz = dt == SP_F64 ? 8 : 4;
+    const size_t vbytes = pad16((size_t)(P > 0 ? P : 1) * vsz);
+    t->values = mem.get(vbytes);
+    t->nvalues = P;
+    if (!t->values) return SP_ERR_ALLOC;
+    if (P != nnz) SP_TRY(spmi_fill_zero(t->values, vbytes, st));
+    if (nnz > 0) {
+        // where each sorted entry's value goes: its own rank (innermost level compressed), the key itself (every
+        // level dense), or the position carried down from the last compressed level
+        const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : dense_prefix ? (const uint64_t *)keys : pin;
+        if (dt == SP_F64)
+            hipLaunchKernelGGL(place_values_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                               (const unsigned long long *)payload, position, nnz, (unsigned long long *)t->values);
+        else
+            hipLaunchKernelGGL(place_values_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                               (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
+        SP_HIP(hipGetLastError());
+    }
+    // longest innermost segment (kernel choice) and the row blocks of the streaming kernels
+    if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
+        unsigned long long *mx = (unsigned long long *)(flags + 4);
+        const int64_t nseg = t->npos[rank - 1] - 1;
+        const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
+        if (enc->pw == 32)
+            hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
+        else
+            hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
+        SP_HIP(hipGetLastError());
+        unsigned long long hmx = 0;
+        SP_HIP(hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipStreamSynchronize(st));
+        t->max_segment = (int64_t)hmx;
+    }
+    SP_TRY(spmi_build_rowblocks(t, st));
+    SP_TRY(build_nonempty_rows(t, tmp, st));
+    SP_HIP(hipStreamSynchronize(st));
+    return SP_OK;
+}
+
+// A new tensor handle with shape, sizes by level and the key width worked out; SP_ERR_TOO_LARGE / SP_ERR_WIDTH as sp_pack documents.
+static sp_status new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
+                            bool entries_in_an_empty_dimension, sp_tensor **out, int *key_bits_out)
+{
+    const int rank = enc->rank;
+    sp_tensor *t = new sp_tensor();
+    memset(t, 0, sizeof(*t));
+    t->enc = *enc; t->dtype = dt; t->alloc = alloc; t->free_ = free_; t->ctx = ctx;
+    // the linearised key and every dense position count must stay below 2^63
+    unsigned __int128 prod = 1;
+    for (int l = 0; l < rank; ++l) {
+        t->shape[l] = shape[l];
+        t->size[l] = shape[enc->perm[l]];
+        prod *= (unsigned __int128)(t->size[l] > 0 ? t->size[l] : 1);
+        if (prod >= ((unsigned __int128)1 << 63)) { delete t; return SP_ERR_TOO_LARGE; }
+    }
+    if (entries_in_an_empty_dimension) { delete t; return SP_ERR_COORD_RANGE; }
+    for (int l = 0; l < rank; ++l)
+        if (enc->lt[l] == SP_COMPRESSED && enc->cw_store < 64 && t->size[l] - 1 > (((int64_t)1 << (enc->cw_store - 1)) - 1)) {
+            delete t;
+            return SP_ERR_WIDTH;
+        }
+    int key_bits = 0;
+    while (key_bits < 63 && ((unsigned __int128)1 << key_bits) < prod) ++key_bits;
+    *key_bits_out = key_bits;
+    *out = t;
+    return SP_OK;
+}
+
+static sp_status finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out)
+{
+    if (status == SP_ERR_HIP && g_last_hip_error == 0) g_last_hip_error = (int)hipGetLastError();
+    if (status != SP_OK) { release_tensor_arrays(t); delete t; return status; }
+    *out = t;
+    return SP_OK;
+}
+
 extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64_t nnz, const int64_t *const *coords,
                              const void *values, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx, void *stream,
                              sp_tensor **out)
@@ -652,51 +902,28 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
     if (dt != SP_F32 && dt != SP_F64) return SP_ERR_DTYPE;
     if (nnz < 0) return SP_ERR_SHAPE;
     const int rank = enc->rank;
+    bool zero_dim = false;
     for (int d = 0; d < rank; ++d) {
         if (shape[d] < 0) return SP_ERR_SHAPE;
+        if (shape[d] == 0) zero_dim = true;
         if (nnz > 0 && !coords[d]) return SP_ERR_NULL;
     }
     if (nnz >= ((int64_t)1 << 31)) return SP_ERR_TOO_LARGE;
     hipStream_t st = (hipStream_t)stream;
-
-    sp_tensor *t = new sp_tensor();
-    memset(t, 0, sizeof(*t));
-    t->enc = *enc; t->dtype = dt; t->alloc = alloc; t->free_ = free_; t->ctx = ctx; t->nnz = nnz;
-    // the linearised key and every dense position count must stay below 2^63
-    unsigned __int128 prod = 1;
-    bool zero_dim = false;
-    for (int l = 0; l < rank; ++l) {
-        t->shape[l] = shape[l];
-        t->size[l] = shape[enc->perm[l]];
-        if (t->size[l] == 0) zero_dim = true;
-        prod *= (unsigned __int128)(t->size[l] > 0 ? t->size[l] : 1);
-        if (prod >= ((unsigned __int128)1 << 63)) { delete t; return SP_ERR_TOO_LARGE; }
-    }
-    if (zero_dim && nnz > 0) { delete t; return SP_ERR_COORD_RANGE; }
-    for (int l = 0; l < rank; ++l)
-        if (enc->lt[l] == SP_COMPRESSED && enc->cw_store < 64 && t->size[l] - 1 > (((int64_t)1 << (enc->cw_store - 1)) - 1)) {
-            delete t;
-            return SP_ERR_WIDTH;
-        }
+    sp_tensor *t = nullptr;
     int key_bits = 0;
-    while (key_bits < 63 && ((unsigned __int128)1 << key_bits) < prod) ++key_bits;
-
+    SP_TRY(new_tensor(enc, shape, dt, alloc, free_, ctx, zero_dim && nnz > 0, &t, &key_bits));
     sp_mem mem{alloc, free_, ctx};
     sp_status status = SP_OK;
     {
         sp_scratch tmp(mem);
         const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
         uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
-        const int vsz0 = dt == SP_F64 ? 8 : 4;
-        void *payload = tmp.get(cnt * vsz0);      // the values, carried through the sort
-        uint64_t *parentA = (uint64_t *)tmp.get(cnt * 8);
-        uint64_t *parentB = (uint64_t *)tmp.get(cnt * 8);
-        uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
+        void *payload = tmp.get(cnt * (dt == SP_F64 ? 8 : 4));      // the values, carried through the sort
         int *flags = (int *)tmp.get(64);
-        auto fail = [&](sp_status s) { status = s; return s; };
         do {
-            if (!keys || !payload || !parentA || !parentB || !child || !flags) { fail(SP_ERR_ALLOC); break; }
-            if (spmi_fill_zero(flags, 64, st) != SP_OK) { fail(SP_ERR_HIP); break; }
+            if (!keys || !payload || !flags) { status = SP_ERR_ALLOC; break; }
+            if ((status = spmi_fill_zero(flags, 64, st)) != SP_OK) break;
             if (nnz > 0) {
                 level_args la;
                 memset(&la, 0, sizeof(la));
@@ -708,152 +935,31 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                 else
                     hipLaunchKernelGGL(make_keys_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz,
                                        (const uint32_t *)values, keys, (uint32_t *)payload, flags);
-                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-                if (fail(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st)) != SP_OK) break;
-                hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
-                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
-            int hflags[2] = {0, 0};
-            if (hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, st) != hipSuccess ||
-                hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
-            if (hflags[0]) { fail(SP_ERR_COORD_RANGE); break; }
-            if (hflags[1]) { fail(SP_ERR_DUPLICATE); break; }
-
-            // level sweep
-            const uint64_t *pin = nullptr;      // nullptr = the position at the level above is the key prefix (dense levels so far)
-            bool dense_prefix = true;
-            uint64_t *pbuf[2] = {parentA, parentB};
-            int which = 0;
-            int64_t P = 1;
-            for (int l = 0; l < rank && status == SP_OK; ++l) {
-                uint64_t stride = 1;
-                for (int k = l + 1; k < rank; ++k) stride *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
-                const uint64_t size = (uint64_t)(t->size[l] > 0 ? t->size[l] : 1);
-                uint64_t *pout = pbuf[which];
-                if (enc->lt[l] == SP_DENSE && dense_prefix) {
-                    P *= t->size[l];                  // nothing to compute: the position at this level is the key prefix
-                    continue;
-                }
-                if (enc->lt[l] == SP_DENSE) {
-                    if (nnz > 0) {
-                        hipLaunchKernelGGL(dense_level_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz,
-                                           stride, size, pin, pout);
-                        if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-                    }
-                    P *= t->size[l];
-                } else {
-                    int64_t nchild = nnz;
-                    const uint32_t *child_excl = nullptr;
-                    if (l != rank - 1 && nnz > 0) {
-                        hipLaunchKernelGGL(mark_children_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, stride, child);
-                        if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-                        if (fail(spmi_exclusive_scan(child, nnz, 32, tmp, st)) != SP_OK) break;
-                        // children = exclusive[nnz-1] + mark[nnz-1]; the last mark is recomputed from the two last keys
-                        uint32_t last_excl = 0;
-                        uint64_t lastk[2] = {0, 0};
-                        if (hipMemcpyAsync(&last_excl, child + (nnz - 1), 4, hipMemcpyDeviceToHost, st) != hipSuccess) { fail(SP_ERR_HIP); break; }
-                        const int64_t from = nnz >= 2 ? nnz - 2 : 0;
-                        if (hipMemcpyAsync(lastk, keys + from, (size_t)(nnz - from) * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
-                            hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
-                        const bool last_mark = nnz == 1 || (lastk[0] / stride != lastk[1] / stride);
-                        nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
-                        child_excl = child;
-                    }
-                    if (enc->pw_store < 64 && nchild > (((int64_t)1 << (enc->pw_store - 1)) - 1)) { fail(SP_ERR_WIDTH); break; }
-                    const size_t pbytes = pad16((size_t)(P + 1) * (enc->pw / 8));
-                    const size_t cbytes = pad16((size_t)(nchild > 0 ? nchild : 1) * (enc->cw / 8));
-                    t->pos[l] = mem.get(pbytes);
-                    t->crd[l] = mem.get(cbytes);
-                    t->npos[l] = P + 1;
-                    t->ncrd[l] = nchild;
-                    if (!t->pos[l] || !t->crd[l]) { fail(SP_ERR_ALLOC); break; }
-                    if (spmi_fill_zero(t->pos[l], pbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
-                    if (nnz > 0) {
-                        sp_status s;
-                        if (enc->pw == 32 && enc->cw == 32) s = launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
-                        else if (enc->pw == 32) s = launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
-                        else if (enc->cw == 32) s = launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
-                        else s = launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, l == rank - 1 ? nullptr : pout, t->pos[l], t->crd[l], st);
-                        if (fail(s) != SP_OK) break;
-                    }
-                    if (fail(spmi_exclusive_scan(t->pos[l], P + 1, enc->pw, tmp, st)) != SP_OK) break;
-                    P = nchild;
-                }
-                if (enc->lt[l] == SP_COMPRESSED) dense_prefix = false;
-                if (nnz > 0 && !(enc->lt[l] == SP_COMPRESSED && l == rank - 1)) { pin = pout; which ^= 1; }
-            }
-            if (status != SP_OK) break;
-
-            // 8- and 16-bit widths: the arrays handed out are narrowed copies of the 32-bit working arrays
-            for (int l = 0; l < rank && status == SP_OK; ++l) {
-                if (enc->lt[l] != SP_COMPRESSED) continue;
-                if (enc->pw_store < 32) {
-                    t->pos_narrow[l] = mem.get(pad16((size_t)t->npos[l] * (enc->pw_store / 8)));
-                    if (!t->pos_narrow[l]) { fail(SP_ERR_ALLOC); break; }
-                    if (enc->pw_store == 8)
-                        hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
-                                           (const int32_t *)t->pos[l], t->npos[l], (int8_t *)t->pos_narrow[l]);
-                    else
-                        hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->npos[l])), dim3(kThreads), 0, st,
-                                           (const int32_t *)t->pos[l], t->npos[l], (int16_t *)t->pos_narrow[l]);
-                }
-                if (enc->cw_store < 32) {
-                    t->crd_narrow[l] = mem.get(pad16((size_t)(t->ncrd[l] > 0 ? t->ncrd[l] : 1) * (enc->cw_store / 8)));
-                    if (!t->crd_narrow[l]) { fail(SP_ERR_ALLOC); break; }
-                    if (enc->cw_store == 8)
-                        hipLaunchKernelGGL((narrow_kernel<int32_t, int8_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
-                                           (const int32_t *)t->crd[l], t->ncrd[l], (int8_t *)t->crd_narrow[l]);
-                    else
-                        hipLaunchKernelGGL((narrow_kernel<int32_t, int16_t>), dim3(blocks_for(t->ncrd[l])), dim3(kThreads), 0, st,
-                                           (const int32_t *)t->crd[l], t->ncrd[l], (int16_t *)t->crd_narrow[l]);
-                }
-                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-            }
-            if (status != SP_OK) break;
-
-            // values: zero padding only where a dense level sits below a compressed one
-            const size_t vsz = dt == SP_F64 ? 8 : 4;
-            const size_t vbytes = pad16((size_t)(P > 0 ? P : 1) * vsz);
-            t->values = mem.get(vbytes);
-            t->nvalues = P;
-            if (!t->values) { fail(SP_ERR_ALLOC); break; }
-            if (P != nnz && spmi_fill_zero(t->values, vbytes, st) != SP_OK) { fail(SP_ERR_HIP); break; }
-            if (nnz > 0) {
-                // where each sorted entry's value goes: its own rank (innermost level compressed), the key itself (every
-                // level dense), or the position carried down from the last compressed level
-                const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : dense_prefix ? (const uint64_t *)keys : pin;
-                if (dt == SP_F64)
-                    hipLaunchKernelGGL(place_values_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
-                                       (const unsigned long long *)payload, position, nnz, (unsigned long long *)t->values);
-                else
-                    hipLaunchKernelGGL(place_values_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
-                                       (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
-                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-            }
-            // longest innermost segment (kernel choice) and the row blocks of the streaming kernels
-            if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
-                unsigned long long *mx = (unsigned long long *)(flags + 4);
-                const int64_t nseg = t->npos[rank - 1] - 1;
-                const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
-                if (enc->pw == 32)
-                    hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
-                else
-                    hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
-                if (hipGetLastError() != hipSuccess) { fail(SP_ERR_HIP); break; }
-                unsigned long long hmx = 0;
-                if (hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
-                t->max_segment = (int64_t)hmx;
-            }
-            if (fail(spmi_build_rowblocks(t, st)) != SP_OK) break;
-            if (fail(build_nonempty_rows(t, tmp, st)) != SP_OK) break;
-            if (hipStreamSynchronize(st) != hipSuccess) { fail(SP_ERR_HIP); break; }
+            status = pack_core(t, nnz, keys, payload, key_bits, false, flags, tmp, mem, st);
         } while (0);
-        if (status == SP_ERR_HIP && g_last_hip_error == 0) g_last_hip_error = (int)hipGetLastError();
         if (status != SP_OK) (void)hipStreamSynchronize(st);   // temporaries may still be in use by queued kernels
     }
-    if (status != SP_OK) { release_tensor_arrays(t); delete t; return status; }
-    *out = t;
-    return SP_OK;
+    return finish_pack(t, status, st, out);
+}
+
+// The storage of a tensor whose entries are given as linearised keys (level order, mixed radix over the level sizes)
+// with the value bits as payload; entries with equal keys are added up in the order they are given.
+sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
+                         int64_t n, uint64_t *keys, void *payload, sp_scratch &tmp, hipStream_t st, sp_tensor **out)
+{
+    *out = nullptr;
+    if (n >= ((int64_t)1 << 31)) return SP_ERR_TOO_LARGE;
+    sp_tensor *t = nullptr;
+    int key_bits = 0;
+    SP_TRY(new_tensor(enc, shape, dt, alloc, free_, ctx, false, &t, &key_bits));
+    sp_mem mem{alloc, free_, ctx};
+    int *flags = (int *)tmp.get(64);
+    sp_status status = flags ? spmi_fill_zero(flags, 64, st) : SP_ERR_ALLOC;
+    if (status == SP_OK) status = pack_core(t, n, keys, payload, key_bits, true, flags, tmp, mem, st);
+    if (status != SP_OK) (void)hipStreamSynchronize(st);
+    return finish_pack(t, status, st, out);
 }
 
 extern "C" sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream)

@@ -133,6 +133,10 @@ sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, 
 // Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits, payload of 4 or 8 bytes; results end in keys/vals.
 sp_status spmi_radix_sort_pairs(uint64_t *keys, void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
+// The storage of a tensor whose n entries are given as linearised keys (level order, mixed radix over the level sizes)
+// with the value bits as payload, both temporaries of `tmp`; entries with equal keys are added up in the order given.
+sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
+                         int64_t n, uint64_t *keys, void *payload, sp_scratch &tmp, hipStream_t st, sp_tensor **out);
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
 sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
 #ifndef SPMI_ST
@@ -144,6 +148,10 @@ sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_byt
 constexpr int kSpmiStreamThreads = SPMI_ST;                  // threads per block of the stream kernel
 constexpr int kSpmiStreamPer = SPMI_PER;                     // stored entries per thread (even)
 constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // stored entries per block
+
+// ---- api.hip -----------------------------------------------------------------------------
+// Builds and keeps the row-major copy of a column-major tensor (A->transposed); no-op when it exists.
+sp_status spmi_build_transposed(sp_tensor *A, hipStream_t st);
 
 // ---- matmul.hip --------------------------------------------------------------------------
 sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
