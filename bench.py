@@ -205,12 +205,85 @@ def bench_mttkrp(args, torch, sp, dev):
     print(json.dumps(out))
 
 
+def bench_spmspm(args, torch, sp, dev):
+    """C = A.B with sparse A, B and C, all CSR (Sections 4.4 and 6.2): n x n uniform random operands of density 0.01, the
+    sizes of the paper's table; the headline line is the largest one.  One step = one sp_spgemm (it allocates and
+    builds C, and synchronises)."""
+    from gen import workloads as W
+    sizes = [256, 512] if args.small else [1024, 2048, 4096, 8192]
+    steps = args.steps or 10
+    warmup = args.warmup or 2
+    enc = sp.sp_encode((0, 1), (0, 1), args.width, args.width)
+    table = []
+    t0 = time.time()
+    for n in sizes:
+        nnz = int(round(0.01 * n * n))
+        a = W.uniform_random(n, n, nnz, seed=W.BASE_SEED + 500 + n)
+        b = W.uniform_random(n, n, nnz, seed=W.BASE_SEED + 600 + n)
+        A = sp.sp_pack(enc, a.shape, [torch.from_numpy(a.rows).to(dev), torch.from_numpy(a.cols).to(dev)], torch.from_numpy(a.vals).to(dev))
+        B = sp.sp_pack(enc, b.shape, [torch.from_numpy(b.rows).to(dev), torch.from_numpy(b.cols).to(dev)], torch.from_numpy(b.vals).to(dev))
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, args.spgemm_kernel)
+        for _ in range(warmup):
+            sp.sp_spgemm(A, B, enc).free()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            sp.sp_spgemm(A, B, enc).free()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        C = sp.sp_spgemm(A, B, enc)
+        ia, ib, ic = sp.sp_tensor_info(A), sp.sp_tensor_info(B), sp.sp_tensor_info(C)
+        pairs = int((torch.bincount(sp.sp_crd(A, 1).long(), minlength=n) * (sp.sp_pos(B, 1)[1:] - sp.sp_pos(B, 1)[:-1]).long()).sum())
+        table.append({"n": n, "ms": ms, "density_c": ic.nvalues / float(n * n), "pairs": pairs, "entries_c": int(ic.nvalues),
+                      "bytes": int(ia.storageBytes + ib.storageBytes + ic.storageBytes)})
+        last = (a, b, C, n)
+    gen_s = time.time() - t0
+    a, b, C, n = last
+    top = table[-1]
+    cpu, parity = None, None
+    if not args.no_cpu:
+        import oracle
+        t0 = time.time()
+        ci, cj, cv, mag = oracle.spgemm_coo(a.shape, a.rows, a.cols, a.vals, b.shape, b.rows, b.cols, b.vals)
+        cpu_s = time.time() - t0
+        P = oracle.pack((0, 1), (0, 1), (n, n), [ci, cj], cv, args.width, args.width)
+        M = oracle.pack((0, 1), (0, 1), (n, n), [ci, cj], mag, args.width, args.width)
+        parity = bool(np.array_equal(sp.sp_pos(C, 1).cpu().numpy(), P.pos[1]) and np.array_equal(sp.sp_crd(C, 1).cpu().numpy(), P.crd[1])
+                      and np.all(np.abs(sp.sp_values(C).cpu().numpy() - P.values) <= 1e-12 * M.values))
+        cpu = {"value": top["bytes"] / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "the whole n = %d product (%d pairs), one run, %.3f s" % (n, top["pairs"], cpu_s), "ms": cpu_s * 1e3}
+    paper = {1024: 3.7, 2048: 27.0, 4096: 224.4, 8192: 1775.1}
+    for r in table:
+        r["paper_ms"] = paper.get(r["n"])
+    achieved = top["bytes"] / (top["ms"] * 1e-3) / 1e9
+    out = {
+        "metric": "effective HBM GB/s (algorithmic bytes / time per product)",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": top["ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "SpMSpM C=A.B, all CSR f64 (Sections 4.4, 6.2): n x n uniform random A and B of density 0.01, n = %d, "
+                               "%d pairs -> %d stored entries of C, pos/crd %d-bit" % (n, top["pairs"], top["entries_c"], args.width),
+                   "kernel": "spgemm_expand_kernel + radix sort + sum_runs_kernel + level build" if args.spgemm_kernel == 1 else
+                             "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_kernel", "small": bool(args.small)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "whole sp_spgemm call (allocation and host synchronisations included)",
+                     "kernel_us": top["ms"] * 1e3, "algorithmic_bytes": top["bytes"]},
+        "cpu_baseline": cpu,
+        "table": table,
+        "parity_ok": parity,
+        "gen_s": gen_s,
+        "paper_note": "paper_ms: the paper's table on one Xeon W2135 core, for context only",
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm", "mttkrp"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm", "mttkrp", "spmspm"])
     ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense", "dss", "dss-alt", "sss", "sss-alt"],
                     help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table); "
                          "mttkrp: dss (default) / dss-alt as in the paper's table, sss / sss-alt with a compressed outer level")
@@ -219,6 +292,7 @@ def main():
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
     ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
     ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads with a wave per row, 3 16-byte loads cut by entries")
+    ap.add_argument("--spgemm-kernel", type=int, default=0, help="SpMSpM: 0 auto, 1 pairs through the storage builder, 2 LDS workspace per row")
     ap.add_argument("--accumulate", action="store_true", help="C += A.B instead of C = A.B")
     ap.add_argument("--small", action="store_true", help="scaled-down matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
@@ -236,6 +310,8 @@ def main():
     name = args.workload
     if name == "mttkrp":
         return bench_mttkrp(args, torch, sp, dev)
+    if name == "spmspm":
+        return bench_spmspm(args, torch, sp, dev)
     t0 = time.time()
     w = make_workload(name, args.small)
     gen_s = time.time() - t0

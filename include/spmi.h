@@ -171,8 +171,12 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *                        3 = the same cut by stored entries instead of rows (2 and 3 need N a multiple
  *                        of 16 / element size with 1, 2, 4, ... 64 such vectors per row, and B, C rows 16-byte aligned)
  *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
+ *   SP_TUNE_SPGEMM_KERNEL (set on the left operand of sp_spgemm): 0 = automatic, 1 = pairs expanded, sorted and added
+ *                        up by the storage builder (any sizes and encodings), 2 = a row of C at a time in an LDS
+ *                        workspace (CSR / DCSR operands and a CSR result with one pos / crd width, rows of C that
+ *                        fit the LDS; SP_ERR_UNSUPPORTED otherwise)
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
-enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4 };
+enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4, SP_TUNE_SPGEMM_KERNEL = 5 };
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);
 
 /* Kernel timing for measurements.  After sp_tensor_tune(t, SP_TUNE_PROFILE, 1) every sp_matmul on

@@ -8,7 +8,7 @@ from . import build as _build
 
 SP_DENSE, SP_COMPRESSED = 0, 1
 SP_F32, SP_F64 = 0, 1
-SP_TUNE_SPMV_KERNEL, SP_TUNE_CSC_MODE, SP_TUNE_SPMM_KERNEL, SP_TUNE_PROFILE = 1, 2, 3, 4
+SP_TUNE_SPMV_KERNEL, SP_TUNE_CSC_MODE, SP_TUNE_SPMM_KERNEL, SP_TUNE_PROFILE, SP_TUNE_SPGEMM_KERNEL = 1, 2, 3, 4, 5
 SP_MAX_RANK = 8
 
 STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_ERR_ORDERING", "SP_ERR_WIDTH",

@@ -641,6 +641,33 @@ static sp_status launch_emit(const uint64_t *keys, int64_t nnz, uint64_t stride,
     return SP_OK;
 }
 
+// The tables a finished storage carries for the product kernels: longest innermost segment (kernel choice), the row
+// blocks of the streaming kernels, the list of non-empty rows of a mostly empty CSR.  flags: 64 device bytes, the
+// second half zero.  Synchronises.
+sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st)
+{
+    const sp_encoding *enc = &t->enc;
+    const int rank = enc->rank;
+    if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
+        unsigned long long *mx = (unsigned long long *)(flags + 4);
+        const int64_t nseg = t->npos[rank - 1] - 1;
+        const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
+        if (enc->pw == 32)
+            hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
+        else
+            hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
+        SP_HIP(hipGetLastError());
+        unsigned long long hmx = 0;
+        SP_HIP(hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipStreamSynchronize(st));
+        t->max_segment = (int64_t)hmx;
+    }
+    SP_TRY(spmi_build_rowblocks(t, st));
+    SP_TRY(build_nonempty_rows(t, tmp, st));
+    SP_HIP(hipStreamSynchronize(st));
+    return SP_OK;
+}
+
 // Everything after the keys exist: sort, duplicates (an error, or summed in sorted order when `sum_duplicates`), the
 // level sweep, narrow copies, values, and the tables the product kernels want.  keys / payload: nnz entries in
 // temporaries of `tmp` (the payload is the value's bits); flags: 64 zeroed bytes, flags[0] != 0 afterwards on the
@@ -833,29 +860,11 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
                                (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
         SP_HIP(hipGetLastError());
     }
-    // longest innermost segment (kernel choice) and the row blocks of the streaming kernels
-    if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
-        unsigned long long *mx = (unsigned long long *)(flags + 4);
-        const int64_t nseg = t->npos[rank - 1] - 1;
-        const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
-        if (enc->pw == 32)
-            hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
-        else
-            hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
-        SP_HIP(hipGetLastError());
-        unsigned long long hmx = 0;
-        SP_HIP(hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st));
-        SP_HIP(hipStreamSynchronize(st));
-        t->max_segment = (int64_t)hmx;
-    }
-    SP_TRY(spmi_build_rowblocks(t, st));
-    SP_TRY(build_nonempty_rows(t, tmp, st));
-    SP_HIP(hipStreamSynchronize(st));
-    return SP_OK;
+    return spmi_finish_tensor(t, flags, tmp, st);
 }
 
 // A new tensor handle with shape, sizes by level and the key width worked out; SP_ERR_TOO_LARGE / SP_ERR_WIDTH as sp_pack documents.
-static sp_status new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
+sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
                             bool entries_in_an_empty_dimension, sp_tensor **out, int *key_bits_out)
 {
     const int rank = enc->rank;
@@ -883,7 +892,7 @@ static sp_status new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dty
     return SP_OK;
 }
 
-static sp_status finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out)
+sp_status spmi_finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out)
 {
     if (status == SP_ERR_HIP && g_last_hip_error == 0) g_last_hip_error = (int)hipGetLastError();
     if (status != SP_OK) { release_tensor_arrays(t); delete t; return status; }
@@ -912,7 +921,7 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
     hipStream_t st = (hipStream_t)stream;
     sp_tensor *t = nullptr;
     int key_bits = 0;
-    SP_TRY(new_tensor(enc, shape, dt, alloc, free_, ctx, zero_dim && nnz > 0, &t, &key_bits));
+    SP_TRY(spmi_new_tensor(enc, shape, dt, alloc, free_, ctx, zero_dim && nnz > 0, &t, &key_bits));
     sp_mem mem{alloc, free_, ctx};
     sp_status status = SP_OK;
     {
@@ -941,7 +950,7 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
         } while (0);
         if (status != SP_OK) (void)hipStreamSynchronize(st);   // temporaries may still be in use by queued kernels
     }
-    return finish_pack(t, status, st, out);
+    return spmi_finish_pack(t, status, st, out);
 }
 
 // The storage of a tensor whose entries are given as linearised keys (level order, mixed radix over the level sizes)
@@ -953,13 +962,13 @@ sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype 
     if (n >= ((int64_t)1 << 31)) return SP_ERR_TOO_LARGE;
     sp_tensor *t = nullptr;
     int key_bits = 0;
-    SP_TRY(new_tensor(enc, shape, dt, alloc, free_, ctx, false, &t, &key_bits));
+    SP_TRY(spmi_new_tensor(enc, shape, dt, alloc, free_, ctx, false, &t, &key_bits));
     sp_mem mem{alloc, free_, ctx};
     int *flags = (int *)tmp.get(64);
     sp_status status = flags ? spmi_fill_zero(flags, 64, st) : SP_ERR_ALLOC;
     if (status == SP_OK) status = pack_core(t, n, keys, payload, key_bits, true, flags, tmp, mem, st);
     if (status != SP_OK) (void)hipStreamSynchronize(st);
-    return finish_pack(t, status, st, out);
+    return spmi_finish_pack(t, status, st, out);
 }
 
 extern "C" sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream)

@@ -8,6 +8,13 @@
 // are written in the order of A's stored entries and, inside one entry, of B's row, so the sum of an element of C
 // runs over k in A's storage order: for a row-major A exactly the order of the paper's loop, and the same bits on
 // every call.  Cost: 16 bytes per pair, written once and sorted; no per-row workspace, no atomics, no limit on n.
+//
+// When a full row of C fits the LDS (72 KB: 9216 columns in f64) and the operands are CSR / DCSR with a CSR result,
+// the paper's workspace itself is used instead, one wave per row of A with the workspace in LDS: a first kernel
+// marks the columns a row reaches in an n-bit map and counts them, the counts are scanned into C's pos, and a second
+// kernel adds the products into a dense row of n values, then walks the bit map in column order and writes crd and
+// values: the paper's expand / compress, with the sort of the added indices replaced by the ordered walk.  One wave
+// owns a row and takes the pairs in a fixed order, so there are no atomics on values and the bits repeat.
 #include "spmi_internal.h"
 
 namespace {
@@ -107,6 +114,203 @@ sp_status spgemm_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *e
     return spmi_pack_keys(encC, shapeC, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, total, keys, payload, tmp, st, out);
 }
 
+// ---- a row of C at a time in an LDS workspace ---------------------------------------------------------------------
+constexpr int64_t kWorkspaceBytes = 72 * 1024;          // dense row of C + its bit map; two such waves fit a CU's LDS
+
+// block = one wave = one stored row r of A.  count[i] = number of distinct columns the row reaches.
+template <typename PT, typename CT>
+__global__ __launch_bounds__(64) void spgemm_ws_count_kernel(const PT *__restrict__ apos, const CT *__restrict__ acrd,
+                                                             const CT *__restrict__ arowid, const PT *__restrict__ bpos,
+                                                             const CT *__restrict__ bcrd, int64_t n, PT *__restrict__ count)
+{
+    extern __shared__ uint32_t ws_bits[];
+    const int lane = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
+    if (a1 == a0) return;
+    const int64_t words = (n + 31) >> 5;
+    for (int64_t w = lane; w < words; w += 64) ws_bits[w] = 0u;
+    __syncthreads();
+    for (int64_t g = a0; g < a1; g += 64) {
+        const int64_t e = g + lane;
+        int64_t b0 = 0, b1 = 0;
+        if (e < a1) {
+            const int64_t k = (int64_t)acrd[e];
+            b0 = (int64_t)bpos[k];
+            b1 = (int64_t)bpos[k + 1];
+        }
+        const int cnt = (int)(a1 - g < 64 ? a1 - g : 64);
+        for (int x = 0; x < cnt; ++x) {                            // wave-uniform
+            const int64_t s0 = __shfl(b0, x, 64), s1 = __shfl(b1, x, 64);
+            for (int64_t t = s0 + lane; t < s1; t += 64) {
+                const uint32_t j = (uint32_t)bcrd[t];
+                atomicOr(&ws_bits[j >> 5], 1u << (j & 31));
+            }
+        }
+    }
+    __syncthreads();
+    int c = 0;
+    for (int64_t w = lane; w < words; w += 64) c += __popc(ws_bits[w]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    if (lane == 0) count[arowid ? (int64_t)arowid[r] : r] = (PT)c;
+}
+
+// block = one wave = one stored row r of A; LDS: n values, then the n-bit map.  U rows of B are requested together and
+// then added in turn: the order of the additions to one element is fixed by the structure, not by timing.
+template <typename PT, typename CT, typename VT, int U>
+__global__ __launch_bounds__(64) void spgemm_ws_numeric_kernel(const PT *__restrict__ apos, const CT *__restrict__ acrd,
+                                                               const VT *__restrict__ aval, const CT *__restrict__ arowid,
+                                                               const PT *__restrict__ bpos, const CT *__restrict__ bcrd,
+                                                               const VT *__restrict__ bval, int64_t n, const PT *__restrict__ cpos,
+                                                               CT *__restrict__ ccrd, VT *__restrict__ cval)
+{
+    extern __shared__ unsigned char ws_raw[];
+    VT *acc = (VT *)ws_raw;
+    uint32_t *bits = (uint32_t *)(ws_raw + (size_t)n * sizeof(VT));
+    const int lane = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
+    if (a1 == a0) return;
+    const int64_t words = (n + 31) >> 5;
+    for (int64_t j = lane; j < n; j += 64) acc[j] = (VT)0;
+    for (int64_t w = lane; w < words; w += 64) bits[w] = 0u;
+    __syncthreads();
+    for (int64_t g = a0; g < a1; g += 64) {
+        const int64_t e = g + lane;
+        int64_t b0 = 0, b1 = 0;
+        VT a = (VT)0;
+        if (e < a1) {
+            const int64_t k = (int64_t)acrd[e];
+            a = aval[e];
+            b0 = (int64_t)bpos[k];
+            b1 = (int64_t)bpos[k + 1];
+        }
+        const int cnt = (int)(a1 - g < 64 ? a1 - g : 64);
+        for (int x0 = 0; x0 < cnt; x0 += U) {                      // wave-uniform
+            int64_t s0[U], s1[U];
+            VT av[U];
+            int64_t longest = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int x = x0 + u < cnt ? x0 + u : x0;           // past the end: an empty range
+                s0[u] = __shfl(b0, x, 64);
+                s1[u] = x0 + u < cnt ? __shfl(b1, x, 64) : s0[u];
+                av[u] = __shfl(a, x, 64);
+                longest = s1[u] - s0[u] > longest ? s1[u] - s0[u] : longest;
+            }
+            for (int64_t c = 0; c < longest; c += 64) {
+                int64_t j[U];
+                VT bv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t t = s0[u] + c + lane;
+                    const bool in = t < s1[u];
+                    j[u] = in ? (int64_t)bcrd[t] : -1;
+                    bv[u] = in ? bval[t] : (VT)0;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (j[u] >= 0) {
+                        atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
+                        acc[j[u]] += av[u] * bv[u];                  // the lanes of one row of B hold distinct columns
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+    }
+    __syncthreads();
+    int64_t base = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r];
+    for (int64_t j0 = 0; j0 < n; j0 += 64) {                       // the compress step: set bits in column order
+        const int64_t j = j0 + lane;
+        const bool set = j < n && ((bits[j >> 5] >> (j & 31)) & 1u);
+        const unsigned long long mask = __ballot(set);
+        if (set) {
+            const int64_t o = base + __popcll(mask & ((1ull << lane) - 1ull));
+            ccrd[o] = (CT)j;
+            cval[o] = acc[j];
+        }
+        base += __popcll(mask);
+    }
+}
+
+template <typename PT, typename CT, typename VT>
+sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *encC, hipStream_t st, sp_tensor **out)
+{
+    const int64_t m = A->shape[0], n = Br->shape[1];
+    const int64_t shapeC[2] = {m, n};
+    sp_tensor *t = nullptr;
+    int key_bits = 0;
+    SP_TRY(spmi_new_tensor(encC, shapeC, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, false, &t, &key_bits));
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    sp_status status = SP_OK;
+    {
+        sp_scratch tmp(mem);
+        do {
+            int *flags = (int *)tmp.get(64);
+            if (!flags) { status = SP_ERR_ALLOC; break; }
+            if ((status = spmi_fill_zero(flags, 64, st)) != SP_OK) break;
+            const size_t pbytes = ((size_t)(m + 1) * sizeof(PT) + 15) & ~(size_t)15;
+            t->pos[1] = mem.get(pbytes);
+            t->npos[1] = m + 1;
+            if (!t->pos[1]) { status = SP_ERR_ALLOC; break; }
+            if ((status = spmi_fill_zero(t->pos[1], pbytes, st)) != SP_OK) break;
+            const bool a_outer_compressed = A->enc.lt[0] == SP_COMPRESSED;
+            const int64_t arows = a_outer_compressed ? A->ncrd[0] : m;
+            const CT *arowid = a_outer_compressed ? (const CT *)A->crd[0] : nullptr;
+            const size_t bits_bytes = (size_t)((n + 31) / 32) * 4;
+            const size_t ws_bytes = (size_t)n * sizeof(VT) + bits_bytes;
+            const bool work = arows > 0 && A->nvalues > 0 && Br->nvalues > 0 && n > 0;
+            if (work) {
+                hipLaunchKernelGGL((spgemm_ws_count_kernel<PT, CT>), dim3((unsigned)arows), dim3(64), bits_bytes, st, (const PT *)A->pos[1],
+                                   (const CT *)A->crd[1], arowid, (const PT *)Br->pos[1], (const CT *)Br->crd[1], n, (PT *)t->pos[1]);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            }
+            if ((status = spmi_exclusive_scan(t->pos[1], m + 1, (int)sizeof(PT) * 8, tmp, st)) != SP_OK) break;
+            PT total = 0;
+            if (hipMemcpyAsync(&total, (const PT *)t->pos[1] + m, sizeof(PT), hipMemcpyDeviceToHost, st) != hipSuccess ||
+                hipStreamSynchronize(st) != hipSuccess) { status = SP_ERR_HIP; break; }
+            const int64_t nnzc = (int64_t)total;
+            if (nnzc < 0 || nnzc >= ((int64_t)1 << 31)) { status = SP_ERR_TOO_LARGE; break; }     // a 32-bit pos that wrapped shows as negative
+            t->crd[1] = mem.get((((size_t)(nnzc > 0 ? nnzc : 1) * sizeof(CT)) + 15) & ~(size_t)15);
+            t->values = mem.get((((size_t)(nnzc > 0 ? nnzc : 1) * sizeof(VT)) + 15) & ~(size_t)15);
+            t->ncrd[1] = nnzc;
+            t->nvalues = nnzc;
+            t->nnz = nnzc;
+            if (!t->crd[1] || !t->values) { status = SP_ERR_ALLOC; break; }
+            if (work && nnzc > 0) {
+                auto kernel = spgemm_ws_numeric_kernel<PT, CT, VT, 4>;
+                if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
+                    status = SP_ERR_HIP;
+                    break;
+                }
+                hipLaunchKernelGGL(kernel, dim3((unsigned)arows), dim3(64), ws_bytes, st, (const PT *)A->pos[1], (const CT *)A->crd[1],
+                                   (const VT *)A->values, arowid, (const PT *)Br->pos[1], (const CT *)Br->crd[1], (const VT *)Br->values, n,
+                                   (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            }
+            status = spmi_finish_tensor(t, flags, tmp, st);
+        } while (0);
+        if (status != SP_OK) (void)hipStreamSynchronize(st);
+    }
+    return spmi_finish_pack(t, status, st, out);
+}
+
+// can the workspace kernels take this product?
+static bool workspace_fits(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *encC)
+{
+    const int64_t n = Br->shape[1];
+    const size_t vsz = A->dtype == SP_F64 ? 8 : 4;
+    return encC->lt[0] == SP_DENSE && encC->lt[1] == SP_COMPRESSED && encC->perm[0] == 0 &&        // C in CSR
+           A->enc.perm[0] == 0 && A->enc.lt[1] == SP_COMPRESSED &&                                 // A in CSR or DCSR
+           Br->enc.lt[0] == SP_DENSE &&                                                            // B's rows indexed directly
+           A->enc.pw == Br->enc.pw && A->enc.cw == Br->enc.cw && encC->pw == A->enc.pw && encC->cw == A->enc.cw &&
+           encC->pw_store >= 32 && encC->cw_store >= 32 &&
+           (size_t)n * vsz + (size_t)((n + 31) / 32) * 4 <= (size_t)kWorkspaceBytes &&
+           (unsigned __int128)A->shape[0] * (unsigned __int128)n < ((unsigned __int128)1 << 31);        // so that no 32-bit pos can wrap
+}
+
 }  // namespace
 
 extern "C" sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C)
@@ -125,6 +329,17 @@ extern "C" sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_
         Br = B->transposed;
     }
     const int pw = Br->enc.pw, cw = Br->enc.cw;
+    const bool fits = workspace_fits(A, Br, encC);
+    if (A->tune_spgemm == 2 && !fits) return SP_ERR_UNSUPPORTED;
+    if (fits && A->tune_spgemm != 1) {
+#define SPMI_WS(PT, CT)                                                                                        \
+    return A->dtype == SP_F64 ? spgemm_workspace_t<PT, CT, double>(A, Br, encC, st, C) : spgemm_workspace_t<PT, CT, float>(A, Br, encC, st, C)
+        if (pw == 32 && cw == 32) SPMI_WS(int32_t, int32_t);
+        if (pw == 32) SPMI_WS(int32_t, int64_t);
+        if (cw == 32) SPMI_WS(int64_t, int32_t);
+        SPMI_WS(int64_t, int64_t);
+#undef SPMI_WS
+    }
 #define SPMI_GO(PT, CT)                                                                                        \
     return A->dtype == SP_F64 ? spgemm_t<PT, CT, double>(A, Br, encC, st, C) : spgemm_t<PT, CT, float>(A, Br, encC, st, C)
     if (pw == 32 && cw == 32) SPMI_GO(int32_t, int32_t);

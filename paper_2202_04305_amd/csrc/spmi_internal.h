@@ -67,7 +67,7 @@ struct sp_tensor {
     void *mttkrp_windows;            // DEVICE int32[2 * windows]: fibre and slice holding the first entry of each window (rank 3)
     void *mttkrp_carry;              // DEVICE scratch of the MTTKRP (J values per window), grown on demand
     size_t mttkrp_carry_bytes;
-    int tune_spmv, tune_csc, tune_spmm;
+    int tune_spmv, tune_csc, tune_spmm, tune_spgemm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
 };
@@ -148,6 +148,15 @@ sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_byt
 constexpr int kSpmiStreamThreads = SPMI_ST;                  // threads per block of the stream kernel
 constexpr int kSpmiStreamPer = SPMI_PER;                     // stored entries per thread (even)
 constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // stored entries per block
+
+// A new tensor handle with shape, sizes by level and the key width worked out (SP_ERR_TOO_LARGE, SP_ERR_WIDTH as sp_pack
+// documents; `entries_in_an_empty_dimension` turns into SP_ERR_COORD_RANGE at its place in that order).
+sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
+                          bool entries_in_an_empty_dimension, sp_tensor **out, int *key_bits_out);
+// The derived tables of a finished storage (see pack.hip); flags: 64 zeroed device bytes.
+sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st);
+// Hands the tensor out on SP_OK, releases everything it holds otherwise.
+sp_status spmi_finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out);
 
 // ---- api.hip -----------------------------------------------------------------------------
 // Builds and keeps the row-major copy of a column-major tensor (A->transposed); no-op when it exists.

@@ -100,6 +100,54 @@ def test_spgemm_exact_integers_kept_zeros_and_chained_product():
     assert np.array_equal(y.cpu().numpy(), yref.ravel())
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("fa", ["csr", "dcsr"])
+def test_spgemm_both_kernels(dtype, fa):
+    """Kernel 1 (pairs through the storage builder) and kernel 2 (a row of C at a time in an LDS workspace) against the
+    checker and each other's pattern; widths 32 and 64; rows of A from empty to hundreds of entries, rows of B longer
+    than a wave."""
+    a = W.cfg2_powerlaw_csr(2500, 1800, mean=8.0, cap=700)
+    b = W.cfg2_powerlaw_csr(1800, 9000, mean=40.0, cap=3000, seed=W.BASE_SEED + 34)      # 9000 columns: near the LDS limit in f64
+    va, vb = a.vals.astype(dtype), b.vals.astype(dtype)
+    ref = oracle.spgemm_coo(a.shape, a.rows, a.cols, va, b.shape, b.rows, b.cols, vb)
+    for pw, cw in [(32, 32), (64, 64)]:
+        A = gpu_pack(*ENC[fa], a.shape, [a.rows, a.cols], va, pw, cw)
+        B = gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], vb, pw, cw)
+        enc = sp.sp_encode(*ENC["csr"], pw, cw)
+        for kernel in (1, 2, 0):
+            say("case spgemm kernels", dtype.__name__, fa, pw, "kernel", kernel, len(ref[0]))
+            sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, kernel)
+            C = sp.sp_spgemm(A, B, enc)
+            check(C, "csr", (2500, 9000), ref, dtype, pw=pw, cw=cw)
+            C2 = sp.sp_spgemm(A, B, enc)
+            assert torch.equal(sp.sp_values(C), sp.sp_values(C2)), "not reproducible"
+
+
+def test_spgemm_workspace_kernel_limits_and_exact_integers():
+    a, b = pair(300, 200, 9100, 2500, 30000)
+    A = gpu_pack(*ENC["csr"], a.shape, [a.rows, a.cols], a.vals)
+    B = gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], b.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, 2)
+    with pytest.raises(sp.SpError) as err:           # a row of 9100 f64 does not fit the workspace
+        sp.sp_spgemm(A, B, sp.sp_encode(*ENC["csr"], 32, 32))
+    assert err.value.code == 10
+    with pytest.raises(sp.SpError) as err:           # nor does the workspace kernel write a column-major result
+        sp.sp_spgemm(A, gpu_pack(*ENC["csr"], (200, 50), [np.array([1]), np.array([2])], np.array([1.0])), sp.sp_encode(*ENC["csc"], 32, 32))
+    assert err.value.code == 10
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, 0)
+    ref = oracle.spgemm_coo(a.shape, a.rows, a.cols, a.vals, b.shape, b.rows, b.cols, b.vals)
+    check(sp.sp_spgemm(A, B, sp.sp_encode(*ENC["csr"], 32, 32)), "csr", (300, 9100), ref, np.float64)     # automatic: the other kernel
+    # small integers, zeros among them, through the workspace kernel: bit for bit, kept zeros included
+    a, b = pair(400, 300, 350, 5000, 4000)
+    va, vb = prng.small_ints(7, 1, a.nnz), prng.small_ints(7, 2, b.nnz)
+    ref = oracle.spgemm_coo(a.shape, a.rows, a.cols, va, b.shape, b.rows, b.cols, vb)
+    for fa in ("csr", "dcsr"):
+        A = gpu_pack(*ENC[fa], a.shape, [a.rows, a.cols], va)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, 2)
+        C = sp.sp_spgemm(A, gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], vb), sp.sp_encode(*ENC["csr"], 32, 32))
+        check(C, "csr", (400, 350), ref, np.float64, exact=True)
+
+
 def test_spgemm_degenerate_and_errors():
     e = np.zeros(0, dtype=np.int64)
     enc = sp.sp_encode(*ENC["csr"], 32, 32)
