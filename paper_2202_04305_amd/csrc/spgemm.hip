@@ -12,7 +12,7 @@
 // When a full row of C fits the LDS (72 KB: 9216 columns in f64) and the operands are CSR / DCSR with a CSR result,
 // the paper's workspace itself is used instead, one wave per row of A with the workspace in LDS: a first kernel
 // marks the columns a row reaches in an n-bit map and counts them, the counts are scanned into C's pos, and a second
-// kernel adds the products into a dense row of n values, then walks the bit map in column order and writes crd and
+// kernel adds the products into a dense row of n values (32 chunks of 64 entries of B requested at a time), then walks the bit map in column order and writes crd and
 // values: the paper's expand / compress, with the sort of the added indices replaced by the ordered walk.  One wave
 // owns a row and takes the pairs in a fixed order, so there are no atomics on values and the bits repeat.
 #include "spmi_internal.h"
@@ -156,8 +156,29 @@ __global__ __launch_bounds__(64) void spgemm_ws_count_kernel(const PT *__restric
     if (lane == 0) count[arowid ? (int64_t)arowid[r] : r] = (PT)c;
 }
 
-// block = one wave = one stored row r of A; LDS: n values, then the n-bit map.  U rows of B are requested together and
-// then added in turn: the order of the additions to one element is fixed by the structure, not by timing.
+// block = one wave = one stored row r of A; LDS: n values, the n-bit map, then a short list of chunk descriptors.
+// The rows of B that the row of A selects are cut into chunks of 64 entries (one per lane); U chunks are requested
+// together, whichever rows they belong to, and then added in turn, so that only two waves per CU (the workspace
+// fills the LDS) still keep many loads in flight.  The order of the additions to one element is fixed by the
+// structure, not by timing.
+constexpr int kChunkList = 64;             // one descriptor per lane
+template <typename VT>
+struct chunk_list {
+    int64_t start[kChunkList];
+    int32_t len[kChunkList];
+    VT a[kChunkList];
+};
+
+// the value a given lane holds, as a wave-uniform value (lane index uniform)
+__device__ inline int64_t uniform_i64(int64_t v, int src)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uint64_t)v, src);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), src);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ inline double uniform_val(double v, int src) { return __longlong_as_double(uniform_i64(__double_as_longlong(v), src)); }
+__device__ inline float uniform_val(float v, int src) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src)); }
+
 template <typename PT, typename CT, typename VT, int U>
 __global__ __launch_bounds__(64) void spgemm_ws_numeric_kernel(const PT *__restrict__ apos, const CT *__restrict__ acrd,
                                                                const VT *__restrict__ aval, const CT *__restrict__ arowid,
@@ -166,6 +187,7 @@ __global__ __launch_bounds__(64) void spgemm_ws_numeric_kernel(const PT *__restr
                                                                CT *__restrict__ ccrd, VT *__restrict__ cval)
 {
     extern __shared__ unsigned char ws_raw[];
+    __shared__ chunk_list<VT> list;
     VT *acc = (VT *)ws_raw;
     uint32_t *bits = (uint32_t *)(ws_raw + (size_t)n * sizeof(VT));
     const int lane = threadIdx.x;
@@ -186,52 +208,81 @@ __global__ __launch_bounds__(64) void spgemm_ws_numeric_kernel(const PT *__restr
             b0 = (int64_t)bpos[k];
             b1 = (int64_t)bpos[k + 1];
         }
-        const int cnt = (int)(a1 - g < 64 ? a1 - g : 64);
-        for (int x0 = 0; x0 < cnt; x0 += U) {                      // wave-uniform
-            int64_t s0[U], s1[U];
-            VT av[U];
-            int64_t longest = 0;
+        // chunks of this lane's row of B, numbered across the wave in lane order
+        const int mine = (int)((b1 - b0 + 63) >> 6);
+        int before = mine;                                         // inclusive scan over the lanes
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int x = x0 + u < cnt ? x0 + u : x0;           // past the end: an empty range
-                s0[u] = __shfl(b0, x, 64);
-                s1[u] = x0 + u < cnt ? __shfl(b1, x, 64) : s0[u];
-                av[u] = __shfl(a, x, 64);
-                longest = s1[u] - s0[u] > longest ? s1[u] - s0[u] : longest;
-            }
-            for (int64_t c = 0; c < longest; c += 64) {
-                int64_t j[U];
-                VT bv[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t t = s0[u] + c + lane;
-                    const bool in = t < s1[u];
-                    j[u] = in ? (int64_t)bcrd[t] : -1;
-                    bv[u] = in ? bval[t] : (VT)0;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(before, d, 64);
+            if (lane >= d) before += up;
+        }
+        const int total = __shfl(before, 63, 64);
+        before -= mine;
+        for (int w0 = 0; w0 < total; w0 += kChunkList) {           // wave-uniform: a window of the chunk numbering
+            for (int c = 0; c < mine; ++c) {
+                const int id = before + c - w0;
+                if (id >= 0 && id < kChunkList) {
+                    const int64_t s = b0 + (int64_t)c * 64;
+                    list.start[id] = s;
+                    list.len[id] = (int32_t)(b1 - s < 64 ? b1 - s : 64);
+                    list.a[id] = a;
                 }
+            }
+            __syncthreads();
+            const int here = total - w0 < kChunkList ? total - w0 : kChunkList;
+            // lane x keeps descriptor x in registers; the loop below reads them with readlane (no LDS round trip per chunk)
+            const int64_t my_start = lane < here ? list.start[lane] : 0;
+            const int my_len = lane < here ? list.len[lane] : 0;
+            const VT my_a = lane < here ? list.a[lane] : (VT)0;
+            for (int d0 = 0; d0 < here; d0 += U) {
+                uint32_t j[U];
+                VT p[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if (j[u] >= 0) {
-                        atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
-                        acc[j[u]] += av[u] * bv[u];                  // the lanes of one row of B hold distinct columns
+                    j[u] = 0xffffffffu;
+                    p[u] = (VT)0;
+                    if (d0 + u < here) {                           // wave-uniform
+                        // a wave-uniform base plus the lane: the address needs no vector arithmetic
+                        const int64_t s0 = uniform_i64(my_start, d0 + u);
+                        const CT *cp = bcrd + s0;
+                        const VT *vp = bval + s0;
+                        if (lane < __builtin_amdgcn_readlane(my_len, d0 + u)) {
+                            j[u] = (uint32_t)cp[lane];
+                            p[u] = vp[lane];
+                        }
                     }
-                    __builtin_amdgcn_wave_barrier();
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (d0 + u < here && j[u] != 0xffffffffu) {
+                        // LDS atomics without a return value: the LDS takes one wave's instructions in the order
+                        // they were issued, so the additions to one element still happen in program order
+                        atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
+                        atomicAdd(&acc[j[u]], uniform_val(my_a, d0 + u) * p[u]);
+                    }
                 }
             }
+            __syncthreads();
         }
     }
     __syncthreads();
-    int64_t base = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r];
-    for (int64_t j0 = 0; j0 < n; j0 += 64) {                       // the compress step: set bits in column order
-        const int64_t j = j0 + lane;
-        const bool set = j < n && ((bits[j >> 5] >> (j & 31)) & 1u);
+    // the compress step: set bits in column order.  Row-relative 32-bit positions on wave-uniform row pointers.
+    const int64_t row_at = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r];
+    CT *crow = ccrd + row_at;
+    VT *vrow = cval + row_at;
+    uint32_t base = 0;
+    const uint32_t n32 = (uint32_t)n;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (uint32_t j0 = 0; j0 < n32; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        const bool set = j < n32 && ((bits[j >> 5] >> (j & 31)) & 1u);
         const unsigned long long mask = __ballot(set);
         if (set) {
-            const int64_t o = base + __popcll(mask & ((1ull << lane) - 1ull));
-            ccrd[o] = (CT)j;
-            cval[o] = acc[j];
+            const uint32_t o = base + (uint32_t)__popcll(mask & below);
+            crow[o] = (CT)j;
+            vrow[o] = acc[j];
         }
-        base += __popcll(mask);
+        base += (uint32_t)__popcll(mask);
     }
 }
 
@@ -280,7 +331,7 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             t->nnz = nnzc;
             if (!t->crd[1] || !t->values) { status = SP_ERR_ALLOC; break; }
             if (work && nnzc > 0) {
-                auto kernel = spgemm_ws_numeric_kernel<PT, CT, VT, 4>;
+                auto kernel = spgemm_ws_numeric_kernel<PT, CT, VT, 32>;
                 if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
                     status = SP_ERR_HIP;
                     break;
