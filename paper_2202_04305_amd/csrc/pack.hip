@@ -221,10 +221,8 @@ struct level_args {
 };
 
 // The payload that travels with the key through the sort is the value itself (its bits), so that no gather by
-// entry id is needed afterwards.
-template <typename P>
-__global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64_t nnz, const P *__restrict__ values,
-                                                             uint64_t *__restrict__ keys, P *__restrict__ payload, int *__restrict__ flags)
+// entry id is needed afterwards; the first pass of the sort reads it from the caller's array.
+__global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64_t nnz, uint64_t *__restrict__ keys, int *__restrict__ flags)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
@@ -236,7 +234,6 @@ __global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64
         key = key * (uint64_t)a.size[l] + (uint64_t)c;
     }
     keys[e] = bad ? 0 : key;
-    payload[e] = values[e];
     if (bad) atomicOr(&flags[0], 1);
 }
 
@@ -246,24 +243,57 @@ __global__ __launch_bounds__(kThreads) void check_duplicates_kernel(const uint64
     if (e >= 1 && e < nnz && keys[e] == keys[e - 1]) atomicOr(&flags[1], 1);
 }
 
+// Division of a key by a level's stride or size, which the host knows when it launches: a shift when the divisor is a
+// power of two, a multiplication by the reciprocal in double plus a one-step correction while the dividend is below
+// 2^52 (the estimate is then within one of the quotient), the hardware's 64-bit division otherwise.
+struct divisor {
+    uint64_t d;
+    double inv;
+    int shift;          // >= 0: d == 1 << shift
+};
+
+static divisor make_divisor(uint64_t d)
+{
+    divisor v;
+    v.d = d;
+    v.inv = 1.0 / (double)d;
+    v.shift = -1;
+    if ((d & (d - 1)) == 0) { v.shift = 0; while (((uint64_t)1 << v.shift) != d) ++v.shift; }
+    return v;
+}
+
+__device__ inline uint64_t div_by(uint64_t x, const divisor &v)
+{
+    if (v.shift >= 0) return x >> v.shift;
+    if (x < ((uint64_t)1 << 52)) {
+        uint64_t q = (uint64_t)((double)x * v.inv);
+        const int64_t r = (int64_t)(x - q * v.d);
+        if (r < 0) --q;
+        else if ((uint64_t)r >= v.d) ++q;
+        return q;
+    }
+    return x / v.d;
+}
+
 // dense level: position = parent * size + coordinate
-__global__ __launch_bounds__(kThreads) void dense_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
-                                                               uint64_t size, const uint64_t *__restrict__ parent_in,
+__global__ __launch_bounds__(kThreads) void dense_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, divisor stride,
+                                                               divisor size, const uint64_t *__restrict__ parent_in,
                                                                uint64_t *__restrict__ parent_out)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
-    const uint64_t c = (keys[e] / stride) % size;
-    parent_out[e] = (parent_in ? parent_in[e] : 0ull) * size + c;
+    const uint64_t pre = div_by(keys[e], stride);
+    const uint64_t c = pre - div_by(pre, size) * size.d;
+    parent_out[e] = (parent_in ? parent_in[e] : 0ull) * size.d + c;
 }
 
 // compressed level, step 1: mark[e] = 1 where the key prefix down to this level changes
-__global__ __launch_bounds__(kThreads) void mark_children_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
+__global__ __launch_bounds__(kThreads) void mark_children_kernel(const uint64_t *__restrict__ keys, int64_t nnz, divisor stride,
                                                                  uint32_t *__restrict__ mark)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
-    mark[e] = (e == 0 || keys[e] / stride != keys[e - 1] / stride) ? 1u : 0u;
+    mark[e] = (e == 0 || div_by(keys[e], stride) != div_by(keys[e - 1], stride)) ? 1u : 0u;
 }
 
 // compressed level, step 2: write crd, count children per parent (one add per run end, one
@@ -271,22 +301,24 @@ __global__ __launch_bounds__(kThreads) void mark_children_kernel(const uint64_t 
 // and hand each entry its child position.  child_excl = exclusive scan of the marks, or
 // nullptr on the innermost level, where every entry is its own child.
 template <typename PT, typename CT>
-__global__ __launch_bounds__(kThreads) void emit_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, uint64_t stride,
-                                                              uint64_t size, const uint32_t *__restrict__ child_excl,
+__global__ __launch_bounds__(kThreads) void emit_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, divisor stride,
+                                                              divisor size, const uint32_t *__restrict__ child_excl,
                                                               const uint64_t *__restrict__ parent_in, uint64_t *__restrict__ parent_out,
                                                               PT *__restrict__ cnt, CT *__restrict__ crd)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
-    const uint64_t pre = keys[e] / stride;
-    const bool first = (e == 0) || (keys[e - 1] / stride != pre);
+    const uint64_t pre = div_by(keys[e], stride);
+    const uint64_t pre_before = e > 0 ? div_by(keys[e - 1], stride) : 0;
+    const bool first = (e == 0) || (pre_before != pre);
     const uint64_t child = child_excl ? (uint64_t)child_excl[e] + (first ? 1u : 0u) - 1u : (uint64_t)e;
-    if (first) crd[child] = (CT)(pre % size);
+    const uint64_t up = div_by(pre, size);
+    if (first) crd[child] = (CT)(pre - up * size.d);
     // position of the entry at the level above: carried in parent_in, or, while every level above is dense, simply
     // the key prefix down to that level (pre / size), which needs no array
-    const uint64_t par = parent_in ? parent_in[e] : pre / size;
-    const bool head = (e == 0) || (parent_in ? parent_in[e - 1] : keys[e - 1] / stride / size) != par;
-    const bool tail = (e == nnz - 1) || (parent_in ? parent_in[e + 1] : keys[e + 1] / stride / size) != par;
+    const uint64_t par = parent_in ? parent_in[e] : up;
+    const bool head = (e == 0) || (parent_in ? parent_in[e - 1] : div_by(pre_before, size)) != par;
+    const bool tail = (e == nnz - 1) || (parent_in ? parent_in[e + 1] : div_by(div_by(keys[e + 1], stride), size)) != par;
     typedef typename std::conditional<sizeof(PT) == 8, unsigned long long, unsigned int>::type UT;
     if (tail) atomicAdd((UT *)&cnt[par], (UT)(child + 1));
     if (head) atomicAdd((UT *)&cnt[par], (UT)(0) - (UT)child);
@@ -418,40 +450,52 @@ sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, 
     return exclusive_scan_t<unsigned long long>((unsigned long long *)data, n, tmp, st);
 }
 
+static size_t pad16(size_t b);
+
+// keys: n entries in a temporary of `tmp`, reordered freely; vals_in: n payloads, only read (it may be the caller's own
+// array).  On return *keys_out / *vals_out point at the sorted arrays: temporaries of `tmp`, or the inputs when there
+// was nothing to sort.
 template <typename P>
-static sp_status radix_sort_pairs_t(uint64_t *keys, P *vals, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
+static sp_status radix_sort_pairs_t(uint64_t *keys, const P *vals_in, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                                    uint64_t **keys_out, const P **vals_out)
 {
+    *keys_out = keys;
+    *vals_out = vals_in;
     if (n <= 1 || key_bits <= 0) return SP_OK;
     const int passes = (key_bits + 7) / 8;
     const int nblocks = (int)ceil_div(n, kSortTile);
     uint64_t *kalt = (uint64_t *)tmp.get((size_t)n * 8);
-    P *valt = (P *)tmp.get((size_t)n * sizeof(P));
+    P *va = (P *)tmp.get(pad16((size_t)n * sizeof(P)));
+    P *vb = passes > 1 ? (P *)tmp.get(pad16((size_t)n * sizeof(P))) : va;
     uint32_t *hist = (uint32_t *)tmp.get((size_t)256 * nblocks * 4);
-    if (!kalt || !valt || !hist) return SP_ERR_ALLOC;
+    if (!kalt || !va || !vb || !hist) return SP_ERR_ALLOC;
     uint64_t *kin = keys, *kout = kalt;
-    P *vin = vals, *vout = valt;
+    const P *vin = vals_in;
+    P *vout = va;
     for (int p = 0; p < passes; ++p) {
         const int shift = 8 * p;
         hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, n, shift, hist, nblocks);
         SP_HIP(hipGetLastError());
         SP_TRY(spmi_exclusive_scan(hist, (int64_t)256 * nblocks, 32, tmp, st));
-        hipLaunchKernelGGL(radix_scatter_kernel<P>, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, (const P *)vin, kout, vout,
+        hipLaunchKernelGGL(radix_scatter_kernel<P>, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, vin, kout, vout,
                            (const uint32_t *)hist, n, shift, nblocks);
         SP_HIP(hipGetLastError());
         uint64_t *tk = kin; kin = kout; kout = tk;
-        P *tv = vin; vin = vout; vout = tv;
+        vin = vout;
+        vout = vout == va ? vb : va;
     }
-    if (kin != keys) {      // odd number of passes: bring the result home
-        SP_HIP(hipMemcpyAsync(keys, kin, (size_t)n * 8, hipMemcpyDeviceToDevice, st));
-        SP_HIP(hipMemcpyAsync(vals, vin, (size_t)n * sizeof(P), hipMemcpyDeviceToDevice, st));
-    }
+    *keys_out = kin;
+    *vals_out = vin;
     return SP_OK;
 }
 
-sp_status spmi_radix_sort_pairs(uint64_t *keys, void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st)
+sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
+                                hipStream_t st, uint64_t **keys_out, const void **vals_out)
 {
-    if (payload_bytes == 4) return radix_sort_pairs_t<uint32_t>(keys, (uint32_t *)vals, n, key_bits, tmp, st);
-    return radix_sort_pairs_t<unsigned long long>(keys, (unsigned long long *)vals, n, key_bits, tmp, st);
+    if (payload_bytes == 4)
+        return radix_sort_pairs_t<uint32_t>(keys, (const uint32_t *)vals, n, key_bits, tmp, st, keys_out, (const uint32_t **)vals_out);
+    return radix_sort_pairs_t<unsigned long long>(keys, (const unsigned long long *)vals, n, key_bits, tmp, st, keys_out,
+                                                  (const unsigned long long **)vals_out);
 }
 
 static size_t pad16(size_t b) { return (b + 15) & ~(size_t)15; }
@@ -632,7 +676,7 @@ extern "C" void sp_tensor_free(sp_tensor *t)
 }
 
 template <typename PT, typename CT>
-static sp_status launch_emit(const uint64_t *keys, int64_t nnz, uint64_t stride, uint64_t size, const uint32_t *child_excl,
+static sp_status launch_emit(const uint64_t *keys, int64_t nnz, divisor stride, divisor size, const uint32_t *child_excl,
                              const uint64_t *pin, uint64_t *pout, void *cnt, void *crd, hipStream_t st)
 {
     hipLaunchKernelGGL((emit_level_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, keys, nnz, stride, size, child_excl,
@@ -695,7 +739,7 @@ __global__ __launch_bounds__(kThreads) void mark_heads_kernel(const uint64_t *__
     if (e < n) mark[e] = (e == 0 || keys[e] != keys[e - 1]) ? 1u : 0u;
 }
 
-static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payload, int key_bits, bool sum_duplicates, int *flags,
+static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void *payload, int key_bits, bool sum_duplicates, int *flags,
                            sp_scratch &tmp, const sp_mem &mem, hipStream_t st)
 {
     const sp_encoding *enc = &t->enc;
@@ -707,7 +751,7 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
     uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
     if (!child) return SP_ERR_ALLOC;
     if (nnz > 0) {
-        SP_TRY(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st));
+        SP_TRY(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st, &keys, &payload));
         if (!sum_duplicates) {
             hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
             SP_HIP(hipGetLastError());
@@ -732,7 +776,7 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
         const int64_t distinct = (int64_t)last_excl + (lastk[0] != lastk[1] ? 1 : 0);
         if (distinct != nnz) {
             uint64_t *k2 = (uint64_t *)tmp.get((size_t)distinct * 8);
-            void *v2 = tmp.get((size_t)distinct * vsz0);
+            void *v2 = tmp.get(pad16((size_t)distinct * vsz0));
             if (!k2 || !v2) return SP_ERR_ALLOC;
             if (dt == SP_F64)
                 hipLaunchKernelGGL(sum_runs_kernel<double>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys,
@@ -754,9 +798,10 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
     int which = 0;
     int64_t P = 1;
     for (int l = 0; l < rank; ++l) {
-        uint64_t stride = 1;
-        for (int k = l + 1; k < rank; ++k) stride *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
-        const uint64_t size = (uint64_t)(t->size[l] > 0 ? t->size[l] : 1);
+        uint64_t stride_u = 1;
+        for (int k = l + 1; k < rank; ++k) stride_u *= (uint64_t)(t->size[k] > 0 ? t->size[k] : 1);
+        const divisor stride = make_divisor(stride_u);
+        const divisor size = make_divisor((uint64_t)(t->size[l] > 0 ? t->size[l] : 1));
         if (enc->lt[l] == SP_DENSE && dense_prefix) {
             P *= t->size[l];                  // nothing to compute: the position at this level is the key prefix
             continue;
@@ -789,7 +834,7 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
                 const int64_t from = nnz >= 2 ? nnz - 2 : 0;
                 SP_HIP(hipMemcpyAsync(lastk, keys + from, (size_t)(nnz - from) * 8, hipMemcpyDeviceToHost, st));
                 SP_HIP(hipStreamSynchronize(st));
-                const bool last_mark = nnz == 1 || (lastk[0] / stride != lastk[1] / stride);
+                const bool last_mark = nnz == 1 || (lastk[0] / stride_u != lastk[1] / stride_u);
                 nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
                 child_excl = child;
             }
@@ -841,24 +886,30 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, void *payl
         SP_HIP(hipGetLastError());
     }
 
-    // values: zero padding only where a dense level sits below a compressed one
+    // values: zero padding only where a dense level sits below a compressed one.  With a compressed innermost level the
+    // sorted payload already is the values array: the tensor takes that buffer over when the sort (or the summation)
+    // made it, and copies only when it still is the caller's own array.
     const size_t vsz = dt == SP_F64 ? 8 : 4;
     const size_t vbytes = pad16((size_t)(P > 0 ? P : 1) * vsz);
-    t->values = mem.get(vbytes);
     t->nvalues = P;
-    if (!t->values) return SP_ERR_ALLOC;
-    if (P != nnz) SP_TRY(spmi_fill_zero(t->values, vbytes, st));
-    if (nnz > 0) {
-        // where each sorted entry's value goes: its own rank (innermost level compressed), the key itself (every
-        // level dense), or the position carried down from the last compressed level
-        const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : dense_prefix ? (const uint64_t *)keys : pin;
-        if (dt == SP_F64)
-            hipLaunchKernelGGL(place_values_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
-                               (const unsigned long long *)payload, position, nnz, (unsigned long long *)t->values);
-        else
-            hipLaunchKernelGGL(place_values_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
-                               (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
-        SP_HIP(hipGetLastError());
+    if (nnz > 0 && enc->lt[rank - 1] == SP_COMPRESSED && tmp.release((void *)payload)) {
+        t->values = (void *)payload;
+    } else {
+        t->values = mem.get(vbytes);
+        if (!t->values) return SP_ERR_ALLOC;
+        if (P != nnz) SP_TRY(spmi_fill_zero(t->values, vbytes, st));
+        if (nnz > 0) {
+            // where each sorted entry's value goes: its own rank (innermost level compressed), the key itself (every
+            // level dense), or the position carried down from the last compressed level
+            const uint64_t *position = (enc->lt[rank - 1] == SP_COMPRESSED) ? nullptr : dense_prefix ? (const uint64_t *)keys : pin;
+            if (dt == SP_F64)
+                hipLaunchKernelGGL(place_values_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                                   (const unsigned long long *)payload, position, nnz, (unsigned long long *)t->values);
+            else
+                hipLaunchKernelGGL(place_values_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st,
+                                   (const uint32_t *)payload, position, nnz, (uint32_t *)t->values);
+            SP_HIP(hipGetLastError());
+        }
     }
     return spmi_finish_tensor(t, flags, tmp, st);
 }
@@ -928,25 +979,19 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
         sp_scratch tmp(mem);
         const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
         uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
-        void *payload = tmp.get(cnt * (dt == SP_F64 ? 8 : 4));      // the values, carried through the sort
         int *flags = (int *)tmp.get(64);
         do {
-            if (!keys || !payload || !flags) { status = SP_ERR_ALLOC; break; }
+            if (!keys || !flags) { status = SP_ERR_ALLOC; break; }
             if ((status = spmi_fill_zero(flags, 64, st)) != SP_OK) break;
             if (nnz > 0) {
                 level_args la;
                 memset(&la, 0, sizeof(la));
                 la.rank = rank;
                 for (int l = 0; l < rank; ++l) { la.coord[l] = coords[enc->perm[l]]; la.size[l] = t->size[l]; }
-                if (dt == SP_F64)
-                    hipLaunchKernelGGL(make_keys_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz,
-                                       (const unsigned long long *)values, keys, (unsigned long long *)payload, flags);
-                else
-                    hipLaunchKernelGGL(make_keys_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz,
-                                       (const uint32_t *)values, keys, (uint32_t *)payload, flags);
+                hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz, keys, flags);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
-            status = pack_core(t, nnz, keys, payload, key_bits, false, flags, tmp, mem, st);
+            status = pack_core(t, nnz, keys, values, key_bits, false, flags, tmp, mem, st);   // the values are the sort's payload
         } while (0);
         if (status != SP_OK) (void)hipStreamSynchronize(st);   // temporaries may still be in use by queued kernels
     }

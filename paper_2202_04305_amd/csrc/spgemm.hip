@@ -101,7 +101,7 @@ sp_status spgemm_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *e
         total = (int64_t)htotal;
     }
     uint64_t *keys = (uint64_t *)tmp.get((size_t)(total > 0 ? total : 1) * 8);
-    VT *payload = (VT *)tmp.get((size_t)(total > 0 ? total : 1) * sizeof(VT));
+    VT *payload = (VT *)tmp.get((((size_t)(total > 0 ? total : 1) * sizeof(VT)) + 15) & ~(size_t)15);   // the result may keep it as its values
     if (!keys || !payload) return SP_ERR_ALLOC;
     if (total > 0) {
         const int c_is_row_major = encC->perm[0] == 0;

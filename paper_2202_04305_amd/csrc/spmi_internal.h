@@ -124,14 +124,23 @@ struct sp_scratch {
         if (p) ptrs.push_back(p);
         return p;
     }
+    // Takes a temporary out of the scope (its new owner frees it through the same allocator); false when p is not one.
+    bool release(void *p) {
+        for (size_t i = 0; i < ptrs.size(); ++i)
+            if (ptrs[i] == p) { ptrs.erase(ptrs.begin() + (long)i); return true; }
+        return false;
+    }
 };
 
 // ---- pack.hip ----------------------------------------------------------------------------
 // In-place exclusive prefix sum of n elements of width `bits` (32 or 64); data[n-1] afterwards
 // holds the sum of the first n-1 inputs.
 sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, hipStream_t st);
-// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits, payload of 4 or 8 bytes; results end in keys/vals.
-sp_status spmi_radix_sort_pairs(uint64_t *keys, void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st);
+// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits, payload of 4 or 8 bytes.  keys: a temporary of
+// `tmp`, overwritten; vals: only read.  *keys_out / *vals_out: where the sorted arrays are (temporaries of `tmp`, or
+// the inputs themselves when there was nothing to sort).
+sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
+                                hipStream_t st, uint64_t **keys_out, const void **vals_out);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
 // The storage of a tensor whose n entries are given as linearised keys (level order, mixed radix over the level sizes)
 // with the value bits as payload, both temporaries of `tmp`; entries with equal keys are added up in the order given.
