@@ -205,6 +205,80 @@ def bench_mttkrp(args, torch, sp, dev):
     print(json.dumps(out))
 
 
+def bench_pack(args, torch, sp, dev):
+    """The storage builder alone (Section 6.1 measures reading and packing tensors into an all-compressed format): four
+    synthetic tensors with the rank and entry count of the paper's table, uniform random distinct coordinates in a
+    seeded shuffled order, packed with every level compressed.  The paper prints no shapes except the rank-3 one;
+    the others are this benchmark's own choice.  One step = one sp_pack (it synchronises)."""
+    from gen import workloads as W, prng
+    cases = [("rank 2", (16384, 16384), 1_091_362, 136.0), ("rank 3", (12092, 9184, 28818), 76_879_419, 2055.0),
+             ("rank 4", (256, 32, 1024, 2048), 3_309_490, 107.0), ("rank 5", (131072, 8192, 2, 128, 64), 26_021_945, 1728.0)]
+    if args.small:
+        cases = [(n, s, z // 64, p) for n, s, z, p in cases]
+    steps = args.steps or 5
+    warmup = args.warmup or 1
+    table, t0 = [], time.time()
+    cpu, parity = None, None
+    for ci, (label, shape, nnz, paper_ms) in enumerate(cases):
+        rank = len(shape)
+        cells = int(np.prod([int(x) for x in shape]))
+        _, lin = W.distinct_sorted_per_segment(W.BASE_SEED + 800 + ci, 1, np.array([nnz], dtype=np.int64), cells)
+        lin = lin[prng.permutation(W.BASE_SEED + 800 + ci, 2, nnz)]
+        coords, rest = [], lin
+        for d in range(rank - 1, -1, -1):
+            coords.insert(0, np.ascontiguousarray(rest % shape[d]))
+            rest = rest // shape[d]
+        vals = prng.uniform_pm1(W.BASE_SEED + 800 + ci, 3, nnz)
+        enc = sp.sp_encode((1,) * rank, tuple(range(rank)), args.width, args.width)
+        cd = [torch.from_numpy(c).to(dev) for c in coords]
+        vd = torch.from_numpy(vals).to(dev)
+        for _ in range(warmup):
+            sp.sp_pack(enc, shape, cd, vd).free()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            sp.sp_pack(enc, shape, cd, vd).free()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        T = sp.sp_pack(enc, shape, cd, vd)
+        info = sp.sp_tensor_info(T)
+        in_bytes = nnz * (8 * rank + 8)
+        row = {"tensor": label, "shape": list(shape), "nnz": nnz, "ms": ms, "mnnz_per_s": nnz / ms / 1e3,
+               "bytes": int(in_bytes + info.storageBytes), "paper_pack_ms": paper_ms}
+        if not args.no_cpu and nnz <= 4_000_000:
+            import oracle
+            t1 = time.time()
+            ref = oracle.pack((1,) * rank, tuple(range(rank)), shape, coords, vals, args.width, args.width)
+            row["oracle_ms"] = (time.time() - t1) * 1e3
+            ok = all(np.array_equal(sp.sp_pos(T, l).cpu().numpy(), ref.pos[l]) and np.array_equal(sp.sp_crd(T, l).cpu().numpy(), ref.crd[l])
+                     for l in range(rank)) and sp.sp_values(T).cpu().numpy().tobytes() == ref.values.tobytes()
+            parity = ok if parity is None else (parity and ok)
+            cpu = {"value": row["bytes"] / (row["oracle_ms"] * 1e-3) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                   "sample": "the %s tensor (%d entries), one run, %.3f s" % (label, nnz, row["oracle_ms"] * 1e-3)}
+        table.append(row)
+        T.free()
+        del cd, vd
+    gen_s = time.time() - t0
+    top = max(table, key=lambda r: r["nnz"])
+    achieved = top["bytes"] / (top["ms"] * 1e-3) / 1e9
+    out = {
+        "metric": "effective HBM GB/s (algorithmic bytes / time per pack)",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": top["ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "sp_pack to an all-compressed format (Section 6.1): %s, %s, %d entries (coordinates int64 per dimension + f64 "
+                               "values in, pos/crd %d-bit + values out)" % (top["tensor"], "x".join(str(x) for x in top["shape"]), top["nnz"], args.width),
+                   "kernel": "make_keys + radix sort passes + level sweep", "small": bool(args.small)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole sp_pack call (allocation and host synchronisations included)", "kernel_us": top["ms"] * 1e3,
+                     "algorithmic_bytes": top["bytes"]},
+        "cpu_baseline": cpu, "table": table, "parity_ok": parity, "gen_s": gen_s,
+        "paper_note": "paper_pack_ms: the pack column of the paper's input table (its real tensors, one Xeon W2135 core), context only",
+    }
+    print(json.dumps(out))
+
+
 def bench_spmspm(args, torch, sp, dev):
     """C = A.B with sparse A, B and C, all CSR (Sections 4.4 and 6.2): n x n uniform random operands of density 0.01, the
     sizes of the paper's table; the headline line is the largest one.  One step = one sp_spgemm (it allocates and
@@ -283,7 +357,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed products (default: 300 for SpMV, 20 for SpMM)")
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm", "mttkrp", "spmspm"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "rowband", "sddmm", "mttkrp", "spmspm", "pack"])
     ap.add_argument("--format", default="", choices=["", "csr", "dcsr", "cdr", "dense", "dss", "dss-alt", "sss", "sss-alt"],
                     help="store the workload's matrix under another row-major encoding (rowband: csr, dcsr or cdr as in the paper's table); "
                          "mttkrp: dss (default) / dss-alt as in the paper's table, sss / sss-alt with a compressed outer level")
@@ -312,6 +386,8 @@ def main():
         return bench_mttkrp(args, torch, sp, dev)
     if name == "spmspm":
         return bench_spmspm(args, torch, sp, dev)
+    if name == "pack":
+        return bench_pack(args, torch, sp, dev)
     t0 = time.time()
     w = make_workload(name, args.small)
     gen_s = time.time() - t0
