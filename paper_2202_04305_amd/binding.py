@@ -165,15 +165,16 @@ def _dt(t):
     return -1
 
 
-def sp_pack(enc, shape, coords, values):
-    """coords: one int64 device tensor per dimension; values: device tensor (f32/f64)."""
+def sp_pack(enc, shape, coords, values, allocator=None):
+    """coords: one int64 device tensor per dimension; values: device tensor (f32/f64).  allocator: an object with
+    alloc_cb / free_cb (ctypes callbacks) that outlives the tensor; default: torch's caching allocator."""
     L = load_library()
     assert values.is_cuda and all(c.is_cuda and c.dtype == torch.int64 and c.is_contiguous() for c in coords)
     assert values.is_contiguous()
     nnz = int(values.shape[0])
     shp = (ctypes.c_int64 * max(len(shape), 1))(*[int(s) for s in shape])
     carr = (ctypes.c_void_p * max(len(coords), 1))(*[c.data_ptr() for c in coords])
-    allocator = _TorchAllocator(values.device)
+    allocator = allocator or _TorchAllocator(values.device)
     h = ctypes.c_void_p()
     code = L.sp_pack(enc._h, shp, nnz, carr, values.data_ptr(), _dt(values), allocator.alloc_cb, allocator.free_cb, None,
                      _stream_ptr(), ctypes.byref(h))
