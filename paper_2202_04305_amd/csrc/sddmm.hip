@@ -71,14 +71,45 @@ __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *_
                 const int64_t pc = pp[u] < b ? pp[u] : b - 1;
                 bv[u] = *(const vec_t *)(Bt + (int64_t)crd[pc] * ldt + jl * V);
             }
+            VT dot[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                VT dot = 0;
+                dot[u] = 0;
 #pragma unroll
-                for (int ee = 0; ee < V; ++ee) dot += av[ee] * bv[u][ee];
+                for (int ee = 0; ee < V; ++ee) dot[u] += av[ee] * bv[u][ee];
+            }
+            if (LR >= U) {
+                // The U sums are reduced together: each of the first log2(U) exchange steps halves the number of sums
+                // a lane carries (a lane keeps the half its bit selects and hands the other half over), the remaining
+                // steps finish the one sum left.  U - 1 + log2(LR / U) shuffles instead of U * log2(LR); sum u ends
+                // complete in the lanes whose top bits of jl are u.
+                int m = LR / 2;
 #pragma unroll
-                for (int d = LR / 2; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
-                if (jl == 0 && pp[u] < b) X[pp[u]] = sval[pp[u]] * dot;
+                for (int n = U; n > 1; n >>= 1) {
+                    const bool upper = (jl & m) != 0;
+#pragma unroll
+                    for (int k = 0; k < n / 2; ++k) {
+                        const VT send = upper ? dot[k] : dot[k + n / 2];
+                        const VT keep = upper ? dot[k + n / 2] : dot[k];
+                        dot[k] = keep + __shfl_xor(send, m, 64);
+                    }
+                    m >>= 1;
+                }
+#pragma unroll
+                for (; m >= 1; m >>= 1) dot[0] += __shfl_xor(dot[0], m, 64);
+                constexpr int G = LR / U > 0 ? LR / U : 1;      // lanes that end with the same sum
+                const int u = jl / G;
+                int64_t mine = pp[0];
+#pragma unroll
+                for (int k = 1; k < U; ++k) mine = u == k ? pp[k] : mine;
+                if (jl % G == 0 && mine < b) X[mine] = sval[mine] * dot[0];
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+#pragma unroll
+                    for (int d = LR / 2; d >= 1; d >>= 1) dot[u] += __shfl_xor(dot[u], d, 64);
+                    if (jl == 0 && pp[u] < b) X[pp[u]] = sval[pp[u]] * dot[u];
+                }
             }
         }
     }
