@@ -30,6 +30,18 @@ __global__ __launch_bounds__(kThreads) void zero_rows_kernel(char *__restrict__ 
         *(uint32_t *)(A + (t / words) * ld_bytes + (t % words) * 4) = 0u;
 }
 
+// dst[r, 0..cols) = src[r, 0..cols) for a row-major matrix with other leading dimensions (16-byte pieces)
+__global__ __launch_bounds__(kThreads) void repitch_rows_kernel(const char *__restrict__ src, int64_t src_ld_bytes, int64_t rows,
+                                                                int64_t row_bytes, char *__restrict__ dst, int64_t dst_ld_bytes)
+{
+    const int64_t pieces = row_bytes / 16;
+    const int64_t total = rows * pieces;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < total; t += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = t / pieces, c = t % pieces;
+        *(uint4 *)(dst + r * dst_ld_bytes + c * 16) = *(const uint4 *)(src + r * src_ld_bytes + c * 16);
+    }
+}
+
 // wfib[w] = level-1 fibre holding entry w*TW, wslc[w] = level-0 position holding that fibre (largest index whose
 // pos entry is <= the target: empty slices are skipped by construction).  A window boundary w that is the first one
 // its slice crosses (the slice begins inside window w - 1) is appended to `cross` (count in cross[-1]); the order of
@@ -279,9 +291,41 @@ sp_status mttkrp_t(const sp_tensor *B, const VT *M, int64_t ldm, const VT *X, in
     constexpr int VV = 16 / sizeof(VT);
     const bool vec = J % VV == 0 && ldm % VV == 0 && ldx % VV == 0 && lda % VV == 0 && (uintptr_t)M % 16 == 0 && (uintptr_t)X % 16 == 0 &&
                      (uintptr_t)A % 16 == 0 && (uintptr_t)B->mttkrp_carry % 16 == 0;
-    // byte offsets into the factor matrices fit 32 bits when both are below 4 GB
     const int64_t K = B->shape[1], L = B->shape[2];
     const int64_t rows_m = B->enc.perm[1] == 1 ? K : L, rows_x = B->enc.perm[1] == 1 ? L : K;
+    // The inner factor is gathered a row per stored entry, the mid factor a row per fibre.  When such a matrix is
+    // larger than an XCD's L2 and its rows do not start on 128-byte lines, a copy with rows padded to whole lines is
+    // gathered from instead (a 336-byte row then touches 3 lines, not 3.6 on average); the copy is made on every call
+    // into a buffer the tensor keeps.
+    const int64_t row_bytes = J * (int64_t)sizeof(VT);
+    for (int which = 0; which < 2; ++which) {
+        const VT *&F = which == 0 ? X : M;
+        int64_t &ldf = which == 0 ? ldx : ldm;
+        const int64_t rows_f = which == 0 ? rows_x : rows_m;
+        if (!(vec && rows_f * row_bytes > ((int64_t)4 << 20) && row_bytes % 128 != 0 &&
+              (ldf * (int64_t)sizeof(VT) % 128 != 0 || (uintptr_t)F % 128 != 0)))
+            continue;
+        const int64_t ldp_bytes = (row_bytes + 127) / 128 * 128;
+        const size_t want = (size_t)rows_f * (size_t)ldp_bytes;
+        if (Bt->mttkrp_pad_bytes[which] < want) {
+            if (Bt->mttkrp_pad[which]) {
+                SP_HIP(hipStreamSynchronize(st));
+                mem.put(Bt->mttkrp_pad[which]);
+                Bt->mttkrp_pad[which] = nullptr;
+                Bt->mttkrp_pad_bytes[which] = 0;
+            }
+            Bt->mttkrp_pad[which] = mem.get(want);
+            if (!Bt->mttkrp_pad[which]) return SP_ERR_ALLOC;
+            Bt->mttkrp_pad_bytes[which] = want;
+        }
+        const int64_t pieces = rows_f * (row_bytes / 16);
+        hipLaunchKernelGGL(repitch_rows_kernel, dim3((unsigned)(ceil_div(pieces, kThreads) < 4096 ? ceil_div(pieces, kThreads) : 4096)), dim3(kThreads),
+                           0, st, (const char *)F, ldf * (int64_t)sizeof(VT), rows_f, row_bytes, (char *)Bt->mttkrp_pad[which], ldp_bytes);
+        SP_HIP(hipGetLastError());
+        F = (const VT *)Bt->mttkrp_pad[which];
+        ldf = ldp_bytes / (int64_t)sizeof(VT);
+    }
+    // byte offsets into the factor matrices fit 32 bits when both are below 4 GB
     const bool small = (uint64_t)rows_m * (uint64_t)ldm * sizeof(VT) < ((uint64_t)1 << 32) && (uint64_t)rows_x * (uint64_t)ldx * sizeof(VT) < ((uint64_t)1 << 32);
     {
         sp_prof_scope prof(B, st);

@@ -658,6 +658,7 @@ static void release_tensor_arrays(sp_tensor *t)
     mem.put(t->spmm_carry); t->spmm_carry = nullptr; t->spmm_carry_bytes = 0;
     mem.put(t->mttkrp_windows); t->mttkrp_windows = nullptr;
     mem.put(t->mttkrp_carry); t->mttkrp_carry = nullptr; t->mttkrp_carry_bytes = 0;
+    for (int w = 0; w < 2; ++w) { mem.put(t->mttkrp_pad[w]); t->mttkrp_pad[w] = nullptr; t->mttkrp_pad_bytes[w] = 0; }
     mem.put(t->nz_rowid); mem.put(t->nz_pos); mem.put(t->nz_rowblocks.start); mem.put(t->nz_rowblocks.carry);
     t->nz_rowid = t->nz_pos = t->nz_rowblocks.start = t->nz_rowblocks.carry = nullptr;
 }

@@ -67,6 +67,8 @@ struct sp_tensor {
     void *mttkrp_windows;            // DEVICE int32[2 * windows]: fibre and slice holding the first entry of each window (rank 3)
     void *mttkrp_carry;              // DEVICE scratch of the MTTKRP (J values per window), grown on demand
     size_t mttkrp_carry_bytes;
+    void *mttkrp_pad[2];             // DEVICE scratch of the MTTKRP: inner / mid factor matrix with rows padded to whole cache lines
+    size_t mttkrp_pad_bytes[2];
     int tune_spmv, tune_csc, tune_spmm, tune_spgemm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned

@@ -108,6 +108,23 @@ def test_mttkrp_one_slice_longer_than_many_windows_and_empty_slices():
             assert np.all(A.cpu().numpy()[[0, 1, 2, 3, 4, 6, 7, 8]] == 0.0)
 
 
+def test_mttkrp_factor_matrices_beyond_the_l2_size():
+    """Inner factor matrices of more than 4 MB whose rows do not start on cache lines are gathered from a padded copy."""
+    w = W.tensor3_slices(I=40, K=13000, L=13500, nnz=120_000, k_mean=300, l_mean=400, sigma=1.0, J=42)
+    C, D = w.factors()
+    ref, mag = oracle.mttkrp_coo(w.shape, w.ci, w.ck, w.cl, w.vals, C, D)
+    Cd, Dd = dev(C), dev(D)
+    for order in ORDERS:
+        say("case mttkrp large factors", order)
+        B = gpu_pack((0, 1, 1), order, w.shape, [w.ci, w.ck, w.cl], w.vals)
+        A = sp.sp_mttkrp(B, Cd, Dd)
+        assert_product_close(A, ref, mag, np.float64, "mttkrp large factors")
+        A2 = sp.sp_mttkrp(B, Cd, Dd)                    # second call: the kept buffer is reused
+        assert torch.equal(A, A2)
+        # the caller's matrices are untouched
+        assert np.array_equal(Cd.cpu().numpy(), C) and np.array_equal(Dd.cpu().numpy(), D)
+
+
 def test_mttkrp_degenerate_and_unsupported():
     C = torch.ones((3, 4), dtype=torch.float64, device=DEV)
     D = torch.ones((5, 4), dtype=torch.float64, device=DEV)
