@@ -51,5 +51,22 @@ def build(verbose=False):
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "client.c")
+C_CLIENT = os.path.join(ROOT, "tests", "c_client", "client")
+
+
+def build_c_client():
+    """The plain-C client of the ABI used by the tests: gcc, the public header as C, linked against libspmi.so."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    tmp = C_CLIENT + ".tmp%d" % os.getpid()
+    subprocess.check_call(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-isystem", os.path.join(rocm, "include"),
+                           "-I", os.path.join(ROOT, "include"), C_CLIENT_SRC, "-o", tmp, "-L", HERE, "-lspmi",
+                           "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+                           "-Wl,-rpath,$ORIGIN/../../paper_2202_04305_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    os.replace(tmp, C_CLIENT)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_client())
