@@ -170,3 +170,36 @@ def test_convert_between_encodings():
     Bt = sp.sp_convert(A, sp.sp_encode((1, 1), (1, 0), 32, 32))
     A.free()
     assert_storage_equal(Bt, oracle.pack((1, 1), (1, 0), w.shape, [w.rows, w.cols], w.vals, 32, 32))
+
+
+def test_random_ranks_levels_orderings_and_widths():
+    """Seeded random encodings of rank 1 to 6: any mix of level types, any ordering, pos / crd widths from 8 to 64 bits
+    (whatever the sizes allow), several sort tiles of entries; the storage bit for bit, then back to coordinates."""
+    rng = np.random.default_rng(220204305)
+    done = 0
+    while done < 48:
+        rank = int(rng.integers(1, 7))
+        shape = tuple(int(x) for x in rng.integers(1, [200, 90, 40, 12, 8, 6][rank - 1] + 1, size=rank))
+        cells = int(np.prod(shape))
+        nnz = int(min(cells, rng.integers(1, 30000)))
+        lt = tuple(int(x) for x in rng.integers(0, 2, size=rank))
+        order = tuple(int(x) for x in rng.permutation(rank))
+        pw, cw = int(rng.choice([8, 16, 32, 64, 0])), int(rng.choice([8, 16, 32, 64, 0]))
+        lin = rng.choice(cells, size=nnz, replace=False)
+        coords = [c.astype(np.int64) for c in np.unravel_index(lin, shape)]
+        vals = rng.standard_normal(nnz)
+        try:
+            ref = oracle.pack(lt, order, shape, coords, vals, pw, cw)
+        except oracle.OracleError as e:
+            assert e.code == oracle.ERR_WIDTH          # the drawn widths cannot hold this tensor: the GPU must say the same
+            with pytest.raises(sp.SpError) as err:
+                gpu_pack(lt, order, shape, coords, vals, pw, cw)
+            assert err.value.code == oracle.ERR_WIDTH
+            continue
+        say("case random", rank, shape, lt, order, pw, cw, nnz)
+        A = gpu_pack(lt, order, shape, coords, vals, pw, cw)
+        assert_storage_equal(A, ref)
+        gc, gv = sp.sp_unpack(A)
+        rc, rv = ref.unpack()
+        assert all(np.array_equal(g.cpu().numpy(), r) for g, r in zip(gc, rc)) and np.array_equal(gv.cpu().numpy(), rv)
+        done += 1
