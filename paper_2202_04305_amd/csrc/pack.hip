@@ -688,12 +688,14 @@ static sp_status launch_emit(const uint64_t *keys, int64_t nnz, divisor stride, 
 
 // The tables a finished storage carries for the product kernels: longest innermost segment (kernel choice), the row
 // blocks of the streaming kernels, the list of non-empty rows of a mostly empty CSR.  flags: 64 device bytes, the
-// second half zero.  Synchronises.
-sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st)
+// second half zero.  Synchronises.  input_flags (HOST int[2], may be null) receives flags[0..1], the input checks of
+// the storage builder, read back together with the maximum; when one is set nothing more is built.
+sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st, int *input_flags)
 {
     const sp_encoding *enc = &t->enc;
     const int rank = enc->rank;
-    if (enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1) {
+    const bool want_max = enc->lt[rank - 1] == SP_COMPRESSED && t->npos[rank - 1] > 1;
+    if (want_max) {
         unsigned long long *mx = (unsigned long long *)(flags + 4);
         const int64_t nseg = t->npos[rank - 1] - 1;
         const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
@@ -702,10 +704,19 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
         else
             hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
         SP_HIP(hipGetLastError());
-        unsigned long long hmx = 0;
-        SP_HIP(hipMemcpyAsync(&hmx, mx, 8, hipMemcpyDeviceToHost, st));
+    }
+    if (want_max || input_flags) {
+        int h[6] = {0, 0, 0, 0, 0, 0};
+        SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
         SP_HIP(hipStreamSynchronize(st));
-        t->max_segment = (int64_t)hmx;
+        if (input_flags) {
+            input_flags[0] = h[0];
+            input_flags[1] = h[1];
+            if (h[0] || h[1]) return SP_OK;
+        }
+        unsigned long long hmx = 0;
+        memcpy(&hmx, &h[4], 8);
+        if (want_max) t->max_segment = (int64_t)hmx;
     }
     SP_TRY(spmi_build_rowblocks(t, st));
     SP_TRY(build_nonempty_rows(t, tmp, st));
@@ -758,11 +769,15 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
             SP_HIP(hipGetLastError());
         }
     }
-    int hflags[2] = {0, 0};
-    SP_HIP(hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
-    SP_HIP(hipStreamSynchronize(st));
-    if (hflags[0]) return SP_ERR_COORD_RANGE;
-    if (hflags[1]) return SP_ERR_DUPLICATE;
+    // The input checks (a coordinate out of range, an entry given twice) come back to the host with the last read-back
+    // of the build, not here: a host synchronisation in the middle costs a tenth of a small pack.  Every kernel below stays
+    // in bounds on such input (bad coordinates were replaced by 0 when the keys were made; equal keys only make equal
+    // writes).  input_error() reads them early where another error would otherwise be reported in their place.
+    auto input_error = [&]() -> sp_status {
+        int h[2] = {0, 0};
+        if (hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return SP_ERR_HIP;
+        return h[0] ? SP_ERR_COORD_RANGE : h[1] ? SP_ERR_DUPLICATE : SP_OK;
+    };
     if (sum_duplicates && nnz > 1) {
         hipLaunchKernelGGL(mark_heads_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, child);
         SP_HIP(hipGetLastError());
@@ -839,7 +854,10 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
                 nchild = (int64_t)last_excl + (last_mark ? 1 : 0);
                 child_excl = child;
             }
-            if (enc->pw_store < 64 && nchild > (((int64_t)1 << (enc->pw_store - 1)) - 1)) return SP_ERR_WIDTH;
+            if (enc->pw_store < 64 && nchild > (((int64_t)1 << (enc->pw_store - 1)) - 1)) {
+                SP_TRY(input_error());
+                return SP_ERR_WIDTH;
+            }
             const size_t pbytes = pad16((size_t)(P + 1) * (enc->pw / 8));
             const size_t cbytes = pad16((size_t)(nchild > 0 ? nchild : 1) * (enc->cw / 8));
             t->pos[l] = mem.get(pbytes);
@@ -912,7 +930,11 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
             SP_HIP(hipGetLastError());
         }
     }
-    return spmi_finish_tensor(t, flags, tmp, st);
+    int hf[2] = {0, 0};
+    SP_TRY(spmi_finish_tensor(t, flags, tmp, st, sum_duplicates ? nullptr : hf));
+    if (hf[0]) return SP_ERR_COORD_RANGE;
+    if (hf[1]) return SP_ERR_DUPLICATE;
+    return SP_OK;
 }
 
 // A new tensor handle with shape, sizes by level and the key width worked out; SP_ERR_TOO_LARGE / SP_ERR_WIDTH as sp_pack documents.

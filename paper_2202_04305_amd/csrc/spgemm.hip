@@ -341,7 +341,7 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                                    (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
-            status = spmi_finish_tensor(t, flags, tmp, st);
+            status = spmi_finish_tensor(t, flags, tmp, st, nullptr);
         } while (0);
         if (status != SP_OK) (void)hipStreamSynchronize(st);
     }

@@ -164,8 +164,9 @@ constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // sto
 // documents; `entries_in_an_empty_dimension` turns into SP_ERR_COORD_RANGE at its place in that order).
 sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
                           bool entries_in_an_empty_dimension, sp_tensor **out, int *key_bits_out);
-// The derived tables of a finished storage (see pack.hip); flags: 64 zeroed device bytes.
-sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st);
+// The derived tables of a finished storage (see pack.hip); flags: 64 device bytes, the second half zero; input_flags: HOST
+// int[2] that receives flags[0..1] (nothing more is built when one is set), or null.
+sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st, int *input_flags);
 // Hands the tensor out on SP_OK, releases everything it holds otherwise.
 sp_status spmi_finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out);
 
