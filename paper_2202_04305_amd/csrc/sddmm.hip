@@ -35,6 +35,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const VT *__restrict__ B
 // the row holding every T-th entry are the stream SpMV's), its waves take the rows that meet that window in turn
 // and each handles the part of its row inside the window.  A row of 20,000 entries is thus spread over 20 blocks
 // instead of being walked by one wave; no results need combining because every entry has its own output.
+// The window's values of S and, instead of its coordinates, the byte offsets of the rows of the transposed B that they
+// select (32 bits: the dispatch checks that the matrix is below 4 GB) are first copied into LDS with coalesced loads, so
+// that the loop over the entries does its index arithmetic on small window-relative integers and every gather address
+// is a wave-uniform base plus a 32-bit lane offset.
 template <typename PT, typename CT, typename VT, int LR>
 __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
                                                                      const VT *__restrict__ sval, const CT *__restrict__ rowid,
@@ -45,31 +49,46 @@ __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *_
     constexpr int V = 16 / sizeof(VT);
     constexpr int S = 64 / LR;
     constexpr int U = S >= 4 ? 2 : 4;
+    constexpr int T = (int)kSpmiStreamT;
     typedef VT vec_t __attribute__((ext_vector_type(V)));
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ uint32_t s_off[T];
+    __shared__ VT s_val[T];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int jl = lane % LR, sl = lane / LR;
-    const int64_t s = (int64_t)blockIdx.x * kSpmiStreamT;
-    const int64_t e = s + kSpmiStreamT < nnz ? s + kSpmiStreamT : nnz;
+    const int64_t s = (int64_t)blockIdx.x * T;
+    const int64_t e = s + T < nnz ? s + T : nnz;
+    const int ne = (int)(e - s);
+    const uint32_t brow = (uint32_t)(ldt * (int64_t)sizeof(VT));
+    for (int i = threadIdx.x; i < ne; i += kThreads) {
+        s_off[i] = (uint32_t)crd[s + i] * brow;
+        s_val[i] = sval[s + i];
+    }
     const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
     const int64_t last = hi < nrows ? hi : nrows - 1;
+    __syncthreads();
+    const char *Bb = (const char *)Bt;
+    const uint32_t colb = (uint32_t)(jl * V * (int)sizeof(VT));
+    VT *Xw = X + s;                                   // this window's part of the result
+    int slot[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot[u] = sl + u * S;
     for (int64_t r = lo + wave; r <= last; r += kThreads / 64) {
         const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
-        const int64_t a = pa > s ? pa : s, b = pb < e ? pb : e;
+        const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
         if (b <= a) continue;                         // wave-uniform
         const int64_t i = rowid ? (int64_t)rowid[r] : r;
         const vec_t av = *(const vec_t *)(A + i * lda + jl * V);
         // the step count is the same for every lane of the wave, so the shuffles run with all lanes active;
         // entries past the end are clamped and their result dropped
-        const int64_t steps = (b - a + (int64_t)U * S - 1) / ((int64_t)U * S);
-        for (int64_t t = 0; t < steps; ++t) {
-            const int64_t p0 = a + t * U * S + sl;
+        for (int p0 = a; p0 < b; p0 += U * S) {
             vec_t bv[U];
-            int64_t pp[U];
+            int pp[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                pp[u] = p0 + (int64_t)u * S;
-                const int64_t pc = pp[u] < b ? pp[u] : b - 1;
-                bv[u] = *(const vec_t *)(Bt + (int64_t)crd[pc] * ldt + jl * V);
+                pp[u] = p0 + slot[u];
+                const int pc = pp[u] < b ? pp[u] : b - 1;
+                bv[u] = *(const vec_t *)(Bb + (s_off[pc] + colb));
             }
             VT dot[U];
 #pragma unroll
@@ -99,16 +118,16 @@ __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *_
                 for (; m >= 1; m >>= 1) dot[0] += __shfl_xor(dot[0], m, 64);
                 constexpr int G = LR / U > 0 ? LR / U : 1;      // lanes that end with the same sum
                 const int u = jl / G;
-                int64_t mine = pp[0];
+                int mine = pp[0];
 #pragma unroll
                 for (int k = 1; k < U; ++k) mine = u == k ? pp[k] : mine;
-                if (jl % G == 0 && mine < b) X[mine] = sval[mine] * dot[0];
+                if (jl % G == 0 && mine < b) Xw[mine] = s_val[mine] * dot[0];
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
 #pragma unroll
                     for (int d = LR / 2; d >= 1; d >>= 1) dot[u] += __shfl_xor(dot[u], d, 64);
-                    if (jl == 0 && pp[u] < b) X[pp[u]] = sval[pp[u]] * dot[u];
+                    if (jl == 0 && pp[u] < b) Xw[pp[u]] = s_val[pp[u]] * dot[u];
                 }
             }
         }
@@ -177,7 +196,8 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
         sp_prof_scope prof(S, st);
         const int64_t lr = K / V;
         const bool vec = rowblocks->start && K % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && lda % V == 0 &&
-                         ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0;
+                         ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0 &&
+                         (uint64_t)n * (uint64_t)ldt * sizeof(VT) < ((uint64_t)1 << 32);      // 32-bit byte offsets into the transposed B
         const dim3 grid(grid_for(nrows, kThreads / 64));
         if (vec) {
 #define SPMI_SDDMM_VEC(LR)                                                                                                    \
