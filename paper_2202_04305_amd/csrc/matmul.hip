@@ -320,7 +320,10 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_vec_kernel(const PT *__res
 // owns the entries [w*T, (w+1)*T) with T and `rowblk` as in the stream SpMV, its four waves take the rows that meet
 // the window in turn.  The part of a row that began in an earlier window goes to carry[w] (N values) and the fix-up
 // kernel below adds the carries to C in block order; everything else is written to C directly.  No atomics.
-template <typename PT, typename CT, typename VT, int LR>
+// The window's values and, instead of its coordinates, the byte offsets of the rows of B that they select (OT: 32 bits
+// when B is below 4 GB) are first copied into LDS with coalesced loads: the loop over the entries then works on small
+// window-relative integers and every gather address is a wave-uniform base plus a lane offset.
+template <typename PT, typename CT, typename VT, int LR, typename OT>
 __global__ __launch_bounds__(kThreads) void spmm_windows_vec_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
                                                                     const VT *__restrict__ val, const CT *__restrict__ rowid,
                                                                     const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
@@ -331,32 +334,45 @@ __global__ __launch_bounds__(kThreads) void spmm_windows_vec_kernel(const PT *__
     constexpr int S = 64 / LR;
     constexpr int U = S >= 4 ? 2 : 4;
     typedef VT vec_t __attribute__((ext_vector_type(V)));
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ OT s_off[kStreamT];
+    __shared__ VT s_val[kStreamT];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int jl = lane % LR, sl = lane / LR;
     const int64_t s = (int64_t)blockIdx.x * kStreamT;
     const int64_t e = s + kStreamT < nnz ? s + kStreamT : nnz;
+    const int ne = (int)(e - s);
+    const OT brow = (OT)(ldb * (int64_t)sizeof(VT));
+    for (int i = threadIdx.x; i < ne; i += kThreads) {
+        s_off[i] = (OT)crd[s + i] * brow;
+        s_val[i] = val[s + i];
+    }
     const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
     const int64_t last = hi < nrows ? hi : nrows - 1;
+    __syncthreads();
+    const char *Bb = (const char *)B;
+    const OT colb = (OT)(jl * V * (int)sizeof(VT));
+    int slot[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot[u] = sl + u * S;
     for (int64_t r = lo + wave; r <= last; r += kThreads / 64) {
         const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
-        const int64_t a = pa > s ? pa : s, b = pb < e ? pb : e;
+        const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
         if (r == hi && b <= a) continue;              // row hi starts at the next window: not ours (wave-uniform)
         vec_t accu[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) accu[u] = (vec_t)(0);
-        for (int64_t p = a + sl; p - sl < b; p += (int64_t)U * S) {      // p - sl is wave-uniform
-            int64_t k[U];
+        for (int p0 = a; p0 < b; p0 += U * S) {       // wave-uniform
             VT v[U];
             vec_t bv[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t pp = p + (int64_t)u * S;
+                const int pp = p0 + slot[u];
                 const bool in = pp < b;
-                k[u] = (int64_t)crd[in ? pp : a];
-                v[u] = in ? val[pp] : (VT)0;
+                const int idx = in ? pp : a;
+                v[u] = in ? s_val[idx] : (VT)0;
+                bv[u] = *(const vec_t *)(Bb + (s_off[idx] + colb));
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) bv[u] = *(const vec_t *)(B + k[u] * ldb + jl * V);
 #pragma unroll
             for (int u = 0; u < U; ++u) accu[u] += v[u] * bv[u];
         }
@@ -654,9 +670,15 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
                 if (!At->spmm_carry) return SP_ERR_ALLOC;
                 At->spmm_carry_bytes = need;
             }
-#define SPMI_SPMM_WIN(LR)                                                                                                     \
-    hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,        \
+            const bool small = (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B
+#define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
+    hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,    \
                        (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)A->spmm_carry, accumulate)
+#define SPMI_SPMM_WIN(LR)                           \
+    do {                                            \
+        if (small) SPMI_SPMM_WIN_O(LR, uint32_t);   \
+        else SPMI_SPMM_WIN_O(LR, uint64_t);         \
+    } while (0)
             if (lr == 1) SPMI_SPMM_WIN(1);
             else if (lr == 2) SPMI_SPMM_WIN(2);
             else if (lr == 4) SPMI_SPMM_WIN(4);
@@ -665,6 +687,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             else if (lr == 32) SPMI_SPMM_WIN(32);
             else SPMI_SPMM_WIN(64);
 #undef SPMI_SPMM_WIN
+#undef SPMI_SPMM_WIN_O
             SP_HIP(hipGetLastError());
             if (nb > 1) {
                 hipLaunchKernelGGL((spmm_windows_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads / 64)), dim3(kThreads), 0, st, pos,

@@ -36,10 +36,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const VT *__restrict__ B
 // and each handles the part of its row inside the window.  A row of 20,000 entries is thus spread over 20 blocks
 // instead of being walked by one wave; no results need combining because every entry has its own output.
 // The window's values of S and, instead of its coordinates, the byte offsets of the rows of the transposed B that they
-// select (32 bits: the dispatch checks that the matrix is below 4 GB) are first copied into LDS with coalesced loads, so
+// select are first copied into LDS with coalesced loads, so
 // that the loop over the entries does its index arithmetic on small window-relative integers and every gather address
-// is a wave-uniform base plus a 32-bit lane offset.
-template <typename PT, typename CT, typename VT, int LR>
+// is a wave-uniform base plus a lane offset (OT: 32 bits when the matrix is below 4 GB).
+template <typename PT, typename CT, typename VT, int LR, typename OT>
 __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *__restrict__ pos, const CT *__restrict__ crd,
                                                                      const VT *__restrict__ sval, const CT *__restrict__ rowid,
                                                                      const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *_
     constexpr int U = S >= 4 ? 2 : 4;
     constexpr int T = (int)kSpmiStreamT;
     typedef VT vec_t __attribute__((ext_vector_type(V)));
-    __shared__ uint32_t s_off[T];
+    __shared__ OT s_off[T];
     __shared__ VT s_val[T];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -59,16 +59,16 @@ __global__ __launch_bounds__(kThreads) void sddmm_windows_vec_kernel(const PT *_
     const int64_t s = (int64_t)blockIdx.x * T;
     const int64_t e = s + T < nnz ? s + T : nnz;
     const int ne = (int)(e - s);
-    const uint32_t brow = (uint32_t)(ldt * (int64_t)sizeof(VT));
+    const OT brow = (OT)(ldt * (int64_t)sizeof(VT));
     for (int i = threadIdx.x; i < ne; i += kThreads) {
-        s_off[i] = (uint32_t)crd[s + i] * brow;
+        s_off[i] = (OT)crd[s + i] * brow;
         s_val[i] = sval[s + i];
     }
     const int64_t lo = rowblk[blockIdx.x], hi = rowblk[blockIdx.x + 1];
     const int64_t last = hi < nrows ? hi : nrows - 1;
     __syncthreads();
     const char *Bb = (const char *)Bt;
-    const uint32_t colb = (uint32_t)(jl * V * (int)sizeof(VT));
+    const OT colb = (OT)(jl * V * (int)sizeof(VT));
     VT *Xw = X + s;                                   // this window's part of the result
     int slot[U];
 #pragma unroll
@@ -196,13 +196,18 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
         sp_prof_scope prof(S, st);
         const int64_t lr = K / V;
         const bool vec = rowblocks->start && K % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && lda % V == 0 &&
-                         ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0 &&
-                         (uint64_t)n * (uint64_t)ldt * sizeof(VT) < ((uint64_t)1 << 32);      // 32-bit byte offsets into the transposed B
+                         ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0;
+        const bool small = (uint64_t)n * (uint64_t)ldt * sizeof(VT) < ((uint64_t)1 << 32);      // 32-bit byte offsets into the transposed B
         const dim3 grid(grid_for(nrows, kThreads / 64));
         if (vec) {
-#define SPMI_SDDMM_VEC(LR)                                                                                                    \
-    hipLaunchKernelGGL((sddmm_windows_vec_kernel<PT, CT, VT, LR>), dim3((unsigned)rowblocks->nblocks), dim3(kThreads), 0, st, pos, crd, \
+#define SPMI_SDDMM_VEC_O(LR, OT)                                                                                              \
+    hipLaunchKernelGGL((sddmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)rowblocks->nblocks), dim3(kThreads), 0, st, pos, crd, \
                        sval, rowid, (const int32_t *)rowblocks->start, nrows, S->ncrd[1], A, lda, Bt, ldt, X)
+#define SPMI_SDDMM_VEC(LR)                              \
+    do {                                                \
+        if (small) SPMI_SDDMM_VEC_O(LR, uint32_t);      \
+        else SPMI_SDDMM_VEC_O(LR, uint64_t);            \
+    } while (0)
             if (lr == 1) SPMI_SDDMM_VEC(1);
             else if (lr == 2) SPMI_SDDMM_VEC(2);
             else if (lr == 4) SPMI_SDDMM_VEC(4);
@@ -211,6 +216,7 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
             else if (lr == 32) SPMI_SDDMM_VEC(32);
             else SPMI_SDDMM_VEC(64);
 #undef SPMI_SDDMM_VEC
+#undef SPMI_SDDMM_VEC_O
         } else {
 #define SPMI_SDDMM(CG)                                                                                                        \
     hipLaunchKernelGGL((sddmm_rows_kernel<PT, CT, VT, CG>), grid, dim3(kThreads), 0, st, pos, crd, sval, rowid, nrows, A, lda, Bt, ldt, \
