@@ -174,7 +174,9 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *   SP_TUNE_SPGEMM_KERNEL (set on the left operand of sp_spgemm): 0 = automatic, 1 = pairs expanded, sorted and added
  *                        up by the storage builder (any sizes and encodings), 2 = a row of C at a time in an LDS
  *                        workspace (CSR / DCSR operands and a CSR result with one pos / crd width, rows of C that
- *                        fit the LDS; SP_ERR_UNSUPPORTED otherwise)
+ *                        fit the LDS; SP_ERR_UNSUPPORTED otherwise), four waves per row over a column-panel copy
+ *                        of B that B builds on first use and keeps, 3 = the same workspace with one wave per row
+ *                        and no copy of B
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
 enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4, SP_TUNE_SPGEMM_KERNEL = 5 };
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);

@@ -286,6 +286,131 @@ __global__ __launch_bounds__(64) void spgemm_ws_numeric_kernel(const PT *__restr
     }
 }
 
+// The same with four waves per row of A.  B is read from a copy cut into (at most) four column panels of 2^shift columns
+// (a CSR over the virtual rows panel * kdim + k, built once per B and kept): wave w takes panel w, i.e. the columns
+// [w << shift, (w + 1) << shift) of every row of B that the row of A selects.  The waves share one workspace but never
+// an element of it, so no two waves ever add to the same value and the order of the additions to an element is still
+// fixed by the structure.  Chunks are 32 entries, two per instruction (one per half-wave); each wave compresses its
+// own columns.
+constexpr int kPanelWaves = 4, kHalfChunk = 32, kPanelList = 64;
+template <typename VT>
+struct panel_lists {
+    int64_t start[kPanelWaves][kPanelList];
+    int32_t len[kPanelWaves][kPanelList];
+    VT a[kPanelWaves][kPanelList];
+};
+
+template <typename PT, typename CT, typename VT, int U>
+__global__ __launch_bounds__(64 * kPanelWaves) void spgemm_ws_numeric_panels_kernel(
+    const PT *__restrict__ apos, const CT *__restrict__ acrd, const VT *__restrict__ aval, const CT *__restrict__ arowid,
+    const PT *__restrict__ spos, const CT *__restrict__ scrd, const VT *__restrict__ sval, int64_t kdim, int shift, int64_t n,
+    const PT *__restrict__ cpos, CT *__restrict__ ccrd, VT *__restrict__ cval)
+{
+    extern __shared__ unsigned char ws_raw[];
+    __shared__ panel_lists<VT> lists;
+    VT *acc = (VT *)ws_raw;
+    uint32_t *bits = (uint32_t *)(ws_raw + (size_t)n * sizeof(VT));
+    const int lane = threadIdx.x & 63, half = lane >> 5, hl = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t r = blockIdx.x;
+    const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
+    if (a1 == a0) return;                                          // the whole block
+    const int64_t words = (n + 31) >> 5;
+    for (int64_t j = threadIdx.x; j < n; j += 64 * kPanelWaves) acc[j] = (VT)0;
+    for (int64_t w = threadIdx.x; w < words; w += 64 * kPanelWaves) bits[w] = 0u;
+    __syncthreads();
+    const int64_t col_lo = (int64_t)wave << shift;                 // this wave's columns: [col_lo, col_hi)
+    const int64_t col_hi = col_lo + ((int64_t)1 << shift) < n ? col_lo + ((int64_t)1 << shift) : n;
+    if (col_lo < n) {
+        const PT *wpos = spos + (int64_t)wave * kdim;              // the pos entries of this wave's panel
+        for (int64_t g = a0; g < a1; g += 64) {
+            const int64_t e = g + lane;
+            int64_t b0 = 0, b1 = 0;
+            VT a = (VT)0;
+            if (e < a1) {
+                const int64_t k = (int64_t)acrd[e];
+                a = aval[e];
+                b0 = (int64_t)wpos[k];
+                b1 = (int64_t)wpos[k + 1];
+            }
+            const int mine = (int)((b1 - b0 + kHalfChunk - 1) / kHalfChunk);
+            int before = mine;                                     // inclusive scan over the lanes
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(before, d, 64);
+                if (lane >= d) before += up;
+            }
+            const int total = __shfl(before, 63, 64);
+            before -= mine;
+            for (int w0 = 0; w0 < total; w0 += kPanelList) {       // wave-uniform: a window of the chunk numbering
+                for (int c = 0; c < mine; ++c) {
+                    const int id = before + c - w0;
+                    if (id >= 0 && id < kPanelList) {
+                        const int64_t st = b0 + (int64_t)c * kHalfChunk;
+                        lists.start[wave][id] = st;
+                        lists.len[wave][id] = (int32_t)(b1 - st < kHalfChunk ? b1 - st : kHalfChunk);
+                        lists.a[wave][id] = a;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int here = total - w0 < kPanelList ? total - w0 : kPanelList;
+                for (int d0 = 0; d0 < here; d0 += 2 * U) {
+                    uint32_t j[U];
+                    VT p[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        j[u] = 0xffffffffu;
+                        p[u] = (VT)0;
+                        const int d = d0 + 2 * u + half;           // one descriptor per half-wave
+                        if (d0 + 2 * u < here) {                   // wave-uniform
+                            if (d < here && hl < lists.len[wave][d]) {
+                                const int64_t t = lists.start[wave][d] + hl;
+                                j[u] = (uint32_t)scrd[t];
+                                p[u] = lists.a[wave][d] * sval[t];
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        if (d0 + 2 * u < here && j[u] != 0xffffffffu) {
+                            atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
+                            atomicAdd(&acc[j[u]], p[u]);
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+    }
+    __syncthreads();
+    if (col_lo >= n) return;
+    // the compress step for this wave's columns; its first output follows the set bits of the columns before
+    int before_cols = 0;
+    for (int64_t w = lane; w < (col_lo >> 5); w += 64) before_cols += __popc(bits[w]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) before_cols += __shfl_xor(before_cols, d, 64);
+    const int64_t row_at = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r] + before_cols;
+    CT *crow = ccrd + row_at;
+    VT *vrow = cval + row_at;
+    uint32_t base = 0;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (uint32_t j0 = (uint32_t)col_lo; j0 < (uint32_t)col_hi; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        const bool set = j < (uint32_t)col_hi && ((bits[j >> 5] >> (j & 31)) & 1u);
+        const unsigned long long mask = __ballot(set);
+        if (set) {
+            const uint32_t o = base + (uint32_t)__popcll(mask & below);
+            crow[o] = (CT)j;
+            vrow[o] = acc[j];
+        }
+        base += (uint32_t)__popcll(mask);
+    }
+}
+
 template <typename PT, typename CT, typename VT>
 sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *encC, hipStream_t st, sp_tensor **out)
 {
@@ -330,7 +455,26 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             t->nvalues = nnzc;
             t->nnz = nnzc;
             if (!t->crd[1] || !t->values) { status = SP_ERR_ALLOC; break; }
-            if (work && nnzc > 0) {
+            // four waves per row when the column-panel copy of B can be had (it is built on the first product with this B)
+            const sp_tensor *Bseg = nullptr;
+            int pshift = 0;
+            if (work && nnzc > 0 && A->tune_spgemm != 3 && n >= 4 * 64) {
+                while (((int64_t)kPanelWaves << pshift) < n) ++pshift;      // the narrowest power of two with at most four panels
+                sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(Br), 1, (int64_t)1 << pshift, st);
+                if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= kPanelWaves) Bseg = Br->segments->seg;
+                else if (sb != SP_OK && sb != SP_ERR_UNSUPPORTED) { status = sb; break; }
+            }
+            if (Bseg) {
+                auto kernel = spgemm_ws_numeric_panels_kernel<PT, CT, VT, 8>;
+                if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
+                    status = SP_ERR_HIP;
+                    break;
+                }
+                hipLaunchKernelGGL(kernel, dim3((unsigned)arows), dim3(64 * kPanelWaves), ws_bytes, st, (const PT *)A->pos[1], (const CT *)A->crd[1],
+                                   (const VT *)A->values, arowid, (const PT *)Bseg->pos[1], (const CT *)Bseg->crd[1], (const VT *)Bseg->values,
+                                   Br->shape[0], pshift, n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            } else if (work && nnzc > 0) {
                 auto kernel = spgemm_ws_numeric_kernel<PT, CT, VT, 32>;
                 if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
                     status = SP_ERR_HIP;
@@ -381,7 +525,7 @@ extern "C" sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_
     }
     const int pw = Br->enc.pw, cw = Br->enc.cw;
     const bool fits = workspace_fits(A, Br, encC);
-    if (A->tune_spgemm == 2 && !fits) return SP_ERR_UNSUPPORTED;
+    if ((A->tune_spgemm == 2 || A->tune_spgemm == 3) && !fits) return SP_ERR_UNSUPPORTED;
     if (fits && A->tune_spgemm != 1) {
 #define SPMI_WS(PT, CT)                                                                                        \
     return A->dtype == SP_F64 ? spgemm_workspace_t<PT, CT, double>(A, Br, encC, st, C) : spgemm_workspace_t<PT, CT, float>(A, Br, encC, st, C)

@@ -103,8 +103,8 @@ def test_spgemm_exact_integers_kept_zeros_and_chained_product():
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("fa", ["csr", "dcsr"])
 def test_spgemm_both_kernels(dtype, fa):
-    """Kernel 1 (pairs through the storage builder) and kernel 2 (a row of C at a time in an LDS workspace) against the
-    checker and each other's pattern; widths 32 and 64; rows of A from empty to hundreds of entries, rows of B longer
+    """Kernel 1 (pairs through the storage builder), kernel 2 (a row of C at a time in an LDS workspace, four waves per row
+    over a column-panel copy of B) and kernel 3 (the same with one wave per row) against the checker; widths 32 and 64; rows of A from empty to hundreds of entries, rows of B longer
     than a wave."""
     a = W.cfg2_powerlaw_csr(2500, 1800, mean=8.0, cap=700)
     b = W.cfg2_powerlaw_csr(1800, 9000, mean=40.0, cap=3000, seed=W.BASE_SEED + 34)      # 9000 columns: near the LDS limit in f64
@@ -114,7 +114,7 @@ def test_spgemm_both_kernels(dtype, fa):
         A = gpu_pack(*ENC[fa], a.shape, [a.rows, a.cols], va, pw, cw)
         B = gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], vb, pw, cw)
         enc = sp.sp_encode(*ENC["csr"], pw, cw)
-        for kernel in (1, 2, 0):
+        for kernel in (1, 2, 3, 0):
             say("case spgemm kernels", dtype.__name__, fa, pw, "kernel", kernel, len(ref[0]))
             sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, kernel)
             C = sp.sp_spgemm(A, B, enc)
@@ -142,10 +142,19 @@ def test_spgemm_workspace_kernel_limits_and_exact_integers():
     va, vb = prng.small_ints(7, 1, a.nnz), prng.small_ints(7, 2, b.nnz)
     ref = oracle.spgemm_coo(a.shape, a.rows, a.cols, va, b.shape, b.rows, b.cols, vb)
     for fa in ("csr", "dcsr"):
-        A = gpu_pack(*ENC[fa], a.shape, [a.rows, a.cols], va)
+        for kernel in (2, 3):
+            A = gpu_pack(*ENC[fa], a.shape, [a.rows, a.cols], va)
+            sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, kernel)
+            C = sp.sp_spgemm(A, gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], vb), sp.sp_encode(*ENC["csr"], 32, 32))
+            check(C, "csr", (400, 350), ref, np.float64, exact=True)
+    # widths that are no multiple of the panel width, and fewer columns than four panels of 64
+    for n in (257, 300, 1000, 130):
+        a, b = pair(200, 150, n, 2500, 3000, seed=n)
+        ref = oracle.spgemm_coo(a.shape, a.rows, a.cols, a.vals, b.shape, b.rows, b.cols, b.vals)
+        A = gpu_pack(*ENC["csr"], a.shape, [a.rows, a.cols], a.vals)
+        B = gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], b.vals)
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPGEMM_KERNEL, 2)
-        C = sp.sp_spgemm(A, gpu_pack(*ENC["csr"], b.shape, [b.rows, b.cols], vb), sp.sp_encode(*ENC["csr"], 32, 32))
-        check(C, "csr", (400, 350), ref, np.float64, exact=True)
+        check(sp.sp_spgemm(A, B, sp.sp_encode(*ENC["csr"], 32, 32)), "csr", (200, n), ref, np.float64)
 
 
 def test_spgemm_degenerate_and_errors():
