@@ -225,6 +225,7 @@ extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int
     if (N == 0 || m == 0) return SP_OK;
     if (!C || (!B && n > 0)) return SP_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
+    SP_TRY(spmi_ensure_tables(A, st));
     if (A->enc.lt[1] != SP_COMPRESSED) return spmi_matmul_dense_inner(A, B, N, ldb, C, ldc, accumulate, st);
     if (A->enc.perm[0] == 0) return spmi_matmul_rowmajor(A, B, N, ldb, C, ldc, accumulate, st);
     int mode = A->tune_csc ? A->tune_csc : 2;

@@ -724,6 +724,30 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
     return SP_OK;
 }
 
+// *out (DEVICE, zero before the call) = the longest of the nseg segments of a pos array of width pw; enqueued only.
+sp_status spmi_max_segment_async(const void *pos, int pw, int64_t nseg, unsigned long long *out, hipStream_t st)
+{
+    if (nseg <= 0) return SP_OK;
+    const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
+    if (pw == 32) hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)pos, nseg, out);
+    else hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)pos, nseg, out);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+sp_status spmi_ensure_tables(const sp_tensor *ct, hipStream_t st)
+{
+    if (!ct->tables_pending) return SP_OK;
+    sp_tensor *t = const_cast<sp_tensor *>(ct);
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    sp_scratch tmp(mem);
+    SP_TRY(spmi_build_rowblocks(t, st));
+    SP_TRY(build_nonempty_rows(t, tmp, st));
+    SP_HIP(hipStreamSynchronize(st));
+    t->tables_pending = 0;
+    return SP_OK;
+}
+
 // Everything after the keys exist: sort, duplicates (an error, or summed in sorted order when `sum_duplicates`), the
 // level sweep, narrow copies, values, and the tables the product kernels want.  keys / payload: nnz entries in
 // temporaries of `tmp` (the payload is the value's bits); flags: 64 zeroed bytes, flags[0] != 0 afterwards on the

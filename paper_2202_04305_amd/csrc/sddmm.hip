@@ -247,6 +247,7 @@ extern "C" sp_status sp_sddmm(const sp_tensor *S, const void *A, int64_t lda, co
     if (S->nvalues > 0 && (!X || (K > 0 && (!A || !B)))) return SP_ERR_NULL;
     if (S->enc.perm[0] != 0 || S->enc.lt[1] != SP_COMPRESSED) return SP_ERR_UNSUPPORTED;   // row-major with a compressed inner level
     hipStream_t st = (hipStream_t)stream;
+    SP_TRY(spmi_ensure_tables(S, st));
     const int pw = S->enc.pw, cw = S->enc.cw;
 #define SPMI_GO(PT, CT)                                                                                                       \
     return S->dtype == SP_F64 ? sddmm_t<PT, CT, double>(S, (const double *)A, lda, (const double *)B, ldb, b_is_transposed, K, (double *)X, st) \

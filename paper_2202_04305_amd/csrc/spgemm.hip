@@ -444,9 +444,14 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
             if ((status = spmi_exclusive_scan(t->pos[1], m + 1, (int)sizeof(PT) * 8, tmp, st)) != SP_OK) break;
+            // the longest row of C (the products choose kernels by it) comes back with the total, in one synchronisation
+            if ((status = spmi_max_segment_async(t->pos[1], (int)sizeof(PT) * 8, m, (unsigned long long *)(flags + 4), st)) != SP_OK) break;
             PT total = 0;
+            unsigned long long longest = 0;
             if (hipMemcpyAsync(&total, (const PT *)t->pos[1] + m, sizeof(PT), hipMemcpyDeviceToHost, st) != hipSuccess ||
+                hipMemcpyAsync(&longest, flags + 4, 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
                 hipStreamSynchronize(st) != hipSuccess) { status = SP_ERR_HIP; break; }
+            t->max_segment = (int64_t)longest;
             const int64_t nnzc = (int64_t)total;
             if (nnzc < 0 || nnzc >= ((int64_t)1 << 31)) { status = SP_ERR_TOO_LARGE; break; }     // a 32-bit pos that wrapped shows as negative
             t->crd[1] = mem.get((((size_t)(nnzc > 0 ? nnzc : 1) * sizeof(CT)) + 15) & ~(size_t)15);
@@ -485,7 +490,10 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                                    (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
-            status = spmi_finish_tensor(t, flags, tmp, st, nullptr);
+            // the tables that only sp_matmul and sp_sddmm read (row blocks, non-empty rows) are built when one of them first
+            // takes this tensor: a result that goes into another sparse product never needs them
+            t->tables_pending = 1;
+            if (hipStreamSynchronize(st) != hipSuccess) { status = SP_ERR_HIP; break; }
         } while (0);
         if (status != SP_OK) (void)hipStreamSynchronize(st);
     }

@@ -69,6 +69,7 @@ struct sp_tensor {
     size_t mttkrp_carry_bytes;
     void *mttkrp_pad[2];             // DEVICE scratch of the MTTKRP: inner / mid factor matrix with rows padded to whole cache lines
     size_t mttkrp_pad_bytes[2];
+    int tables_pending;              // rowblocks / non-empty rows not built yet (a result of sp_spgemm): built on first use by a product
     int tune_spmv, tune_csc, tune_spmm, tune_spgemm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
@@ -167,6 +168,10 @@ sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype
 // The derived tables of a finished storage (see pack.hip); flags: 64 device bytes, the second half zero; input_flags: HOST
 // int[2] that receives flags[0..1] (nothing more is built when one is set), or null.
 sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStream_t st, int *input_flags);
+// *out (DEVICE, zero before the call) = the longest of the nseg segments of a pos array of width pw; enqueued only.
+sp_status spmi_max_segment_async(const void *pos, int pw, int64_t nseg, unsigned long long *out, hipStream_t st);
+// Builds the tables a product kernel reads (row blocks, non-empty rows) when the tensor still lacks them; synchronises then.
+sp_status spmi_ensure_tables(const sp_tensor *t, hipStream_t st);
 // Hands the tensor out on SP_OK, releases everything it holds otherwise.
 sp_status spmi_finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_tensor **out);
 
