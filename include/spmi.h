@@ -169,7 +169,8 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *                        3 = streaming over a column-segmented copy (built and kept on first use; CSR only)
  *   SP_TUNE_SPMM_KERNEL: 0 = automatic, 1 = one column per lane, 2 = 16 bytes of a row of B per lane, a wave per row,
  *                        3 = the same cut by stored entries instead of rows (2 and 3 need N a multiple
- *                        of 16 / element size with 1, 2, 4, ... 64 such vectors per row, and B, C rows 16-byte aligned)
+ *                        of 16 / element size and B, C rows 16-byte aligned; 2 takes 1, 2, 4, ... 64 such vectors
+ *                        per row, 3 any number up to 64)
  *   SP_TUNE_CSC_MODE:    0 = automatic, 1 = scatter with atomics, 2 = via a cached transpose
  *   SP_TUNE_SPGEMM_KERNEL (set on the left operand of sp_spgemm): 0 = automatic, 1 = pairs expanded, sorted and added
  *                        up by the storage builder (any sizes and encodings), 2 = a row of C at a time in an LDS

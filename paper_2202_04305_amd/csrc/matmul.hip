@@ -328,17 +328,18 @@ __global__ __launch_bounds__(kThreads) void spmm_windows_vec_kernel(const PT *__
                                                                     const VT *__restrict__ val, const CT *__restrict__ rowid,
                                                                     const int32_t *__restrict__ rowblk, int64_t nrows, int64_t nnz,
                                                                     const VT *__restrict__ B, int64_t ldb, VT *__restrict__ C, int64_t ldc,
-                                                                    VT *__restrict__ carry, int accumulate)
+                                                                    VT *__restrict__ carry, int accumulate, int lr_any)
 {
     constexpr int V = 16 / sizeof(VT);
-    constexpr int S = 64 / LR;
-    constexpr int U = S >= 4 ? 2 : 4;
+    const int LRv = LR > 0 ? LR : lr_any;             // LR = 0: any number of lanes per row of B, known at run time
+    const int S = 64 / LRv;
+    constexpr int U = (LR > 0 && 64 / (LR > 0 ? LR : 1) >= 4) ? 2 : 4;
     typedef VT vec_t __attribute__((ext_vector_type(V)));
     __shared__ OT s_off[kStreamT];
     __shared__ VT s_val[kStreamT];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int jl = lane % LR, sl = lane / LR;
+    const int jl = lane % LRv, sl = lane / LRv;
     const int64_t s = (int64_t)blockIdx.x * kStreamT;
     const int64_t e = s + kStreamT < nnz ? s + kStreamT : nnz;
     const int ne = (int)(e - s);
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void spmm_windows_vec_kernel(const PT *__
     const OT colb = (OT)(jl * V * (int)sizeof(VT));
     int slot[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) slot[u] = sl + u * S;
+    for (int u = 0; u < U; ++u) slot[u] = sl < S ? sl + u * S : (1 << 24);      // lanes beyond LR * S never take an entry
     for (int64_t r = lo + wave; r <= last; r += kThreads / 64) {
         const int64_t pa = (int64_t)pos[r], pb = (int64_t)pos[r + 1];
         const int a = (int)((pa > s ? pa : s) - s), b = (int)((pb < e ? pb : e) - s);
@@ -379,15 +380,23 @@ __global__ __launch_bounds__(kThreads) void spmm_windows_vec_kernel(const PT *__
         vec_t acc0 = accu[0];
 #pragma unroll
         for (int u = 1; u < U; ++u) acc0 += accu[u];
+        if (LR > 0) {
 #pragma unroll
-        for (int ee = 0; ee < V; ++ee) {
-            VT x = acc0[ee];
+            for (int ee = 0; ee < V; ++ee) {
+                VT x = acc0[ee];
 #pragma unroll
-            for (int d = 32; d >= LR; d >>= 1) x += __shfl_xor(x, d, 64);
-            acc0[ee] = x;
+                for (int d = 32; d >= (LR > 0 ? LR : 64); d >>= 1) x += __shfl_xor(x, d, 64);
+                acc0[ee] = x;
+            }
+        } else {                                      // the S groups' sums meet in group 0
+            const vec_t mine = acc0;
+            for (int g = 1; g < S; ++g) {
+#pragma unroll
+                for (int ee = 0; ee < V; ++ee) acc0[ee] += __shfl(mine[ee], jl + g * LRv, 64);
+            }
         }
         if (sl == 0) {
-            if (pa < s) *(vec_t *)(carry + (int64_t)blockIdx.x * LR * V + jl * V) = acc0;
+            if (pa < s) *(vec_t *)(carry + (int64_t)blockIdx.x * LRv * V + jl * V) = acc0;
             else {
                 const int64_t row = rowid ? (int64_t)rowid[r] : r;
                 vec_t *dst = (vec_t *)(C + row * ldc + jl * V);
@@ -652,14 +661,15 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
     {
         constexpr int64_t V = 16 / sizeof(VT);
         const int64_t lr = N / V;
-        const bool fits = N % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && ldb % V == 0 && ldc % V == 0 &&
-                          (uintptr_t)B % 16 == 0 && (uintptr_t)C % 16 == 0;
-        if ((A->tune_spmm == 2 || A->tune_spmm == 3) && !fits) return SP_ERR_UNSUPPORTED;
-        if (A->tune_spmm == 3 && !rowblocks->start) return SP_ERR_UNSUPPORTED;
+        const bool aligned = N % V == 0 && ldb % V == 0 && ldc % V == 0 && (uintptr_t)B % 16 == 0 && (uintptr_t)C % 16 == 0;
+        const bool fits = aligned && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64);    // a wave per row
+        const bool fits_any = aligned && lr >= 1 && lr <= 64;                                                           // cut by entries
+        if (A->tune_spmm == 2 && !fits) return SP_ERR_UNSUPPORTED;
+        if (A->tune_spmm == 3 && (!fits_any || !rowblocks->start)) return SP_ERR_UNSUPPORTED;
         // measured faster than a wave per row on every workload tried (1.42 vs 1.57 ms, 0.68 vs 0.83 ms), and a very long
         // row no longer sets the run time: the default
         const bool by_entries = A->tune_spmm == 3 || (A->tune_spmm == 0 && rowblocks->start);
-        if (fits && by_entries) {
+        if (fits_any && by_entries) {
             const int64_t nb = rowblocks->nblocks;
             sp_tensor *At = const_cast<sp_tensor *>(A);
             const size_t need = (size_t)nb * N * sizeof(VT);
@@ -673,7 +683,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             const bool small = (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B
 #define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
     hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,    \
-                       (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)A->spmm_carry, accumulate)
+                       (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)A->spmm_carry, accumulate, (int)lr)
 #define SPMI_SPMM_WIN(LR)                           \
     do {                                            \
         if (small) SPMI_SPMM_WIN_O(LR, uint32_t);   \
@@ -685,7 +695,8 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             else if (lr == 8) SPMI_SPMM_WIN(8);
             else if (lr == 16) SPMI_SPMM_WIN(16);
             else if (lr == 32) SPMI_SPMM_WIN(32);
-            else SPMI_SPMM_WIN(64);
+            else if (lr == 64) SPMI_SPMM_WIN(64);
+            else SPMI_SPMM_WIN(0);                    // any other number of 16-byte pieces per row, up to 64
 #undef SPMI_SPMM_WIN
 #undef SPMI_SPMM_WIN_O
             SP_HIP(hipGetLastError());

@@ -135,7 +135,7 @@ def test_spmv_is_reproducible_run_to_run(kernel):
     assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[0], ys[2])
 
 
-@pytest.mark.parametrize("N", [2, 3, 4, 8, 16, 32, 64, 70, 128])
+@pytest.mark.parametrize("N", [2, 3, 4, 6, 8, 12, 16, 32, 42, 64, 70, 100, 128, 130, 256, 260])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_csr_spmm(N, dtype):
     w = W.cfg3_powerlaw_csr_spmm(6000, 5000, N=N, cap=2500)
@@ -150,10 +150,10 @@ def test_csr_spmm(N, dtype):
     sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, 1)          # one column per lane, whatever N is
     C, ref, mag = run(A, w, B)
     assert_product_close(C, ref, mag, dtype, "spmm, one column per lane")
-    vec_ok = (N * np.dtype(dtype).itemsize) % 16 == 0 and (N * np.dtype(dtype).itemsize) // 16 in (1, 2, 4, 8, 16, 32, 64)
+    pieces = (N * np.dtype(dtype).itemsize) // 16 if (N * np.dtype(dtype).itemsize) % 16 == 0 else 0
     for kernel in (2, 3):                                     # 16-byte loads, a wave per row / cut by entries: only some N
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, kernel)
-        if vec_ok:
+        if (pieces in (1, 2, 4, 8, 16, 32, 64)) if kernel == 2 else (1 <= pieces <= 64):
             C, ref, mag = run(A, w, B)
             assert_product_close(C, ref, mag, dtype, "spmm, 16-byte loads, kernel %d" % kernel)
             C, ref, mag = run(A, w, B, accumulate=True, C0=C0)
