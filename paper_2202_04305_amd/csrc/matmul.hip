@@ -680,7 +680,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
                 if (!At->spmm_carry) return SP_ERR_ALLOC;
                 At->spmm_carry_bytes = need;
             }
-            const bool small = (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B
+            const bool small = sizeof(CT) == 4 && (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B (64-bit coordinates keep 64-bit offsets)
 #define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
     hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,    \
                        (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)A->spmm_carry, accumulate, (int)lr)

@@ -329,7 +329,8 @@ sp_status mttkrp_t(const sp_tensor *B, const VT *M, int64_t ldm, const VT *X, in
         ldf = ldp_bytes / (int64_t)sizeof(VT);
     }
     // byte offsets into the factor matrices fit 32 bits when both are below 4 GB
-    const bool small = (uint64_t)rows_m * (uint64_t)ldm * sizeof(VT) < ((uint64_t)1 << 32) && (uint64_t)rows_x * (uint64_t)ldx * sizeof(VT) < ((uint64_t)1 << 32);
+    const bool small = sizeof(CT) == 4 && (uint64_t)rows_m * (uint64_t)ldm * sizeof(VT) < ((uint64_t)1 << 32) &&
+                       (uint64_t)rows_x * (uint64_t)ldx * sizeof(VT) < ((uint64_t)1 << 32);      // 64-bit coordinates keep 64-bit offsets
     {
         sp_prof_scope prof(B, st);
         const unsigned gx = (unsigned)(ceil_div(ceil_div(nwin, kWaves), 8) * 8);   // a multiple of 8: see the block mapping in the kernel

@@ -197,7 +197,7 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
         const int64_t lr = K / V;
         const bool vec = rowblocks->start && K % V == 0 && (lr == 1 || lr == 2 || lr == 4 || lr == 8 || lr == 16 || lr == 32 || lr == 64) && lda % V == 0 &&
                          ldt % V == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)Bt % 16 == 0;
-        const bool small = (uint64_t)n * (uint64_t)ldt * sizeof(VT) < ((uint64_t)1 << 32);      // 32-bit byte offsets into the transposed B
+        const bool small = sizeof(CT) == 4 && (uint64_t)n * (uint64_t)ldt * sizeof(VT) < ((uint64_t)1 << 32);      // 32-bit byte offsets into the transposed B (64-bit coordinates keep 64-bit offsets)
         const dim3 grid(grid_for(nrows, kThreads / 64));
         if (vec) {
 #define SPMI_SDDMM_VEC_O(LR, OT)                                                                                              \

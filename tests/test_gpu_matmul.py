@@ -375,3 +375,17 @@ def test_degenerate_products():
     with pytest.raises(sp.SpError) as e:
         sp.sp_matmul(A, B, C, N=7, ldb=3, ldc=7)
     assert e.value.code == oracle.ERR_SHAPE
+
+
+def test_spmm_with_64_bit_coordinates_takes_64_bit_row_offsets():
+    """crd in 64 bits: the kernels cut by entries then keep 64-bit byte offsets of the rows of B (the variant meant for
+    operands of 4 GB and more, exercised here at a small size)."""
+    w = W.cfg3_powerlaw_csr_spmm(5000, 4000, N=16, cap=2000)
+    B = w.dense_operand(16)
+    for pw, cw in [(32, 64), (64, 64)]:
+        say("case spmm 64-bit crd", pw, cw)
+        A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, pw, cw)
+        for kernel in (3, 0):
+            sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, kernel)
+            C, ref, mag = run(A, w, B)
+            assert_product_close(C, ref, mag, w.dtype, "spmm 64-bit crd")

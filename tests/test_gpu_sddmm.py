@@ -75,3 +75,19 @@ def test_sddmm_errors_and_degenerate():
     z = np.zeros(0, dtype=np.int64)
     E = gpu_pack((0, 1), (0, 1), (50, 40), [z, z], np.zeros(0))
     assert sp.sp_sddmm(E, A, B).numel() == 0
+
+
+def test_sddmm_with_64_bit_coordinates():
+    w = W.cfg2_powerlaw_csr(3000, 2500, cap=900)
+    m, n = w.shape
+    K = 32
+    A = prng.uniform_pm1(6, 8, m * K).reshape(m, K)
+    B = prng.uniform_pm1(6, 9, K * n).reshape(K, n)
+    x, mag = oracle.sddmm_coo(w.shape, w.rows, w.cols, w.vals, A, B)
+    for pw, cw in [(32, 64), (64, 64)]:
+        say("case sddmm 64-bit crd", pw, cw)
+        S = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, pw, cw)
+        xs = oracle.pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], x, pw, cw).values
+        ms = oracle.pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], mag, pw, cw).values
+        X = sp.sp_sddmm(S, dev(A), dev(B))
+        assert np.all(np.abs(X.cpu().numpy() - xs) <= 1e-12 * ms)
