@@ -20,7 +20,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int64_t kTW = 256;                  // stored entries per wave
+constexpr int64_t kTW = 128;                  // stored entries per wave
 
 __global__ __launch_bounds__(kThreads) void zero_rows_kernel(char *__restrict__ A, int64_t rows, int64_t row_bytes, int64_t ld_bytes)
 {
