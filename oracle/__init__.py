@@ -259,3 +259,35 @@ def spgemm_coo(shape_a, ra, ca, va, shape_b, rb, cb, vb):
     got = lib().oracle_spgemm_coo(*args, _ptr(ci), _ptr(cj), _ptr(cv), _ptr(mag))
     assert got == cnt
     return ci, cj, cv, mag
+
+
+def add_coo(shape, coords_a, vals_a, coords_b, vals_b):
+    """(coords, vals, mag) of C = A + B element by element (the example of Section 5.1): C stores every position that A
+    or B stores; where both do, the two values are added once in the operands' dtype, so the result is exact to the
+    last bit whatever the order.  Positions come out in lexicographic order of the original dimensions."""
+    va = np.ascontiguousarray(vals_a)
+    vb = np.ascontiguousarray(vals_b, dtype=va.dtype)
+    _dt(va.dtype)
+    ca = [np.ascontiguousarray(c, dtype=np.int64) for c in coords_a]
+    cb = [np.ascontiguousarray(c, dtype=np.int64) for c in coords_b]
+    for c, n in zip(ca + cb, list(shape) * 2):
+        if c.size and (c.min() < 0 or c.max() >= n):
+            raise OracleError(ERR_COORD_RANGE)
+    ka = np.ravel_multi_index(ca, shape) if va.size else np.zeros(0, dtype=np.int64)
+    kb = np.ravel_multi_index(cb, shape) if vb.size else np.zeros(0, dtype=np.int64)
+    if np.unique(ka).size != ka.size or np.unique(kb).size != kb.size:
+        raise OracleError(ERR_DUPLICATE)
+    keys, inv = np.unique(np.concatenate([ka, kb]), return_inverse=True)
+    out = np.zeros(keys.size, dtype=va.dtype)
+    mag = np.zeros(keys.size, dtype=np.float64)
+    out[inv[:ka.size]] = va                                  # every position at most once per operand
+    hit = np.zeros(keys.size, dtype=bool)
+    hit[inv[:ka.size]] = True
+    ib = inv[ka.size:]
+    both = hit[ib]
+    out[ib[both]] = out[ib[both]] + vb[both]                 # one addition, in dtype
+    out[ib[~both]] = vb[~both]
+    mag[inv[:ka.size]] = np.abs(va.astype(np.float64))
+    mag[ib] += np.abs(vb.astype(np.float64))
+    coords = [c.astype(np.int64) for c in np.unravel_index(keys, shape)] if keys.size else [np.zeros(0, dtype=np.int64) for _ in shape]
+    return coords, out, mag
