@@ -144,6 +144,13 @@ sp_status sp_mttkrp(const sp_tensor *B, const void *C, int64_t ldc, const void *
  * differ), DTYPE (A and B differ), TOO_LARGE (2^31 or more pairs), WIDTH (C does not fit encC's widths), ALLOC, HIP. */
 sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C);
 
+/* Element-wise sum C = A + B of two packed tensors of the same shape and dtype, any rank and encodings (the example of
+ * Section 5.1).  *C is a new tensor under `encC` with A's allocator that stores every position A or B stores (padding
+ * zeros of dense levels and explicit zeros included, a sum that comes to zero too); where both store a position the
+ * two values are added once.  Synchronises like sp_pack.  Errors: NULL, RANK, SHAPE (shapes differ), DTYPE,
+ * TOO_LARGE (2^31 or more stored positions together), WIDTH (C does not fit encC's widths), ALLOC, HIP. */
+sp_status sp_add(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C);
+
 /* The paper's convert operation between two sparse encodings (Section 4.2: conversions go through an intermediate
  * coordinate scheme, which avoids one converter per pair of formats).  Every stored position of `from` (explicit and
  * padding zeros included) becomes a stored entry of the new tensor, which has `from`'s shape, dtype and allocator and

@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -68,6 +68,8 @@ def load_library():
     L.sp_values.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
     L.sp_unpack.restype = ci
     L.sp_unpack.argtypes = [vp, vp, vp, vp]
+    L.sp_add.restype = ci
+    L.sp_add.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp)]
     L.sp_spgemm.restype = ci
     L.sp_spgemm.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp)]
     L.sp_mttkrp.restype = ci
@@ -288,6 +290,13 @@ def sp_spgemm(A, B, enc):
     """C = A.B for two packed sparse matrices, as a new tensor under `enc` (it lives in A's allocator)."""
     h = ctypes.c_void_p()
     _check(load_library().sp_spgemm(A._h, B._h, enc._h, _stream_ptr(), ctypes.byref(h)), "in sp_spgemm")
+    return Tensor(h, A._allocator, A.dtype, A.device)
+
+
+def sp_add(A, B, enc):
+    """C = A + B element by element, as a new tensor under `enc` (it lives in A's allocator)."""
+    h = ctypes.c_void_p()
+    _check(load_library().sp_add(A._h, B._h, enc._h, _stream_ptr(), ctypes.byref(h)), "in sp_add")
     return Tensor(h, A._allocator, A.dtype, A.device)
 
 

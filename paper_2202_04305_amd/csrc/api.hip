@@ -215,6 +215,47 @@ extern "C" sp_status sp_convert(const sp_tensor *from, const sp_encoding *to, vo
                    from->free_, from->ctx, st, out);
 }
 
+// C = A + B element by element: the stored positions of both go through the storage builder as one list of
+// (key, value) records, A's first; the builder's stable sort brings the two records of a position both store next to
+// each other and its summation pass adds them (a + b, one addition).
+extern "C" sp_status sp_add(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C)
+{
+    if (!A || !B || !encC || !C) return SP_ERR_NULL;
+    *C = nullptr;
+    const int rank = A->enc.rank;
+    if (B->enc.rank != rank || encC->rank != rank) return SP_ERR_RANK;
+    for (int d = 0; d < rank; ++d) if (A->shape[d] != B->shape[d]) return SP_ERR_SHAPE;
+    if (A->dtype != B->dtype) return SP_ERR_DTYPE;
+    const int64_t na = A->nvalues, nb = B->nvalues, n = na + nb;
+    if (n >= ((int64_t)1 << 31)) return SP_ERR_TOO_LARGE;
+    hipStream_t st = (hipStream_t)stream;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    sp_scratch tmp(mem);
+    const size_t cnt = (size_t)(n > 0 ? n : 1), vsz = A->dtype == SP_F64 ? 8 : 4;
+    int64_t *coords[SP_MAX_RANK] = {nullptr};
+    for (int d = 0; d < rank; ++d) {
+        coords[d] = (int64_t *)tmp.get(cnt * 8);
+        if (!coords[d]) return SP_ERR_ALLOC;
+    }
+    char *vals = (char *)tmp.get((cnt * vsz + 15) & ~(size_t)15);
+    uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
+    int *flags = (int *)tmp.get(64);
+    if (!vals || !keys || !flags) return SP_ERR_ALLOC;
+    SP_TRY(sp_unpack(A, coords, vals, st));
+    int64_t *second[SP_MAX_RANK] = {nullptr};
+    for (int d = 0; d < rank; ++d) second[d] = coords[d] + na;
+    SP_TRY(sp_unpack(B, second, vals + (size_t)na * vsz, st));
+    // a handle with C's level order and sizes, only to make the keys by
+    sp_tensor *shaped = nullptr;
+    int key_bits = 0;
+    SP_TRY(spmi_new_tensor(encC, A->shape, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, false, &shaped, &key_bits));
+    sp_status s = spmi_fill_zero(flags, 64, st);
+    if (s == SP_OK) s = spmi_make_keys(shaped, (const int64_t *const *)coords, n, keys, flags, st);
+    delete shaped;
+    SP_TRY(s);
+    return spmi_pack_keys(encC, A->shape, (sp_dtype)A->dtype, A->alloc, A->free_, A->ctx, n, keys, vals, tmp, st, C);
+}
+
 extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
                                void *stream)
 {

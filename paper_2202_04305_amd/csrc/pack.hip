@@ -1045,6 +1045,20 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
     return spmi_finish_pack(t, status, st, out);
 }
 
+// keys[e] = the linearised key (level order of `t`, mixed radix over its level sizes) of the entry whose coordinate in
+// dimension d is coords[d][e]; flags[0] is set when a coordinate is out of range.
+sp_status spmi_make_keys(const sp_tensor *t, const int64_t *const *coords, int64_t n, uint64_t *keys, int *flags, hipStream_t st)
+{
+    if (n <= 0) return SP_OK;
+    level_args la;
+    memset(&la, 0, sizeof(la));
+    la.rank = t->enc.rank;
+    for (int l = 0; l < la.rank; ++l) { la.coord[l] = coords[t->enc.perm[l]]; la.size[l] = t->size[l]; }
+    hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, st, la, n, keys, flags);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
 // The storage of a tensor whose entries are given as linearised keys (level order, mixed radix over the level sizes)
 // with the value bits as payload; entries with equal keys are added up in the order they are given.
 sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,

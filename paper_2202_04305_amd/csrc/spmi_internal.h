@@ -161,6 +161,9 @@ constexpr int kSpmiStreamThreads = SPMI_ST;                  // threads per bloc
 constexpr int kSpmiStreamPer = SPMI_PER;                     // stored entries per thread (even)
 constexpr int64_t kSpmiStreamT = kSpmiStreamThreads * kSpmiStreamPer;     // stored entries per block
 
+// keys[e] = linearised key, in the level order of `shaped` (a tensor handle whose enc and size[] are set), of the entry
+// with coordinates coords[d][e]; flags[0] != 0 afterwards on the device when a coordinate was out of range.
+sp_status spmi_make_keys(const sp_tensor *shaped, const int64_t *const *coords, int64_t n, uint64_t *keys, int *flags, hipStream_t st);
 // A new tensor handle with shape, sizes by level and the key width worked out (SP_ERR_TOO_LARGE, SP_ERR_WIDTH as sp_pack
 // documents; `entries_in_an_empty_dimension` turns into SP_ERR_COORD_RANGE at its place in that order).
 sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
