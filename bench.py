@@ -31,6 +31,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg2", 32, 3): 378.9e6,      # profiles/spmv_segmented_cfg2_w32_hbm_traffic.txt
     ("cfg2", 32, 2): 1447.0e6,     # profiles/spmv_stream_cfg2_w32_hbm_traffic.txt
     ("cfg3", 32, 0): 9.47e9,       # profiles/spmm_windows_cfg3_w32_profile.txt
+    ("cfg4", 32, 2): 0.43e9,       # profiles/spmv_dcsr_cfg4_w32_profile.txt
+    ("cfg5", 32, 0): 1.77e9,       # profiles/spmm_csc_cfg5_w32_profile.txt
     ("mttkrp", 32, "dss"): 11.67e9,  # profiles/mttkrp_windows_tensor3_w32_profile.txt
 }
 
