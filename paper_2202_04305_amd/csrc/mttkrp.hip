@@ -12,7 +12,7 @@
 // Work is cut by stored entries: wave w owns the entries [w*TW, (w+1)*TW) and walks the fibres that meet that window,
 // each clipped to it.  LR lanes cover the J columns (16-byte loads when J allows) and S = 64 / LR entries go side by
 // side; the S partial sums meet only when a slice ends.  The part of a slice that began in an earlier window goes to
-// carry[w] (J values); a second kernel adds the carries to A in window order; everything else is written to A
+// carry[w] (J values); a second kernel adds a slice's carries to A in a fixed pattern; everything else is written to A
 // directly.  No atomics: results are bit-reproducible.
 #include "spmi_internal.h"
 
@@ -20,7 +20,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int64_t kTW = 128;                  // stored entries per wave
+// stored entries per wave.  Measured on the 76.9 M-entry tensor with 42 columns: 512 -> 3.18 ms, 256 -> 2.21, 128 -> 1.97,
+// 64 -> 2.15: with small windows fewer slices are in flight at a time and more of their factor rows are found in the L2.
+constexpr int64_t kTW = 128;
 
 __global__ __launch_bounds__(kThreads) void zero_rows_kernel(char *__restrict__ A, int64_t rows, int64_t row_bytes, int64_t ld_bytes)
 {
