@@ -184,3 +184,32 @@ def test_full_size_mttkrp_both_storage_orders():
         assert np.all(err <= 1e-12 * mag[sample]), float(np.max(err / np.maximum(mag[sample], 1e-300)))
         assert np.all(Ah[per_slice == 0] == 0.0) and not np.isnan(Ah).any()
         B.free()
+
+
+def test_pack_and_multiply_300_million_entries():
+    """Well above the benchmark sizes: 300,000 rows of exactly 1,000 entries, given in an order scrambled by a
+    multiplicative permutation (made on the device: no host generator needed at this size).  Every array of the result
+    is known in closed form; the product with a vector of ones gives the row sums."""
+    m, k, n = 300_000, 1_000, 4_096
+    N = m * k
+    e = torch.arange(N, dtype=torch.int64, device=DEV)
+    src = (e * 1_000_003) % N                          # a bijection of [0, N): gcd(1000003, N) = 1
+    del e
+    rows = src // k
+    cols = (src % k) * 4 + (rows % 4)                  # distinct inside a row, ascending with src % k
+    vals = (src % 1024).to(torch.float64)              # small integers: sums are exact
+    say("packing", N, "entries")
+    for pw, cw in [(32, 32), (64, 64)]:
+        A = sp.sp_pack(sp.sp_encode((0, 1), (0, 1), pw, cw), (m, n), [rows, cols], vals)
+        info = sp.sp_tensor_info(A)
+        assert info.nvalues == N and info.maxSegment == k
+        pos, crd, v = sp.sp_pos(A, 1), sp.sp_crd(A, 1), sp.sp_values(A)
+        assert bool(torch.equal(pos.long(), torch.arange(m + 1, dtype=torch.int64, device=DEV) * k))
+        want = torch.arange(N, dtype=torch.int64, device=DEV)              # storage order = the unscrambled order
+        assert bool(torch.equal(crd.long(), (want % k) * 4 + ((want // k) % 4)))
+        assert bool(torch.equal(v, (want % 1024).to(torch.float64)))
+        y = torch.full((m,), float("nan"), dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, torch.ones(n, dtype=torch.float64, device=DEV), y)
+        assert bool(torch.equal(y, (want % 1024).to(torch.float64).view(m, k).sum(dim=1)))
+        del want, pos, crd, v
+        A.free()
