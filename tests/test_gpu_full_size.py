@@ -186,12 +186,17 @@ def test_full_size_mttkrp_both_storage_orders():
         B.free()
 
 
-def test_pack_and_multiply_300_million_entries():
-    """Well above the benchmark sizes: 300,000 rows of exactly 1,000 entries, given in an order scrambled by a
-    multiplicative permutation (made on the device: no host generator needed at this size).  Every array of the result
-    is known in closed form; the product with a vector of ones gives the row sums."""
-    m, k, n = 300_000, 1_000, 4_096
+@pytest.mark.parametrize("m", [300_000, 1_500_000])
+def test_pack_and_multiply_hundreds_of_millions_of_entries(m):
+    """Well above the benchmark sizes, up to 1.5 billion entries (the builder takes fewer than 2^31): rows of exactly 1,000
+    entries, given in an order scrambled by a multiplicative permutation (made on the device: no host generator needed
+    at this size).  Every array of the result is known in closed form; the product with a vector of ones gives the row
+    sums."""
+    k, n = 1_000, 4_096
     N = m * k
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < 150 * N:
+        pytest.skip("needs about %d GB of free device memory" % (150 * N >> 30))
     e = torch.arange(N, dtype=torch.int64, device=DEV)
     src = (e * 1_000_003) % N                          # a bijection of [0, N): gcd(1000003, N) = 1
     del e
@@ -199,7 +204,7 @@ def test_pack_and_multiply_300_million_entries():
     cols = (src % k) * 4 + (rows % 4)                  # distinct inside a row, ascending with src % k
     vals = (src % 1024).to(torch.float64)              # small integers: sums are exact
     say("packing", N, "entries")
-    for pw, cw in [(32, 32), (64, 64)]:
+    for pw, cw in ([(32, 32), (64, 64)] if m <= 300_000 else [(32, 32)]):
         A = sp.sp_pack(sp.sp_encode((0, 1), (0, 1), pw, cw), (m, n), [rows, cols], vals)
         info = sp.sp_tensor_info(A)
         assert info.nvalues == N and info.maxSegment == k
