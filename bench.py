@@ -365,7 +365,7 @@ def main():
                          "mttkrp: dss (default) / dss-alt as in the paper's table, sss / sss-alt with a compressed outer level")
     ap.add_argument("--copies", type=int, default=0, help="independent copies of A, B, C rotated through (cold regime)")
     ap.add_argument("--width", type=int, default=32, choices=[32, 64], help="pos/crd bit width")
-    ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming")
+    ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming, 4 binned by column panel and row block")
     ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
     ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads with a wave per row, 3 16-byte loads cut by entries")
     ap.add_argument("--spgemm-kernel", type=int, default=0, help="SpMSpM: 0 auto, 1 pairs through the storage builder, 2 LDS workspace per row")
@@ -534,9 +534,10 @@ def main():
     if spmv:
         kk = args.kernel
         if kk == 0:
-            kk = 3 if (name == "cfg2" and not args.small) else (1 if name == "cfg1" else 2)
+            kk = 4 if (name == "cfg2" and not args.small) else (1 if name == "cfg1" else 2)
         kernel_name = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
-                       3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel"}[kk]
+                       3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel",
+                       4: "binned SpMV: spmv_bins_multiply_kernel + spmv_bins_reduce_kernel"}[kk]
         if w.level_types[1] == 0:
             kernel_name = "dense_rows_kernel"
     else:

@@ -173,7 +173,10 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
 
 /* Kernel choice for sp_matmul on this tensor, for A/B measurements.  key/value pairs:
  *   SP_TUNE_SPMV_KERNEL: 0 = automatic, 1 = lanes-per-row, 2 = streaming over the CSR arrays (bit-reproducible),
- *                        3 = streaming over a column-segmented copy (built and kept on first use; CSR only)
+ *                        3 = streaming over a column-segmented copy (built and kept on first use; CSR only),
+ *                        4 = two streaming passes over a copy binned by column panel and row block, gathers and
+ *                        adds inside the LDS (built and kept on first use; CSR only; the order in which a row's
+ *                        products are added varies from call to call: results agree to rounding, not bit for bit)
  *   SP_TUNE_SPMM_KERNEL: 0 = automatic, 1 = one column per lane, 2 = 16 bytes of a row of B per lane, a wave per row,
  *                        3 = the same cut by stored entries instead of rows (2 and 3 need N a multiple
  *                        of 16 / element size and B, C rows 16-byte aligned; 2 takes 1, 2, 4, ... 64 such vectors

@@ -115,7 +115,7 @@ extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
     if (!t) return SP_ERR_NULL;
     switch (key) {
     case SP_TUNE_SPMV_KERNEL:
-        if (value < 0 || value > 3) return SP_ERR_UNSUPPORTED;
+        if (value < 0 || value > 4) return SP_ERR_UNSUPPORTED;
         t->tune_spmv = (int)value;
         if (t->transposed) t->transposed->tune_spmv = (int)value;
         return SP_OK;

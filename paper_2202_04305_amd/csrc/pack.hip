@@ -551,6 +551,16 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(const PT *__rest
     if (pos[r + 1] > pos[r]) { nz_rowid[excl[r]] = (CT)r; nz_pos[excl[r]] = pos[r]; }
 }
 
+// out (zero before) = the largest number of rows that one window of the streaming kernels meets
+__global__ __launch_bounds__(kThreads) void max_span_kernel(const int32_t *__restrict__ rowblk, int64_t nb, unsigned long long *__restrict__ out)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    unsigned long long span = b < nb ? (unsigned long long)(rowblk[b + 1] - rowblk[b]) : 0ull;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { const unsigned long long o = __shfl_xor(span, d, 64); span = o > span ? o : span; }
+    if ((threadIdx.x & 63) == 0 && span) atomicMax(out, span);
+}
+
 static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
 {
     if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
@@ -564,12 +574,24 @@ static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t 
         hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
     SP_HIP(hipGetLastError());
     uint32_t last_mark = 0, last_excl = 0;
+    unsigned long long span = 0;
     SP_HIP(hipMemcpyAsync(&last_mark, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
     SP_TRY(spmi_exclusive_scan(mark, nrows, 32, tmp, st));
     SP_HIP(hipMemcpyAsync(&last_excl, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    if (t->rowblocks.start) {
+        unsigned long long *dspan = (unsigned long long *)tmp.get(64);
+        if (!dspan) return SP_ERR_ALLOC;
+        SP_TRY(spmi_fill_zero(dspan, 64, st));
+        hipLaunchKernelGGL(max_span_kernel, dim3(blocks_for(t->rowblocks.nblocks)), dim3(kThreads), 0, st, (const int32_t *)t->rowblocks.start,
+                           t->rowblocks.nblocks, dspan);
+        SP_HIP(hipGetLastError());
+        SP_HIP(hipMemcpyAsync(&span, dspan, 8, hipMemcpyDeviceToHost, st));
+    }
     SP_HIP(hipStreamSynchronize(st));
     const int64_t nz = (int64_t)last_excl + last_mark;
-    if (nz * 2 > nrows) return SP_OK;                      // not worth it: at least half of the rows hold something
+    // not worth it when at least half of the rows hold something, unless one window of the streaming kernels would have to walk
+    // over a very long run of empty rows all by itself
+    if (nz * 2 > nrows && span < 65536) return SP_OK;
     sp_mem mem{t->alloc, t->free_, t->ctx};
     const int ps = t->enc.pw / 8, cs = t->enc.cw / 8;
     void *rid = mem.get(pad16((size_t)(nz > 0 ? nz : 1) * cs));
@@ -644,6 +666,161 @@ sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_byt
     return SP_OK;
 }
 
+// ---- how scattered the innermost coordinates are -------------------------------------------
+template <typename CT>
+__global__ __launch_bounds__(kThreads) void count_jumps_kernel(const CT *__restrict__ crd, int64_t n, unsigned long long *__restrict__ out)
+{
+    __shared__ unsigned int wsum[kThreads / 64];
+    unsigned int mine = 0;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e + 1 < n; e += stride)
+        mine += (uint64_t)((int64_t)crd[e + 1] - (int64_t)crd[e]) >= 16u ? 1u : 0u;      // a step back (next segment) counts as well
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned int tot = 0;
+        for (int w = 0; w < kThreads / 64; ++w) tot += wsum[w];
+        if (tot) atomicAdd(out, (unsigned long long)tot);
+    }
+}
+
+sp_status spmi_column_scatter(sp_tensor *A, hipStream_t st, double *share)
+{
+    const int last = A->enc.rank - 1;
+    if (A->scatter < 0) {
+        const int64_t n = A->enc.lt[last] == SP_COMPRESSED ? A->ncrd[last] : 0;
+        if (n < 2) A->scatter = 0;
+        else {
+            sp_mem mem{A->alloc, A->free_, A->ctx};
+            sp_scratch tmp(mem);
+            unsigned long long *cnt = (unsigned long long *)tmp.get(64);
+            if (!cnt) return SP_ERR_ALLOC;
+            SP_TRY(spmi_fill_zero(cnt, 64, st));
+            const unsigned nb = blocks_for(n) < 4096u ? blocks_for(n) : 4096u;
+            if (A->enc.cw == 32)
+                hipLaunchKernelGGL(count_jumps_kernel<int32_t>, dim3(nb), dim3(kThreads), 0, st, (const int32_t *)A->crd[last], n, cnt);
+            else
+                hipLaunchKernelGGL(count_jumps_kernel<int64_t>, dim3(nb), dim3(kThreads), 0, st, (const int64_t *)A->crd[last], n, cnt);
+            SP_HIP(hipGetLastError());
+            unsigned long long h = 0;
+            SP_HIP(hipMemcpyAsync(&h, cnt, 8, hipMemcpyDeviceToHost, st));
+            SP_HIP(hipStreamSynchronize(st));
+            A->scatter = (double)h / (double)(n - 1);
+        }
+    }
+    *share = A->scatter;
+    return SP_OK;
+}
+
+// ---- binned copy (see sp_bins) ------------------------------------------------------------
+static void free_bins(sp_tensor *t)
+{
+    if (!t->bins) return;
+    sp_mem mem{t->alloc, t->free_, t->ctx};
+    mem.put(t->bins->val); mem.put(t->bins->prod); mem.put(t->bins->lcol); mem.put(t->bins->lrow); mem.put(t->bins->off);
+    delete t->bins;
+    t->bins = nullptr;
+}
+
+// key = ((panel * nrows + row) << pshift) | column inside the panel: sorting by it gives panel-major buckets with rows,
+// then columns, ascending inside.
+__global__ __launch_bounds__(kThreads) void bin_keys_kernel(const int64_t *__restrict__ rows, const int64_t *__restrict__ cols, int64_t n,
+                                                            int pshift, int64_t nrows, uint64_t *__restrict__ keys)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    const uint64_t c = (uint64_t)cols[e];
+    keys[e] = (((c >> pshift) * (uint64_t)nrows + (uint64_t)rows[e]) << pshift) | (c & (((uint64_t)1 << pshift) - 1));
+}
+
+// From the sorted keys: the 16-bit coordinates of every entry, and off[b] = first entry of bucket b for every bucket
+// (an entry that opens a new bucket fills in the starts of the empty buckets before it as well; the last entry those
+// after it, up to off[nbuckets] = n).
+__global__ __launch_bounds__(kThreads) void bin_decode_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int rshift,
+                                                              divisor nrows, int64_t rowblocks, int64_t nbuckets,
+                                                              uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow,
+                                                              int64_t *__restrict__ off)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    auto bucket_of = [&](uint64_t key, uint64_t *row_out) -> int64_t {
+        const uint64_t v = key >> pshift;
+        const uint64_t p = div_by(v, nrows);
+        const uint64_t row = v - p * nrows.d;
+        if (row_out) *row_out = row;
+        return (int64_t)(p * (uint64_t)rowblocks + (row >> rshift));
+    };
+    const uint64_t key = keys[e];
+    uint64_t row;
+    const int64_t b = bucket_of(key, &row);
+    lcol[e] = (uint16_t)(key & (((uint64_t)1 << pshift) - 1));
+    lrow[e] = (uint16_t)(row & (((uint64_t)1 << rshift) - 1));
+    const int64_t before = e > 0 ? bucket_of(keys[e - 1], nullptr) : -1;
+    for (int64_t q = before + 1; q <= b; ++q) off[q] = e;
+    if (e == n - 1)
+        for (int64_t q = b + 1; q <= nbuckets; ++q) off[q] = n;
+}
+
+// Builds and keeps the binned copy of a CSR tensor; no-op when it exists.  Synchronises.  SP_ERR_UNSUPPORTED for other
+// encodings, for an empty tensor and when the bucket table would be larger than the tensor itself.
+sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
+{
+    if (A->bins) return SP_OK;
+    if (A->enc.rank != 2 || A->enc.lt[0] != SP_DENSE || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
+    const int64_t m = A->shape[0], n = A->shape[1], nnz = A->nvalues;
+    const int pshift = kSpmiBinPanelShift, rshift = kSpmiBinRowShift;
+    const int64_t panels = ceil_div(n, (int64_t)1 << pshift), rowblocks = ceil_div(m, (int64_t)1 << rshift);
+    if (nnz < 1 || panels > 0x7fffffff || rowblocks > 0x7fffffff) return SP_ERR_UNSUPPORTED;
+    const unsigned __int128 nb128 = (unsigned __int128)panels * (unsigned __int128)rowblocks;
+    if (nb128 > (unsigned __int128)nnz + 4096) return SP_ERR_UNSUPPORTED;
+    const int64_t nbuckets = (int64_t)nb128;
+    const int vbytes = A->dtype == SP_F64 ? 8 : 4;
+    int key_bits = pshift;
+    while (key_bits < 64 && (((unsigned __int128)panels * (unsigned __int128)m) >> (key_bits - pshift)) != 0) ++key_bits;
+    if (key_bits > 63) return SP_ERR_UNSUPPORTED;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    sp_bins *g = new sp_bins();
+    A->bins = g;                                         // owned from here on: free_bins() releases whatever was allocated
+    g->nnz = nnz; g->panels = (int)panels; g->rowblocks = (int)rowblocks;
+    // pieces per panel in the first pass: about 32768 entries each, so that loading the slice of x stays a small part
+    const int64_t per_panel = nnz / panels;
+    g->pieces = (int)(per_panel / 32768 < 1 ? 1 : per_panel / 32768 > 64 ? 64 : per_panel / 32768);
+    while (panels * g->pieces < 512 && per_panel / (2 * g->pieces) >= 4096) g->pieces *= 2;      // enough blocks for every CU
+    g->val = mem.get(pad16((size_t)nnz * vbytes));
+    g->prod = mem.get(pad16((size_t)nnz * vbytes));
+    g->lcol = (uint16_t *)mem.get(pad16((size_t)nnz * 2));
+    g->lrow = (uint16_t *)mem.get(pad16((size_t)nnz * 2));
+    g->off = (int64_t *)mem.get(pad16((size_t)(nbuckets + 1) * 8));
+    sp_status status = (g->val && g->prod && g->lcol && g->lrow && g->off) ? SP_OK : SP_ERR_ALLOC;
+    auto build = [&]() -> sp_status {
+        sp_scratch tmp(mem);
+        int64_t *rows = (int64_t *)tmp.get((size_t)nnz * 8);
+        int64_t *cols = (int64_t *)tmp.get((size_t)nnz * 8);
+        void *vals = tmp.get((size_t)nnz * 8);
+        uint64_t *keys = (uint64_t *)tmp.get((size_t)nnz * 8);
+        if (!rows || !cols || !vals || !keys) return SP_ERR_ALLOC;
+        int64_t *coords[2] = {rows, cols};
+        SP_TRY(sp_unpack(A, coords, vals, st));
+        hipLaunchKernelGGL(bin_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const int64_t *)rows, (const int64_t *)cols, nnz,
+                           pshift, m, keys);
+        SP_HIP(hipGetLastError());
+        uint64_t *sorted_keys = nullptr;
+        const void *sorted_vals = nullptr;
+        SP_TRY(spmi_radix_sort_pairs(keys, vals, vbytes, nnz, key_bits, tmp, st, &sorted_keys, &sorted_vals));
+        hipLaunchKernelGGL(bin_decode_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift, rshift,
+                           make_divisor((uint64_t)m), rowblocks, nbuckets, g->lcol, g->lrow, g->off);
+        SP_HIP(hipGetLastError());
+        SP_HIP(hipMemcpyAsync(g->val, sorted_vals, (size_t)nnz * vbytes, hipMemcpyDeviceToDevice, st));
+        SP_HIP(hipStreamSynchronize(st));
+        return SP_OK;
+    };
+    if (status == SP_OK) status = build();
+    if (status != SP_OK) { (void)hipStreamSynchronize(st); free_bins(A); }
+    return status;
+}
+
 static void release_tensor_arrays(sp_tensor *t)
 {
     sp_mem mem{t->alloc, t->free_, t->ctx};
@@ -668,6 +845,7 @@ extern "C" void sp_tensor_free(sp_tensor *t)
     if (!t) return;
     if (t->transposed) sp_tensor_free(t->transposed);
     free_segments(t);
+    free_bins(t);
     release_tensor_arrays(t);
     if (t->prof_events) {
         for (hipEvent_t e : *t->prof_events) (void)hipEventDestroy(e);
@@ -969,6 +1147,7 @@ sp_status spmi_new_tensor(const sp_encoding *enc, const int64_t *shape, sp_dtype
     sp_tensor *t = new sp_tensor();
     memset(t, 0, sizeof(*t));
     t->enc = *enc; t->dtype = dt; t->alloc = alloc; t->free_ = free_; t->ctx = ctx;
+    t->scatter = -1;
     // the linearised key and every dense position count must stay below 2^63
     unsigned __int128 prod = 1;
     for (int l = 0; l < rank; ++l) {

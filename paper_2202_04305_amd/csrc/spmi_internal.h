@@ -34,6 +34,21 @@ struct sp_segments {
     void *partial = nullptr;          // DEVICE value-typed[panels * nrows]: per-panel results before they are added up
 };
 
+// Binned copy for SpMV with a large x and scattered columns: the stored entries regrouped into buckets (column panel
+// of 2^pshift columns, row block of 2^rshift rows), panel-major, rows ascending inside a bucket.  Every entry keeps
+// its value, its column inside the panel and its row inside the row block in 16 bits each.  The product runs in two
+// streaming passes: one multiplies a panel's entries by the panel's slice of x held in LDS and writes the products in
+// place (`prod`), the other adds a row block's products up in an LDS slice of y.  No gather ever leaves the LDS.
+struct sp_bins {
+    void *val = nullptr;              // DEVICE value-typed[nnz], bucket order
+    void *prod = nullptr;             // DEVICE value-typed[nnz]: the products of the running call
+    uint16_t *lcol = nullptr;         // DEVICE [nnz]: column - panel * 2^pshift
+    uint16_t *lrow = nullptr;         // DEVICE [nnz]: row - rowblock * 2^rshift
+    int64_t *off = nullptr;           // DEVICE [panels * rowblocks + 1]: first entry of bucket panel * rowblocks + rowblock
+    int64_t nnz = 0;
+    int panels = 0, rowblocks = 0, pieces = 0;
+};
+
 struct sp_tensor {
     sp_encoding enc;
     int dtype;
@@ -60,6 +75,8 @@ struct sp_tensor {
     sp_rowblocks nz_rowblocks;
     sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
     sp_segments *segments;           // owned, built on first use
+    sp_bins *bins;                   // owned, built on first use
+    double scatter;                  // share of stored entries whose successor lies in another 128-byte line of x; < 0: not measured yet
     void *dense_partial;             // DEVICE scratch of the dense-row SpMV (per-chunk partial sums), grown on demand
     size_t dense_partial_bytes;
     void *spmm_carry;                // DEVICE scratch of the SpMM cut by entries (N values per block), grown on demand
@@ -151,6 +168,12 @@ sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype 
                          int64_t n, uint64_t *keys, void *payload, sp_scratch &tmp, hipStream_t st, sp_tensor **out);
 sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
 sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
+constexpr int kSpmiBinPanelShift = 13;                       // columns per panel of the binned copy: 8192 (a 64 KB slice of an f64 x)
+constexpr int kSpmiBinRowShift = 11;                         // rows per row block: 2048 (a 16 KB slice of an f64 y)
+sp_status spmi_build_bins(sp_tensor *A, hipStream_t st);
+// How scattered the gathers of a product are: the share of stored entries of the innermost level whose successor is 16 or
+// more coordinates away (or belongs to the next segment).  Measured once per tensor, then cached; synchronises the first time.
+sp_status spmi_column_scatter(sp_tensor *A, hipStream_t st, double *share);
 #ifndef SPMI_ST
 #define SPMI_ST 128
 #endif

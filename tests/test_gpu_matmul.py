@@ -101,6 +101,99 @@ def test_csr_spmv_column_segmented_empty_first_panel_and_fallback():
     assert e.value.code == oracle.ERR_UNSUPPORTED
 
 
+BINNED_CASES = SPMV_CASES + WIDE_CASES + [
+    ("one entry", lambda: W.uniform_random(5, 9, 1)),
+    ("last panel and last row block ragged", lambda: W.cfg2_powerlaw_csr(2048 * 3 + 1, 8192 * 2 + 1, mean=30.0, cap=5000)),
+]
+
+
+@pytest.mark.parametrize("name,maker", BINNED_CASES)
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_csr_spmv_binned(name, maker, dtype):
+    """Kernel 4: entries regrouped by (column panel, row block), products through an LDS slice of x, sums in an LDS slice
+    of y with atomic adds: within tolerance, and bit for bit on exact integers."""
+    w = maker()
+    w.vals = w.vals.astype(dtype)
+    w.dtype = dtype
+    widths = (32, 32) if dtype is np.float64 else (64, 32)
+    say("case binned spmv", name, dtype.__name__, w.stats)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals, *widths)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 4)
+    x = w.dense_operand(1).astype(dtype)
+    y, ref, mag = run(A, w, x)
+    assert_product_close(y, ref, mag, dtype, name)
+    y0 = prng.uniform_pm1(5, 5, w.shape[0]).astype(dtype)
+    y, ref, mag = run(A, w, x, accumulate=True, C0=y0)
+    assert_product_close(y, ref, mag, dtype, name + " accumulate")
+    if dtype is np.float64:
+        vals = w.exact_values()
+        A2 = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], vals, *widths)
+        sp.sp_tensor_tune(A2, sp.SP_TUNE_SPMV_KERNEL, 4)
+        y, ref, mag = run(A2, w, w.dense_operand(1, exact=True), vals=vals)
+        assert np.array_equal(y.cpu().numpy(), ref)
+
+
+def test_csr_spmv_binned_strides_and_refusals():
+    w = W.cfg2_powerlaw_csr(3000, 20000, mean=12.0, cap=900)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 4)
+    say("case binned, strided x and y")
+    x = w.dense_operand(1)
+    xs = torch.zeros((20000, 3), dtype=torch.float64, device=DEV)
+    xs[:, 0] = dev(x[:, 0].copy())
+    ys = torch.full((3000, 2), -7.0, dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, xs, ys, N=1, ldb=3, ldc=2)
+    ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
+    assert_product_close(ys[:, 0].contiguous(), ref, mag, np.float64, "strided binned spmv")
+    assert torch.all(ys[:, 1] == -7.0)
+    say("case binned, not CSR / empty / bucket table larger than the tensor")
+    for lt, shape, coords, vals in [
+        ((1, 1), w.shape, [w.rows, w.cols], w.vals),
+        ((0, 1), (50, 60), [np.zeros(0, dtype=np.int64)] * 2, np.zeros(0)),
+        ((0, 1), (1 << 22, 1 << 22), [w.rows, w.cols], w.vals),
+    ]:
+        T = gpu_pack(lt, (0, 1), shape, coords, vals)
+        sp.sp_tensor_tune(T, sp.SP_TUNE_SPMV_KERNEL, 4)
+        if len(vals) == 0:                                # nothing stored: nothing to bin, the product is zero
+            y = torch.full((shape[0],), float("nan"), dtype=torch.float64, device=DEV)
+            try:
+                sp.sp_matmul(T, torch.ones(shape[1], dtype=torch.float64, device=DEV), y)
+                assert torch.all(y == 0)
+            except sp.SpError as e:
+                assert e.code == oracle.ERR_UNSUPPORTED
+            continue
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_matmul(T, torch.ones(shape[1], dtype=torch.float64, device=DEV), torch.empty(shape[0], dtype=torch.float64, device=DEV))
+        assert e.value.code == oracle.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4])
+def test_csr_spmv_long_run_of_empty_rows(kernel):
+    """Most rows hold entries, but 100,000 consecutive ones hold none (and, for the column-segmented copy, a whole column
+    panel is empty): one window of the streaming kernels must not be left to walk over all of them."""
+    w = W.cfg2_powerlaw_csr(200000, 300000, mean=10.0, cap=2000)
+    w.rows = w.rows + 100000
+    w.cols = w.cols + 300000
+    w.shape = (300000, 600000)
+    say("case long run of empty rows, kernel", kernel)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+    x = w.dense_operand(1)
+    y, ref, mag = run(A, w, x)
+    assert_product_close(y, ref, mag, w.dtype, "empty run")
+    assert torch.all(y[:100000] == 0)
+    y0 = prng.uniform_pm1(5, 5, w.shape[0])
+    y, ref, mag = run(A, w, x, accumulate=True, C0=y0)
+    assert_product_close(y, ref, mag, w.dtype, "empty run, accumulate")
+    t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+    xd, yd = dev(x), torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+    t0.record()
+    for _ in range(10):
+        sp.sp_matmul(A, xd, yd)
+    t1.record(); torch.cuda.synchronize()
+    assert t0.elapsed_time(t1) / 10 < 1.0, "a product of 2 million entries took %.2f ms" % (t0.elapsed_time(t1) / 10)
+
+
 @pytest.mark.parametrize("kernel", [1, 2])
 def test_exact_integer_inputs_bit_exact(kernel):
     w = W.cfg2_powerlaw_csr(30000, 30000, mean=20.0, cap=7000)
