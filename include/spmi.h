@@ -193,7 +193,8 @@ enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, S
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);
 
 /* Kernel timing for measurements.  After sp_tensor_tune(t, SP_TUNE_PROFILE, 1) every sp_matmul on
- * t brackets its main kernel (the one that streams A; not the zero fill, not the fix-up) with a
+ * t brackets its main kernel (the one that streams A; not the zero fill, not the fix-up; both passes of
+ * the binned SpMV, all three launches of the column-segmented one) with a
  * pair of HIP events on the caller's stream.  sp_profile_read waits for those events, returns
  * the summed kernel time in milliseconds and the number of launches, and clears the record.
  * Profiling costs two event records per call; leave it off in production. */
