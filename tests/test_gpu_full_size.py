@@ -67,7 +67,7 @@ def test_cfg2_pack_and_spmv_full_size():
     x = w.dense_operand(1)
     yref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
     xd = dev(x[:, 0].copy())
-    for kernel in (0, 2, 3, 1):            # 0 = what bench.py times (the column-segmented kernel at this size)
+    for kernel in (0, 4, 2, 3, 1):         # 0 = what bench.py times (the binned kernel at this size)
         say("case cfg2 full: spmv kernel", kernel)
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
         y = torch.full((w.shape[0],), float("nan"), dtype=torch.float64, device=DEV)
@@ -79,6 +79,42 @@ def test_cfg2_pack_and_spmv_full_size():
     y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
     sp.sp_matmul(A1, torch.ones(w.shape[1], dtype=torch.float64, device=DEV), y)
     assert torch.equal(y, (sp.sp_pos(A1, 1)[1:] - sp.sp_pos(A1, 1)[:-1]).double())
+
+
+def test_automatic_spmv_kernel_follows_the_column_pattern():
+    """Two matrices of the size class where the automatic choice looks at the columns: nine diagonals (every gather falls
+    next to the previous one: the streaming kernel stays, bit for bit the same sums as with tune value 2) and the scattered
+    1M x 1M matrix (the binned kernel: same sums as with tune value 4 up to their order, so only to rounding)."""
+    n = 600_000
+    say("case automatic kernel: nine diagonals")
+    i = np.repeat(np.arange(n, dtype=np.int64), 9)
+    j = i + np.tile(np.arange(-4, 5, dtype=np.int64), n)
+    keep = (j >= 0) & (j < n)
+    i, j = i[keep], j[keep]
+    v = prng.uniform_pm1(17, 1, len(i))
+    x = prng.uniform_pm1(17, 2, n)
+    yref, mag = oracle.matmul_coo((n, n), i, j, v, x.reshape(n, 1))
+    ys = {}
+    for kernel in (0, 2):
+        A = gpu_pack((0, 1), (0, 1), (n, n), [i, j], v, 32, 32)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+        y = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, dev(x), y)
+        assert_product_close(y, yref, mag, np.float64, "diagonals, kernel %d" % kernel)
+        ys[kernel] = y
+    assert torch.equal(ys[0], ys[2])
+    say("case automatic kernel: scattered columns")
+    w = workload("cfg2")
+    x = w.dense_operand(1)
+    ys = {}
+    for kernel in (0, 2):
+        A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals, 32, 32)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, kernel)
+        y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, dev(x[:, 0].copy()), y)
+        ys[kernel] = y
+    assert not torch.equal(ys[0], ys[2])                     # another kernel, another order of the additions
+    assert float((ys[0] - ys[2]).abs().max()) < 1e-9
 
 
 def test_cfg3_spmm_full_size_sampled_rows():
