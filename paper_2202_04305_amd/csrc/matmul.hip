@@ -721,7 +721,9 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             if (kernel == 2 && !dcsr && nnz >= ((int64_t)1 << 22) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) {
                 double share = 0;
                 SP_TRY(spmi_column_scatter(const_cast<sp_tensor *>(A), st, &share));
-                if (share >= 0.5) kernel = 4;
+                // ... and buckets of at least 64 entries on average: the second pass reads them a bucket at a time
+                const double buckets = (double)ceil_div(A->shape[1], (int64_t)kBinPW) * (double)ceil_div(m, (int64_t)kBinRB);
+                if (share >= 0.5) kernel = (double)nnz >= 64.0 * buckets ? 4 : 3;
             }
         }
         if (kernel == 4 && A->tune_spmv == 0) {
