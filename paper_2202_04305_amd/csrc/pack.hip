@@ -735,32 +735,45 @@ __global__ __launch_bounds__(kThreads) void bin_keys_kernel(const int64_t *__res
     keys[e] = (((c >> pshift) * (uint64_t)nrows + (uint64_t)rows[e]) << pshift) | (c & (((uint64_t)1 << pshift) - 1));
 }
 
-// From the sorted keys: the 16-bit coordinates of every entry, and off[b] = first entry of bucket b for every bucket
-// (an entry that opens a new bucket fills in the starts of the empty buckets before it as well; the last entry those
-// after it, up to off[nbuckets] = n).
+// bucket (panel * rowblocks + row block) of a key; *row_out = its row
+__device__ inline int64_t bin_bucket_of(uint64_t key, int pshift, int rshift, const divisor &nrows, int64_t rowblocks, uint64_t *row_out)
+{
+    const uint64_t v = key >> pshift;
+    const uint64_t p = div_by(v, nrows);
+    const uint64_t row = v - p * nrows.d;
+    if (row_out) *row_out = row;
+    return (int64_t)(p * (uint64_t)rowblocks + (row >> rshift));
+}
+
+// From the sorted keys: the 16-bit coordinates of every entry.
 __global__ __launch_bounds__(kThreads) void bin_decode_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int rshift,
-                                                              divisor nrows, int64_t rowblocks, int64_t nbuckets,
-                                                              uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow,
-                                                              int64_t *__restrict__ off)
+                                                              divisor nrows, int64_t rowblocks,
+                                                              uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= n) return;
-    auto bucket_of = [&](uint64_t key, uint64_t *row_out) -> int64_t {
-        const uint64_t v = key >> pshift;
-        const uint64_t p = div_by(v, nrows);
-        const uint64_t row = v - p * nrows.d;
-        if (row_out) *row_out = row;
-        return (int64_t)(p * (uint64_t)rowblocks + (row >> rshift));
-    };
     const uint64_t key = keys[e];
     uint64_t row;
-    const int64_t b = bucket_of(key, &row);
+    (void)bin_bucket_of(key, pshift, rshift, nrows, rowblocks, &row);
     lcol[e] = (uint16_t)(key & (((uint64_t)1 << pshift) - 1));
     lrow[e] = (uint16_t)(row & (((uint64_t)1 << rshift) - 1));
-    const int64_t before = e > 0 ? bucket_of(keys[e - 1], nullptr) : -1;
-    for (int64_t q = before + 1; q <= b; ++q) off[q] = e;
-    if (e == n - 1)
-        for (int64_t q = b + 1; q <= nbuckets; ++q) off[q] = n;
+}
+
+// off[b] = number of entries in buckets before b (the bucket of a key never decreases along the sorted keys), for
+// b = 0 .. nbuckets: a binary search per bucket, whatever the sizes of the buckets are.
+__global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int rshift,
+                                                               divisor nrows, int64_t rowblocks, int64_t nbuckets,
+                                                               int64_t *__restrict__ off)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (b > nbuckets) return;
+    int64_t lo = 0, hi = n;                            // first entry whose bucket is >= b
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (bin_bucket_of(keys[mid], pshift, rshift, nrows, rowblocks, nullptr) < b) lo = mid + 1;
+        else hi = mid;
+    }
+    off[b] = lo;
 }
 
 // Builds and keeps the binned copy of a CSR tensor; no-op when it exists.  Synchronises.  SP_ERR_UNSUPPORTED for other
@@ -810,7 +823,10 @@ sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
         const void *sorted_vals = nullptr;
         SP_TRY(spmi_radix_sort_pairs(keys, vals, vbytes, nnz, key_bits, tmp, st, &sorted_keys, &sorted_vals));
         hipLaunchKernelGGL(bin_decode_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift, rshift,
-                           make_divisor((uint64_t)m), rowblocks, nbuckets, g->lcol, g->lrow, g->off);
+                           make_divisor((uint64_t)m), rowblocks, g->lcol, g->lrow);
+        SP_HIP(hipGetLastError());
+        hipLaunchKernelGGL(bin_offsets_kernel, dim3(blocks_for(nbuckets + 1)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift,
+                           rshift, make_divisor((uint64_t)m), rowblocks, nbuckets, g->off);
         SP_HIP(hipGetLastError());
         SP_HIP(hipMemcpyAsync(g->val, sorted_vals, (size_t)nnz * vbytes, hipMemcpyDeviceToDevice, st));
         SP_HIP(hipStreamSynchronize(st));
