@@ -263,11 +263,13 @@ __global__ __launch_bounds__(kBinThreads) void spmv_bins_multiply_kernel(const V
 
 // Second pass: block = row block.  Its waves take the panels in turn; the products of bucket (panel, row block) are
 // added into the block's slice of y in LDS (atomic adds: the order in which a row's products meet is not fixed), and
-// the slice is written out at the end.  Every row of the row block is written, so y needs no zero fill.
-template <typename VT>
+// the slice is written out at the end.  Every stored row of the row block is written (m of them; rowid[q] is the matrix
+// row of stored row q when not all rows are stored, and the caller has then zeroed the others).
+template <typename CT, typename VT>
 __global__ __launch_bounds__(kBinThreads) void spmv_bins_reduce_kernel(const VT *__restrict__ prod, const uint16_t *__restrict__ lrow,
                                                                        const int64_t *__restrict__ off, int panels, int rowblocks,
-                                                                       int64_t m, VT *__restrict__ y, int64_t ldc, int accumulate)
+                                                                       int64_t m, const CT *__restrict__ rowid, VT *__restrict__ y,
+                                                                       int64_t ldc, int accumulate)
 {
     __shared__ VT ys[kBinRB];
     constexpr int W = kBinThreads / 64, U = 4;
@@ -314,8 +316,11 @@ __global__ __launch_bounds__(kBinThreads) void spmv_bins_reduce_kernel(const VT 
     __syncthreads();
     const int64_t r0 = (int64_t)rb * kBinRB;
     for (int i = threadIdx.x; i < kBinRB; i += kBinThreads) {
-        const int64_t r = r0 + i;
-        if (r < m) y[r * ldc] = accumulate ? y[r * ldc] + ys[i] : ys[i];
+        const int64_t q = r0 + i;                      // stored row; rowid maps it to the matrix row where not all rows are stored
+        if (q < m) {
+            VT *dst = y + (rowid ? (int64_t)rowid[q] : q) * ldc;
+            *dst = accumulate ? *dst + ys[i] : ys[i];
+        }
     }
 }
 
@@ -718,17 +723,19 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             // a large matrix whose gathers are scattered over a large x: no gather should leave the chip's caches.  The
             // binned copy keeps them inside the LDS (measured 103 us against 122 us on the 1M x 1M matrix); where it cannot
             // be built, L2-sized column panels.  Gathers that mostly fall into the line of their predecessor stay as they are.
-            if (kernel == 2 && !dcsr && nnz >= ((int64_t)1 << 22) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) {
+            if (kernel == 2 && nnz >= ((int64_t)1 << 21) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) {
                 double share = 0;
                 SP_TRY(spmi_column_scatter(const_cast<sp_tensor *>(A), st, &share));
-                // ... and buckets of at least 64 entries on average: the second pass reads them a bucket at a time
-                const double buckets = (double)ceil_div(A->shape[1], (int64_t)kBinPW) * (double)ceil_div(m, (int64_t)kBinRB);
-                if (share >= 0.5) kernel = (double)nnz >= 64.0 * buckets ? 4 : 3;
+                // ... and buckets of at least 32 entries on average (the second pass reads them a bucket at a time), in enough
+                // row blocks to give every CU one (the hypersparse 8M x 8M workload has 41: 85 us binned, 73 us streamed)
+                const int64_t rowblocks = ceil_div(nrows, (int64_t)kBinRB);
+                const double buckets = (double)ceil_div(A->shape[1], (int64_t)kBinPW) * (double)rowblocks;
+                if (share >= 0.5) kernel = ((double)nnz >= 32.0 * buckets && rowblocks >= 256) ? 4 : (!dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
             }
         }
         if (kernel == 4 && A->tune_spmv == 0) {
-            const sp_status sb = A->enc.lt[0] == SP_COMPRESSED ? SP_ERR_UNSUPPORTED : spmi_build_bins(const_cast<sp_tensor *>(A), st);
-            if (sb == SP_ERR_UNSUPPORTED) kernel = 3;
+            const sp_status sb = spmi_build_bins(const_cast<sp_tensor *>(A), st);
+            if (sb == SP_ERR_UNSUPPORTED) kernel = (!dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
             else if (sb != SP_OK) return sb;
         }
         if (kernel == 3) {
@@ -767,17 +774,16 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             return SP_OK;
         }
         if (kernel == 4) {
-            if (A->enc.lt[0] == SP_COMPRESSED) return SP_ERR_UNSUPPORTED;
             SP_TRY(spmi_build_bins(const_cast<sp_tensor *>(A), st));          // first use: builds, allocates, synchronises
-            const sp_bins *g = A->bins;
+            const sp_bins *g = A->bins;                                       // over the same stored rows as pos / rowid here
             sp_prof_scope prof(A, st);
             hipLaunchKernelGGL((spmv_bins_multiply_kernel<VT>), dim3((unsigned)(g->panels * g->pieces)), dim3(kBinThreads), 0, st,
                                (const VT *)g->val, (const uint16_t *)g->lcol, (const int64_t *)g->off, g->rowblocks, g->pieces,
                                A->shape[1], B, ldb, (VT *)g->prod);
             SP_HIP(hipGetLastError());
-            hipLaunchKernelGGL((spmv_bins_reduce_kernel<VT>), dim3((unsigned)g->rowblocks), dim3(kBinThreads), 0, st,
+            hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)g->rowblocks), dim3(kBinThreads), 0, st,
                                (const VT *)g->prod, (const uint16_t *)g->lrow, (const int64_t *)g->off, g->panels, g->rowblocks,
-                               m, C, ldc, accumulate);
+                               g->nrows, rowid, C, ldc, accumulate);
             SP_HIP(hipGetLastError());
             return SP_OK;
         }

@@ -724,15 +724,22 @@ static void free_bins(sp_tensor *t)
     t->bins = nullptr;
 }
 
-// key = ((panel * nrows + row) << pshift) | column inside the panel: sorting by it gives panel-major buckets with rows,
-// then columns, ascending inside.
-__global__ __launch_bounds__(kThreads) void bin_keys_kernel(const int64_t *__restrict__ rows, const int64_t *__restrict__ cols, int64_t n,
-                                                            int pshift, int64_t nrows, uint64_t *__restrict__ keys)
+// key = ((panel * nrows + stored row) << pshift) | column inside the panel: sorting by it gives panel-major buckets with
+// rows, then columns, ascending inside.  The stored row of entry e is found in pos by binary search.
+template <typename PT, typename CT>
+__global__ __launch_bounds__(kThreads) void bin_keys_kernel(const PT *__restrict__ pos, int64_t nrows, const CT *__restrict__ crd, int64_t n,
+                                                            int pshift, uint64_t *__restrict__ keys)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= n) return;
-    const uint64_t c = (uint64_t)cols[e];
-    keys[e] = (((c >> pshift) * (uint64_t)nrows + (uint64_t)rows[e]) << pshift) | (c & (((uint64_t)1 << pshift) - 1));
+    int64_t lo = 0, hi = nrows - 1;                    // last row q with pos[q] <= e (empty rows before it share that pos: the last one wins)
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo + 1) / 2;
+        if ((int64_t)pos[mid] <= e) lo = mid;
+        else hi = mid - 1;
+    }
+    const uint64_t c = (uint64_t)crd[e];
+    keys[e] = (((c >> pshift) * (uint64_t)nrows + (uint64_t)lo) << pshift) | (c & (((uint64_t)1 << pshift) - 1));
 }
 
 // bucket (panel * rowblocks + row block) of a key; *row_out = its row
@@ -776,16 +783,21 @@ __global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *_
     off[b] = lo;
 }
 
-// Builds and keeps the binned copy of a CSR tensor; no-op when it exists.  Synchronises.  SP_ERR_UNSUPPORTED for other
+// Builds and keeps the binned copy of a row-major tensor with a compressed innermost level; no-op when it exists.
+// Synchronises.  Rows are counted among the stored ones (all of them for CSR; the compressed outer level's for DCSR;
+// the non-empty ones where the tensor carries their list), the caller maps them back.  SP_ERR_UNSUPPORTED for other
 // encodings, for an empty tensor and when the bucket table would be larger than the tensor itself.
 sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
 {
     if (A->bins) return SP_OK;
-    if (A->enc.rank != 2 || A->enc.lt[0] != SP_DENSE || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
-    const int64_t m = A->shape[0], n = A->shape[1], nnz = A->nvalues;
+    if (A->enc.rank != 2 || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
+    const bool listed = A->enc.lt[0] == SP_DENSE && A->nz_pos;
+    const void *pos = listed ? A->nz_pos : A->pos[1];
+    const int64_t m = listed ? A->nz_rows : A->npos[1] - 1;          // stored rows
+    const int64_t n = A->shape[1], nnz = A->ncrd[1];
     const int pshift = kSpmiBinPanelShift, rshift = kSpmiBinRowShift;
     const int64_t panels = ceil_div(n, (int64_t)1 << pshift), rowblocks = ceil_div(m, (int64_t)1 << rshift);
-    if (nnz < 1 || panels > 0x7fffffff || rowblocks > 0x7fffffff) return SP_ERR_UNSUPPORTED;
+    if (nnz < 1 || m < 1 || panels > 0x7fffffff || rowblocks > 0x7fffffff) return SP_ERR_UNSUPPORTED;
     const unsigned __int128 nb128 = (unsigned __int128)panels * (unsigned __int128)rowblocks;
     if (nb128 > (unsigned __int128)nnz + 4096) return SP_ERR_UNSUPPORTED;
     const int64_t nbuckets = (int64_t)nb128;
@@ -796,7 +808,7 @@ sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
     sp_mem mem{A->alloc, A->free_, A->ctx};
     sp_bins *g = new sp_bins();
     A->bins = g;                                         // owned from here on: free_bins() releases whatever was allocated
-    g->nnz = nnz; g->panels = (int)panels; g->rowblocks = (int)rowblocks;
+    g->nnz = nnz; g->nrows = m; g->panels = (int)panels; g->rowblocks = (int)rowblocks;
     // pieces per panel in the first pass: about 32768 entries each, so that loading the slice of x stays a small part
     const int64_t per_panel = nnz / panels;
     g->pieces = (int)(per_panel / 32768 < 1 ? 1 : per_panel / 32768 > 64 ? 64 : per_panel / 32768);
@@ -809,19 +821,20 @@ sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
     sp_status status = (g->val && g->prod && g->lcol && g->lrow && g->off) ? SP_OK : SP_ERR_ALLOC;
     auto build = [&]() -> sp_status {
         sp_scratch tmp(mem);
-        int64_t *rows = (int64_t *)tmp.get((size_t)nnz * 8);
-        int64_t *cols = (int64_t *)tmp.get((size_t)nnz * 8);
-        void *vals = tmp.get((size_t)nnz * 8);
         uint64_t *keys = (uint64_t *)tmp.get((size_t)nnz * 8);
-        if (!rows || !cols || !vals || !keys) return SP_ERR_ALLOC;
-        int64_t *coords[2] = {rows, cols};
-        SP_TRY(sp_unpack(A, coords, vals, st));
-        hipLaunchKernelGGL(bin_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const int64_t *)rows, (const int64_t *)cols, nnz,
-                           pshift, m, keys);
+        if (!keys) return SP_ERR_ALLOC;
+#define SPMI_BIN_KEYS(PT, CT)                                                                                                 \
+    hipLaunchKernelGGL((bin_keys_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const PT *)pos, m, (const CT *)A->crd[1], \
+                       nnz, pshift, keys)
+        if (A->enc.pw == 32 && A->enc.cw == 32) SPMI_BIN_KEYS(int32_t, int32_t);
+        else if (A->enc.pw == 32) SPMI_BIN_KEYS(int32_t, int64_t);
+        else if (A->enc.cw == 32) SPMI_BIN_KEYS(int64_t, int32_t);
+        else SPMI_BIN_KEYS(int64_t, int64_t);
+#undef SPMI_BIN_KEYS
         SP_HIP(hipGetLastError());
         uint64_t *sorted_keys = nullptr;
         const void *sorted_vals = nullptr;
-        SP_TRY(spmi_radix_sort_pairs(keys, vals, vbytes, nnz, key_bits, tmp, st, &sorted_keys, &sorted_vals));
+        SP_TRY(spmi_radix_sort_pairs(keys, A->values, vbytes, nnz, key_bits, tmp, st, &sorted_keys, &sorted_vals));
         hipLaunchKernelGGL(bin_decode_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift, rshift,
                            make_divisor((uint64_t)m), rowblocks, g->lcol, g->lrow);
         SP_HIP(hipGetLastError());

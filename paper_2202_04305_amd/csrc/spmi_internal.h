@@ -35,7 +35,7 @@ struct sp_segments {
 };
 
 // Binned copy for SpMV with a large x and scattered columns: the stored entries regrouped into buckets (column panel
-// of 2^pshift columns, row block of 2^rshift rows), panel-major, rows ascending inside a bucket.  Every entry keeps
+// of 2^pshift columns, row block of 2^rshift stored rows), panel-major, rows ascending inside a bucket.  Every entry keeps
 // its value, its column inside the panel and its row inside the row block in 16 bits each.  The product runs in two
 // streaming passes: one multiplies a panel's entries by the panel's slice of x held in LDS and writes the products in
 // place (`prod`), the other adds a row block's products up in an LDS slice of y.  No gather ever leaves the LDS.
@@ -43,9 +43,9 @@ struct sp_bins {
     void *val = nullptr;              // DEVICE value-typed[nnz], bucket order
     void *prod = nullptr;             // DEVICE value-typed[nnz]: the products of the running call
     uint16_t *lcol = nullptr;         // DEVICE [nnz]: column - panel * 2^pshift
-    uint16_t *lrow = nullptr;         // DEVICE [nnz]: row - rowblock * 2^rshift
+    uint16_t *lrow = nullptr;         // DEVICE [nnz]: stored row - rowblock * 2^rshift
     int64_t *off = nullptr;           // DEVICE [panels * rowblocks + 1]: first entry of bucket panel * rowblocks + rowblock
-    int64_t nnz = 0;
+    int64_t nnz = 0, nrows = 0;       // entries, stored rows
     int panels = 0, rowblocks = 0, pieces = 0;
 };
 

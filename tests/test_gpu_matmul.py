@@ -146,11 +146,18 @@ def test_csr_spmv_binned_strides_and_refusals():
     ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, x)
     assert_product_close(ys[:, 0].contiguous(), ref, mag, np.float64, "strided binned spmv")
     assert torch.all(ys[:, 1] == -7.0)
-    say("case binned, not CSR / empty / bucket table larger than the tensor")
+    say("case binned, a huge and mostly empty matrix: only the non-empty rows are binned")
+    T = gpu_pack((0, 1), (0, 1), (1 << 22, 1 << 22), [w.rows, w.cols], w.vals)
+    sp.sp_tensor_tune(T, sp.SP_TUNE_SPMV_KERNEL, 4)
+    xb = prng.uniform_pm1(5, 9, 1 << 22)
+    yb = torch.full((1 << 22,), float("nan"), dtype=torch.float64, device=DEV)
+    sp.sp_matmul(T, dev(xb), yb)
+    ref, mag = oracle.matmul_coo((1 << 22, 1 << 22), w.rows, w.cols, w.vals, xb.reshape(-1, 1))
+    assert_product_close(yb, ref, mag, np.float64, "huge and mostly empty")
+    say("case binned, empty / bucket table larger than the tensor")
     for lt, shape, coords, vals in [
-        ((1, 1), w.shape, [w.rows, w.cols], w.vals),
         ((0, 1), (50, 60), [np.zeros(0, dtype=np.int64)] * 2, np.zeros(0)),
-        ((0, 1), (1 << 22, 1 << 22), [w.rows, w.cols], w.vals),
+        ((0, 1), (3000, 1 << 26), [w.rows[:200], w.cols[:200]], w.vals[:200]),     # 8192 column panels for 200 entries
     ]:
         T = gpu_pack(lt, (0, 1), shape, coords, vals)
         sp.sp_tensor_tune(T, sp.SP_TUNE_SPMV_KERNEL, 4)
@@ -330,6 +337,28 @@ def test_leading_dimensions():
         ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, B[:, :1].copy())
         assert_product_close(ys[:, 0].contiguous(), ref, mag, np.float64, "strided spmv")
         assert torch.all(ys[:, 1] == -7.0)
+
+
+@pytest.mark.parametrize("lt", [(1, 1), (0, 1)])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_spmv_binned_over_stored_rows(lt, dtype):
+    """Kernel 4 where not every row is stored: DCSR, and CSR that carries the list of its non-empty rows.  Rows are
+    binned by their position among the stored ones; the others must come out as zero (overwrite) or untouched (accumulate)."""
+    w = W.cfg4_hypersparse_dcsr(1 << 18, 1 << 18)
+    w.vals = w.vals.astype(dtype)
+    w.dtype = dtype
+    say("case binned over stored rows", lt, dtype.__name__, w.stats)
+    A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], w.vals, 32, 64 if dtype is np.float32 else 32)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 4)
+    x = w.dense_operand(1).astype(dtype)
+    y, ref, mag = run(A, w, x)
+    assert_product_close(y, ref, mag, dtype, "binned, stored rows")
+    assert torch.all(y[torch.from_numpy(mag[:, 0] == 0).to(DEV)] == 0)
+    y0 = prng.uniform_pm1(5, 7, w.shape[0]).astype(dtype)
+    y, ref, mag = run(A, w, x, accumulate=True, C0=y0)
+    assert_product_close(y, ref, mag, dtype, "binned, stored rows, accumulate")
+    untouched = torch.from_numpy(np.bincount(w.rows, minlength=w.shape[0]) == 0).to(DEV)
+    assert torch.equal(y[untouched, 0], dev(y0)[untouched])
 
 
 @pytest.mark.parametrize("kernel", [1, 2])
