@@ -88,8 +88,15 @@ void sp_tensor_free(sp_tensor *t);
  *   C  DEVICE, row-major m x N with leading dimension ldc >= N, A's dtype.
  *   accumulate = 0: C is overwritten (rows of A without stored entries become zero);
  *   accumulate = 1: C += A.B and rows without stored entries are not touched.
- * Enqueues on `stream` and returns without synchronising.  B and C must not overlap.
- * Summation order inside a row is unspecified (floating-point reassociation, Section 5.2). */
+ * Enqueues on `stream` and returns without synchronising, except that the first product of a
+ * tensor may first build tables or a regrouped copy of the entries that later products reuse
+ * (it then allocates through the tensor's allocator and synchronises `stream` once; the handle
+ * keeps what was built until sp_tensor_free).  Because of that cache a handle must not be used
+ * by two host threads at the same time, and the scratch buffers it holds are shared by all
+ * products on it: products of one tensor that run concurrently on different streams race.
+ * B and C must not overlap.  Summation order inside a row is unspecified (floating-point
+ * reassociation, Section 5.2); whether it is the same from call to call depends on the kernel
+ * (see SP_TUNE_SPMV_KERNEL). */
 sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                     void *C, int64_t ldc, int accumulate, void *stream);
 
