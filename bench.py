@@ -341,8 +341,12 @@ def bench_spmspm(args, torch, sp, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "SpMSpM C=A.B, all CSR f64 (Sections 4.4, 6.2): n x n uniform random A and B of density 0.01, n = %d, "
                                "%d pairs -> %d stored entries of C, pos/crd %d-bit" % (n, top["pairs"], top["entries_c"], args.width),
-                   "kernel": "spgemm_expand_kernel + radix sort + sum_runs_kernel + level build" if args.spgemm_kernel == 1 else
-                             "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_kernel", "small": bool(args.small)},
+                   "kernel": {1: "spgemm_expand_kernel + radix sort + sum_runs_kernel + level build",
+                              2: "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_panels_kernel (4 waves per row)",
+                              3: "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_kernel (1 wave per row)",
+                              5: "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_entries_kernel (16 waves per row, order of the additions not fixed)",
+                              }.get(args.spgemm_kernel, "spgemm_ws_count_kernel + scan + spgemm_ws_numeric_wide_kernel (16 waves per row; 4 below 8192 columns)"),
+                   "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "kernel": "whole sp_spgemm call (allocation and host synchronisations included)",
                      "kernel_us": top["ms"] * 1e3, "algorithmic_bytes": top["bytes"]},
@@ -369,7 +373,7 @@ def main():
     ap.add_argument("--kernel", type=int, default=0, help="SpMV kernel: 0 auto, 1 lanes-per-row, 2 streaming, 3 column-segmented streaming, 4 binned by column panel and row block")
     ap.add_argument("--csc-mode", type=int, default=0, help="column-major tensors: 0 auto, 1 scatter with atomics, 2 cached transpose")
     ap.add_argument("--spmm-kernel", type=int, default=0, help="SpMM kernel: 0 auto, 1 one column per lane, 2 16-byte loads with a wave per row, 3 16-byte loads cut by entries")
-    ap.add_argument("--spgemm-kernel", type=int, default=0, help="SpMSpM: 0 auto, 1 pairs through the storage builder, 2 LDS workspace per row")
+    ap.add_argument("--spgemm-kernel", type=int, default=0, help="SpMSpM: 0 auto, 1 pairs through the storage builder, 2 / 3 / 4 LDS workspace per row with 4 / 1 / 16 waves, 5 = 16 waves dealing out the entries (fastest, not bit-reproducible)")
     ap.add_argument("--accumulate", action="store_true", help="C += A.B instead of C = A.B")
     ap.add_argument("--small", action="store_true", help="scaled-down matrix (for quick checks)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")

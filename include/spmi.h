@@ -147,7 +147,7 @@ sp_status sp_mttkrp(const sp_tensor *B, const void *C, int64_t ldc, const void *
  * that the tensor builds on first use and keeps); a B with a dense inner level gives SP_ERR_UNSUPPORTED (convert
  * first).  *C is a new tensor m x n under `encC` with A's dtype and allocator: it stores every (i,j) for which a pair of
  * stored entries A[i,k], B[k,j] exists, whatever the sum comes to, and each sum runs over k in A's storage order, so
- * the result is the same bits on every call.  Synchronises like sp_pack.  Errors: NULL, RANK, SHAPE (inner sizes
+ * the result is the same bits on every call (unless SP_TUNE_SPGEMM_KERNEL 5 was asked for).  Synchronises like sp_pack.  Errors: NULL, RANK, SHAPE (inner sizes
  * differ), DTYPE (A and B differ), TOO_LARGE (2^31 or more pairs), WIDTH (C does not fit encC's widths), ALLOC, HIP. */
 sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_encoding *encC, void *stream, sp_tensor **C);
 
@@ -194,7 +194,12 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *                        workspace (CSR / DCSR operands and a CSR result with one pos / crd width, rows of C that
  *                        fit the LDS; SP_ERR_UNSUPPORTED otherwise), four waves per row over a column-panel copy
  *                        of B that B builds on first use and keeps, 3 = the same workspace with one wave per row
- *                        and no copy of B
+ *                        and no copy of B, 4 = the same with sixteen waves per row (sixteen column panels; results
+ *                        of 1024 columns or more, else as 2; the automatic choice from 8192 columns on), 5 = sixteen
+ *                        waves per row with the entries of the row of A dealt out to them instead of the columns:
+ *                        the fastest (0.38 ms against 0.53 ms on the 8192 x 8192 product of Section 6.2), but the
+ *                        waves add into one workspace in an order that depends on timing, so the values of C agree
+ *                        from call to call only to rounding; never chosen automatically
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
 enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4, SP_TUNE_SPGEMM_KERNEL = 5 };
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);

@@ -130,7 +130,7 @@ extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
         if (t->transposed) return sp_tensor_tune(t->transposed, key, value);
         return SP_OK;
     case SP_TUNE_SPGEMM_KERNEL:
-        if (value < 0 || value > 3) return SP_ERR_UNSUPPORTED;
+        if (value < 0 || value > 5) return SP_ERR_UNSUPPORTED;
         t->tune_spgemm = (int)value;
         return SP_OK;
     case SP_TUNE_SPMM_KERNEL:

@@ -411,6 +411,245 @@ __global__ __launch_bounds__(64 * kPanelWaves) void spgemm_ws_numeric_panels_ker
     }
 }
 
+// Sixteen waves per row of A, for wide rows of C: the same ownership of columns (wave w works on panel w of the
+// column-panel copy of B and on its own part of the workspace, so the additions to an element keep a fixed order) with
+// four times the waves in flight per CU.  A wave loads 64 entries of the row of A at once (one per lane, with the bounds
+// of the selected row of B inside the wave's panel) and hands them out, 32 at a time through a small LDS table, to its
+// eight groups of eight lanes, four entries per group in flight: a group walks its segment of the row of B eight
+// entries at a time.  Measured on the 8192 x 8192 product of density 0.01 (348 us; 478 us with four waves): leaving the
+// adds out changes nothing, the kernel waits for its many short loads (a panel's share of a row of B is five entries);
+// 75 us of it are clearing the workspace, 50 us writing the row out.
+constexpr int kWideWaves = 16, kWideGroup = 8, kWideStage = 32;
+constexpr int64_t kWideMinColumns = 8192;               // from this many columns of C on the sixteen-wave kernel is the default
+template <typename VT>
+struct wide_entry {
+    uint32_t b0, b1;      // the segment of the selected row of B inside the wave's panel (offsets into the panel copy)
+    VT a;                 // the value of the entry of A
+};
+
+template <typename PT, typename CT, typename VT>
+__global__ __launch_bounds__(64 * kWideWaves) void spgemm_ws_numeric_wide_kernel(
+    const PT *__restrict__ apos, const CT *__restrict__ acrd, const VT *__restrict__ aval, const CT *__restrict__ arowid, int64_t arows,
+    const PT *__restrict__ spos, const CT *__restrict__ scrd, const VT *__restrict__ sval, int64_t kdim, int shift, int64_t n,
+    const PT *__restrict__ cpos, CT *__restrict__ ccrd, VT *__restrict__ cval)
+{
+    constexpr int G = kWideGroup, NG = 64 / G, U = 4;
+    static_assert(NG * U == kWideStage, "one pass over the table hands out all of it");
+    extern __shared__ unsigned char ws_raw[];
+    __shared__ wide_entry<VT> table[kWideWaves][kWideStage];
+    VT *acc = (VT *)ws_raw;
+    uint32_t *bits = (uint32_t *)(ws_raw + (size_t)n * sizeof(VT));
+    const int lane = threadIdx.x & 63, g = lane / G, gl = lane % G;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t words = (n + 31) >> 5;
+    // The block keeps its workspace over all the rows it takes (r = blockIdx.x, + gridDim.x, ...): cleared once here, and
+    // after every row each wave clears exactly what the row has touched in its columns while it writes them out.
+    for (int64_t j = threadIdx.x; j < n; j += 64 * kWideWaves) acc[j] = (VT)0;
+    for (int64_t w = threadIdx.x; w < words; w += 64 * kWideWaves) bits[w] = 0u;
+    __syncthreads();
+    const int64_t col_lo = (int64_t)wave << shift;                 // this wave's columns: [col_lo, col_hi), a multiple of 64 wide
+    const int64_t col_hi = col_lo + ((int64_t)1 << shift) < n ? col_lo + ((int64_t)1 << shift) : n;
+    const PT *wpos = spos + (int64_t)wave * kdim;                  // the pos entries of this wave's panel
+    wide_entry<VT> *mine = table[wave];
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int64_t r = blockIdx.x; r < arows; r += gridDim.x) {
+        const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
+        if (a1 == a0) continue;                                    // the whole block
+        if (col_lo < n) {
+            for (int64_t g0 = a0; g0 < a1; g0 += 64) {
+                const int64_t e = g0 + lane;
+                wide_entry<VT> w;
+                w.b0 = 0; w.b1 = 0; w.a = (VT)0;                   // lanes past the row hold empty segments
+                if (e < a1) {
+                    const int64_t k = (int64_t)acrd[e];
+                    w.a = aval[e];
+                    w.b0 = (uint32_t)wpos[k];
+                    w.b1 = (uint32_t)wpos[k + 1];
+                }
+                const int cnt = (int)(a1 - g0 < 64 ? a1 - g0 : 64);   // wave-uniform
+                for (int s0 = 0; s0 < cnt; s0 += kWideStage) {
+                    if (lane >= s0 && lane < s0 + kWideStage) mine[lane - s0] = w;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    wide_entry<VT> seg[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) seg[u] = mine[u * NG + g];
+                    uint32_t j[U];
+                    VT p[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {                  // the first eight entries of each segment: all loads first
+                        const uint32_t t = seg[u].b0 + (uint32_t)gl;
+                        j[u] = 0xffffffffu;
+                        p[u] = (VT)0;
+                        if (t < seg[u].b1) { j[u] = (uint32_t)scrd[t]; p[u] = seg[u].a * sval[t]; }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        if (j[u] != 0xffffffffu) {
+                            atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
+                            atomicAdd(&acc[j[u]], p[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)                    // what is left of longer segments
+                        for (uint32_t t = seg[u].b0 + (uint32_t)(G + gl); __any(t < seg[u].b1); t += G)
+                            if (t < seg[u].b1) {
+                                const uint32_t jj = (uint32_t)scrd[t];
+                                atomicOr(&bits[jj >> 5], 1u << (jj & 31));
+                                atomicAdd(&acc[jj], seg[u].a * sval[t]);
+                            }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the table is rewritten in the next pass
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+            }
+        }
+        __syncthreads();
+        // the compress step for this wave's columns; its first output follows the set bits of the columns before
+        if (col_lo < n) {
+            int before_cols = 0;
+            for (int64_t w = lane; w < (col_lo >> 5); w += 64) before_cols += __popc(bits[w]);
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) before_cols += __shfl_xor(before_cols, d, 64);
+            const int64_t row_at = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r] + before_cols;
+            CT *crow = ccrd + row_at;
+            VT *vrow = cval + row_at;
+            uint32_t base = 0;
+            for (uint32_t j0 = (uint32_t)col_lo; j0 < (uint32_t)col_hi; j0 += 64) {
+                const uint32_t j = j0 + lane;
+                const bool set = j < (uint32_t)col_hi && ((bits[j >> 5] >> (j & 31)) & 1u);
+                const unsigned long long mask = __ballot(set);
+                if (set) {
+                    const uint32_t o = base + (uint32_t)__popcll(mask & below);
+                    crow[o] = (CT)j;
+                    vrow[o] = acc[j];
+                    acc[j] = (VT)0;                                // clean for the block's next row
+                }
+                base += (uint32_t)__popcll(mask);
+            }
+        }
+        __syncthreads();                                           // every wave has counted the bits before its columns
+        if (col_lo < n)
+            for (int64_t w = (col_lo >> 5) + lane; w < ((col_hi + 31) >> 5); w += 64) bits[w] = 0u;
+        // no barrier needed here: until the next row's barrier only this wave touches these words again
+    }
+}
+
+// Sixteen waves per row of A with the ENTRIES of the row dealt out instead of the columns: wave w takes entries
+// w, w + 16, ... of the row of A, a half-wave walks one selected row of B, 32 entries at a time with contiguous loads
+// (no column-panel copy of B, a sixth of the load requests of the kernel above).  All waves add into the one
+// workspace, so the order in which the products of one element of C meet depends on timing: results agree to rounding,
+// not bit for bit.  Persistent blocks and the clean-as-you-go workspace as above; wave w writes out columns
+// [w * n / 16 rounded to 64, ...).
+template <typename PT, typename CT, typename VT>
+__global__ __launch_bounds__(64 * kWideWaves) void spgemm_ws_numeric_entries_kernel(
+    const PT *__restrict__ apos, const CT *__restrict__ acrd, const VT *__restrict__ aval, const CT *__restrict__ arowid, int64_t arows,
+    const PT *__restrict__ bpos, const CT *__restrict__ bcrd, const VT *__restrict__ bval, int64_t n,
+    const PT *__restrict__ cpos, CT *__restrict__ ccrd, VT *__restrict__ cval)
+{
+    constexpr int W = kWideWaves, U = 2;
+    extern __shared__ unsigned char ws_raw[];
+    __shared__ wide_entry<VT> table[W][kWideStage];
+    VT *acc = (VT *)ws_raw;
+    uint32_t *bits = (uint32_t *)(ws_raw + (size_t)n * sizeof(VT));
+    const int lane = threadIdx.x & 63, half = lane >> 5, hl = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t words = (n + 31) >> 5;
+    for (int64_t j = threadIdx.x; j < n; j += 64 * W) acc[j] = (VT)0;
+    for (int64_t w = threadIdx.x; w < words; w += 64 * W) bits[w] = 0u;
+    __syncthreads();
+    const int64_t span = ((n + W - 1) / W + 63) & ~(int64_t)63;     // columns a wave writes out: a multiple of 64
+    const int64_t col_lo = (int64_t)wave * span < n ? (int64_t)wave * span : n;
+    const int64_t col_hi = col_lo + span < n ? col_lo + span : n;
+    wide_entry<VT> *mine = table[wave];
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int64_t r = blockIdx.x; r < arows; r += gridDim.x) {
+        const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
+        if (a1 == a0) continue;                                    // the whole block
+        for (int64_t g0 = a0 + wave; g0 < a1; g0 += kWideStage * W) {      // 32 of this wave's entries at a time, one per lane of the lower half
+            const int64_t e = g0 + (int64_t)lane * W;
+            wide_entry<VT> w;
+            w.b0 = 0; w.b1 = 0; w.a = (VT)0;                       // lanes past the row hold empty rows of B
+            if (lane < kWideStage && e < a1) {
+                const int64_t k = (int64_t)acrd[e];
+                w.a = aval[e];
+                w.b0 = (uint32_t)bpos[k];
+                w.b1 = (uint32_t)bpos[k + 1];
+            }
+            if (lane < kWideStage) mine[lane] = w;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int64_t mine_left = (a1 - g0 + W - 1) / W;       // this wave's entries from g0 on
+            const int cnt = (int)(mine_left < kWideStage ? mine_left : kWideStage);   // wave-uniform
+            for (int s0 = 0; s0 < cnt; s0 += 2 * U) {              // U rows of B per half-wave in flight
+                wide_entry<VT> seg[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int idx = s0 + 2 * u + half;
+                    seg[u] = mine[idx < kWideStage ? idx : kWideStage - 1];
+                    if (idx >= cnt) seg[u].b1 = seg[u].b0;
+                }
+                uint32_t j[U];
+                VT p[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {                      // the first 32 entries of each row: all loads first
+                    const uint32_t t = seg[u].b0 + (uint32_t)hl;
+                    j[u] = 0xffffffffu;
+                    p[u] = (VT)0;
+                    if (t < seg[u].b1) { j[u] = (uint32_t)bcrd[t]; p[u] = seg[u].a * bval[t]; }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (j[u] != 0xffffffffu) {
+                        atomicOr(&bits[j[u] >> 5], 1u << (j[u] & 31));
+                        atomicAdd(&acc[j[u]], p[u]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)                        // the rest of longer rows
+                    for (uint32_t t = seg[u].b0 + (uint32_t)(32 + hl); __any(t < seg[u].b1); t += 32)
+                        if (t < seg[u].b1) {
+                            const uint32_t jj = (uint32_t)bcrd[t];
+                            atomicOr(&bits[jj >> 5], 1u << (jj & 31));
+                            atomicAdd(&acc[jj], seg[u].a * bval[t]);
+                        }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the table is rewritten in the next batch
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        __syncthreads();
+        if (col_lo < col_hi) {
+            int before_cols = 0;
+            for (int64_t w = lane; w < (col_lo >> 5); w += 64) before_cols += __popc(bits[w]);
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) before_cols += __shfl_xor(before_cols, d, 64);
+            const int64_t row_at = (int64_t)cpos[arowid ? (int64_t)arowid[r] : r] + before_cols;
+            CT *crow = ccrd + row_at;
+            VT *vrow = cval + row_at;
+            uint32_t base = 0;
+            for (uint32_t j0 = (uint32_t)col_lo; j0 < (uint32_t)col_hi; j0 += 64) {
+                const uint32_t j = j0 + lane;
+                const bool set = j < (uint32_t)col_hi && ((bits[j >> 5] >> (j & 31)) & 1u);
+                const unsigned long long mask = __ballot(set);
+                if (set) {
+                    const uint32_t o = base + (uint32_t)__popcll(mask & below);
+                    crow[o] = (CT)j;
+                    vrow[o] = acc[j];
+                    acc[j] = (VT)0;                                // clean for the block's next row
+                }
+                base += (uint32_t)__popcll(mask);
+            }
+        }
+        __syncthreads();                                           // every wave has counted the bits before its columns
+        if (col_lo < col_hi)
+            for (int64_t w = (col_lo >> 5) + lane; w < ((col_hi + 31) >> 5); w += 64) bits[w] = 0u;
+        __syncthreads();                                           // any wave may mark any column of the next row
+    }
+}
+
 template <typename PT, typename CT, typename VT>
 sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *encC, hipStream_t st, sp_tensor **out)
 {
@@ -438,6 +677,8 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             const size_t bits_bytes = (size_t)((n + 31) / 32) * 4;
             const size_t ws_bytes = (size_t)n * sizeof(VT) + bits_bytes;
             const bool work = arows > 0 && A->nvalues > 0 && Br->nvalues > 0 && n > 0;
+            // sixteen waves per row for wide results (tune value 4 asks for them from 1024 columns on), else four
+            const bool wide = A->tune_spgemm == 4 ? n >= kWideWaves * 64 : (A->tune_spgemm == 0 && n >= kWideMinColumns);
             if (work) {
                 hipLaunchKernelGGL((spgemm_ws_count_kernel<PT, CT>), dim3((unsigned)arows), dim3(64), bits_bytes, st, (const PT *)A->pos[1],
                                    (const CT *)A->crd[1], arowid, (const PT *)Br->pos[1], (const CT *)Br->crd[1], n, (PT *)t->pos[1]);
@@ -463,13 +704,37 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             // four waves per row when the column-panel copy of B can be had (it is built on the first product with this B)
             const sp_tensor *Bseg = nullptr;
             int pshift = 0;
-            if (work && nnzc > 0 && A->tune_spgemm != 3 && n >= 4 * 64) {
-                while (((int64_t)kPanelWaves << pshift) < n) ++pshift;      // the narrowest power of two with at most four panels
+            const int pwaves = wide ? kWideWaves : kPanelWaves;
+            if (work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
+                while (((int64_t)pwaves << pshift) < n) ++pshift;           // the narrowest power of two with at most that many panels
                 sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(Br), 1, (int64_t)1 << pshift, st);
-                if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= kPanelWaves) Bseg = Br->segments->seg;
+                if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= pwaves) Bseg = Br->segments->seg;
                 else if (sb != SP_OK && sb != SP_ERR_UNSUPPORTED) { status = sb; break; }
             }
-            if (Bseg) {
+            if (work && nnzc > 0 && A->tune_spgemm == 5) {
+                auto kernel = spgemm_ws_numeric_entries_kernel<PT, CT, VT>;
+                if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
+                    status = SP_ERR_HIP;
+                    break;
+                }
+                const unsigned nblocks = (unsigned)(arows < 512 ? arows : 512);
+                hipLaunchKernelGGL(kernel, dim3(nblocks), dim3(64 * kWideWaves), ws_bytes, st, (const PT *)A->pos[1], (const CT *)A->crd[1],
+                                   (const VT *)A->values, arowid, arows, (const PT *)Br->pos[1], (const CT *)Br->crd[1], (const VT *)Br->values,
+                                   n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            } else if (Bseg && wide) {
+                auto kernel = spgemm_ws_numeric_wide_kernel<PT, CT, VT>;
+                if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
+                    status = SP_ERR_HIP;
+                    break;
+                }
+                // two blocks fit a CU's LDS: that many blocks, each taking every 512th row
+                const unsigned wide_blocks = (unsigned)(arows < 512 ? arows : 512);
+                hipLaunchKernelGGL(kernel, dim3(wide_blocks), dim3(64 * kWideWaves), ws_bytes, st, (const PT *)A->pos[1], (const CT *)A->crd[1],
+                                   (const VT *)A->values, arowid, arows, (const PT *)Bseg->pos[1], (const CT *)Bseg->crd[1], (const VT *)Bseg->values,
+                                   Br->shape[0], pshift, n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            } else if (Bseg) {
                 auto kernel = spgemm_ws_numeric_panels_kernel<PT, CT, VT, 8>;
                 if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
                     status = SP_ERR_HIP;
@@ -533,7 +798,7 @@ extern "C" sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_
     }
     const int pw = Br->enc.pw, cw = Br->enc.cw;
     const bool fits = workspace_fits(A, Br, encC);
-    if ((A->tune_spgemm == 2 || A->tune_spgemm == 3) && !fits) return SP_ERR_UNSUPPORTED;
+    if (A->tune_spgemm >= 2 && !fits) return SP_ERR_UNSUPPORTED;
     if (fits && A->tune_spgemm != 1) {
 #define SPMI_WS(PT, CT)                                                                                        \
     return A->dtype == SP_F64 ? spgemm_workspace_t<PT, CT, double>(A, Br, encC, st, C) : spgemm_workspace_t<PT, CT, float>(A, Br, encC, st, C)
