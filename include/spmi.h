@@ -194,10 +194,10 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *                        workspace (CSR / DCSR operands and a CSR result with one pos / crd width, rows of C that
  *                        fit the LDS; SP_ERR_UNSUPPORTED otherwise), four waves per row over a column-panel copy
  *                        of B that B builds on first use and keeps, 3 = the same workspace with one wave per row
- *                        and no copy of B, 4 = the same with sixteen waves per row (sixteen column panels; results
+ *                        and no copy of B, 4 = the same with sixteen waves per row (sixteen column panels, B read in place; results
  *                        of 1024 columns or more, else as 2; the automatic choice from 8192 columns on), 5 = sixteen
  *                        waves per row with the entries of the row of A dealt out to them instead of the columns:
- *                        the fastest (0.38 ms against 0.53 ms on the 8192 x 8192 product of Section 6.2), but the
+ *                        the fastest (0.38 ms against 0.45 ms on the 8192 x 8192 product of Section 6.2), but the
  *                        waves add into one workspace in an order that depends on timing, so the values of C agree
  *                        from call to call only to rounding; never chosen automatically
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */

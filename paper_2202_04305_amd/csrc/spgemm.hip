@@ -411,9 +411,32 @@ __global__ __launch_bounds__(64 * kPanelWaves) void spgemm_ws_numeric_panels_ker
     }
 }
 
-// Sixteen waves per row of A, for wide rows of C: the same ownership of columns (wave w works on panel w of the
-// column-panel copy of B and on its own part of the workspace, so the additions to an element keep a fixed order) with
-// four times the waves in flight per CU.  A wave loads 64 entries of the row of A at once (one per lane, with the bounds
+// bounds[k * (panels + 1) + p] = position of the first entry of row k of B whose column is >= p << shift (p = panels: the
+// end of the row): where each column panel's share of the row starts, the row staying where it is.
+template <typename PT, typename CT>
+__global__ __launch_bounds__(256) void spgemm_panel_bounds_kernel(const PT *__restrict__ bpos, const CT *__restrict__ bcrd, int64_t kdim,
+                                                                  int shift, int panels, uint32_t *__restrict__ bounds)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= kdim * (panels + 1)) return;
+    const int64_t k = i / (panels + 1);
+    const int p = (int)(i - k * (panels + 1));
+    int64_t lo = (int64_t)bpos[k], hi = (int64_t)bpos[k + 1];
+    const int64_t first = (int64_t)p << shift;
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)bcrd[mid] < first) lo = mid + 1;
+        else hi = mid;
+    }
+    bounds[i] = (uint32_t)lo;
+}
+
+// Sixteen waves per row of A, for wide rows of C: the same ownership of columns (wave w works on the columns of panel
+// w and on its own part of the workspace, so the additions to an element keep a fixed order) with four times the waves
+// in flight per CU.  B is read where it is, through the table of panel bounds inside each row (above): the sixteen
+// shares of a row of B are neighbours in memory and the block's waves ask for them at about the same time, so a line
+// is fetched once (with the regrouped copy that the four-wave kernel reads, every 40-byte share cost its own lines:
+// 1.83 GB past the L2 per product).  A wave loads 64 entries of the row of A at once (one per lane, with the bounds
 // of the selected row of B inside the wave's panel) and hands them out, 32 at a time through a small LDS table, to its
 // eight groups of eight lanes, four entries per group in flight: a group walks its segment of the row of B eight
 // entries at a time.  Measured on the 8192 x 8192 product of density 0.01 (348 us; 478 us with four waves): leaving the
@@ -430,7 +453,7 @@ struct wide_entry {
 template <typename PT, typename CT, typename VT>
 __global__ __launch_bounds__(64 * kWideWaves) void spgemm_ws_numeric_wide_kernel(
     const PT *__restrict__ apos, const CT *__restrict__ acrd, const VT *__restrict__ aval, const CT *__restrict__ arowid, int64_t arows,
-    const PT *__restrict__ spos, const CT *__restrict__ scrd, const VT *__restrict__ sval, int64_t kdim, int shift, int64_t n,
+    const uint32_t *__restrict__ bounds, const CT *__restrict__ scrd, const VT *__restrict__ sval, int shift, int64_t n,
     const PT *__restrict__ cpos, CT *__restrict__ ccrd, VT *__restrict__ cval)
 {
     constexpr int G = kWideGroup, NG = 64 / G, U = 4;
@@ -449,7 +472,7 @@ __global__ __launch_bounds__(64 * kWideWaves) void spgemm_ws_numeric_wide_kernel
     __syncthreads();
     const int64_t col_lo = (int64_t)wave << shift;                 // this wave's columns: [col_lo, col_hi), a multiple of 64 wide
     const int64_t col_hi = col_lo + ((int64_t)1 << shift) < n ? col_lo + ((int64_t)1 << shift) : n;
-    const PT *wpos = spos + (int64_t)wave * kdim;                  // the pos entries of this wave's panel
+    const uint32_t *wbounds = bounds + wave;                       // this wave's panel in every row's kWideWaves + 1 bounds
     wide_entry<VT> *mine = table[wave];
     const unsigned long long below = (1ull << lane) - 1ull;
     for (int64_t r = blockIdx.x; r < arows; r += gridDim.x) {
@@ -463,8 +486,8 @@ __global__ __launch_bounds__(64 * kWideWaves) void spgemm_ws_numeric_wide_kernel
                 if (e < a1) {
                     const int64_t k = (int64_t)acrd[e];
                     w.a = aval[e];
-                    w.b0 = (uint32_t)wpos[k];
-                    w.b1 = (uint32_t)wpos[k + 1];
+                    w.b0 = wbounds[k * (kWideWaves + 1)];
+                    w.b1 = wbounds[k * (kWideWaves + 1) + 1];
                 }
                 const int cnt = (int)(a1 - g0 < 64 ? a1 - g0 : 64);   // wave-uniform
                 for (int s0 = 0; s0 < cnt; s0 += kWideStage) {
@@ -705,7 +728,16 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             const sp_tensor *Bseg = nullptr;
             int pshift = 0;
             const int pwaves = wide ? kWideWaves : kPanelWaves;
-            if (work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
+            uint32_t *bounds = nullptr;
+            if (work && nnzc > 0 && wide) {
+                while (((int64_t)kWideWaves << pshift) < n) ++pshift;       // the narrowest power of two with at most sixteen panels
+                const int64_t kdim = Br->shape[0], nb = kdim * (kWideWaves + 1);
+                bounds = (uint32_t *)tmp.get((size_t)nb * 4);
+                if (!bounds) { status = SP_ERR_ALLOC; break; }
+                hipLaunchKernelGGL((spgemm_panel_bounds_kernel<PT, CT>), dim3((unsigned)ceil_div(nb, 256)), dim3(256), 0, st, (const PT *)Br->pos[1],
+                                   (const CT *)Br->crd[1], kdim, pshift, kWideWaves, bounds);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            } else if (work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
                 while (((int64_t)pwaves << pshift) < n) ++pshift;           // the narrowest power of two with at most that many panels
                 sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(Br), 1, (int64_t)1 << pshift, st);
                 if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= pwaves) Bseg = Br->segments->seg;
@@ -722,7 +754,7 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                                    (const VT *)A->values, arowid, arows, (const PT *)Br->pos[1], (const CT *)Br->crd[1], (const VT *)Br->values,
                                    n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
-            } else if (Bseg && wide) {
+            } else if (bounds) {
                 auto kernel = spgemm_ws_numeric_wide_kernel<PT, CT, VT>;
                 if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ws_bytes) != hipSuccess) {
                     status = SP_ERR_HIP;
@@ -731,8 +763,8 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                 // two blocks fit a CU's LDS: that many blocks, each taking every 512th row
                 const unsigned wide_blocks = (unsigned)(arows < 512 ? arows : 512);
                 hipLaunchKernelGGL(kernel, dim3(wide_blocks), dim3(64 * kWideWaves), ws_bytes, st, (const PT *)A->pos[1], (const CT *)A->crd[1],
-                                   (const VT *)A->values, arowid, arows, (const PT *)Bseg->pos[1], (const CT *)Bseg->crd[1], (const VT *)Bseg->values,
-                                   Br->shape[0], pshift, n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
+                                   (const VT *)A->values, arowid, arows, (const uint32_t *)bounds, (const CT *)Br->crd[1], (const VT *)Br->values,
+                                   pshift, n, (const PT *)t->pos[1], (CT *)t->crd[1], (VT *)t->values);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             } else if (Bseg) {
                 auto kernel = spgemm_ws_numeric_panels_kernel<PT, CT, VT, 8>;
