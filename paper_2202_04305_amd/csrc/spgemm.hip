@@ -117,19 +117,23 @@ sp_status spgemm_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *e
 // ---- a row of C at a time in an LDS workspace ---------------------------------------------------------------------
 constexpr int64_t kWorkspaceBytes = 72 * 1024;          // dense row of C + its bit map; two such waves fit a CU's LDS
 
-// block = one wave = one stored row r of A.  count[i] = number of distinct columns the row reaches.
+// block = one stored row r of A, four waves that take the selected rows of B in turn (marking a column is an OR: the order
+// does not matter).  count[i] = number of distinct columns the row reaches.
+constexpr int kCountWaves = 4;
 template <typename PT, typename CT>
-__global__ __launch_bounds__(64) void spgemm_ws_count_kernel(const PT *__restrict__ apos, const CT *__restrict__ acrd,
-                                                             const CT *__restrict__ arowid, const PT *__restrict__ bpos,
-                                                             const CT *__restrict__ bcrd, int64_t n, PT *__restrict__ count)
+__global__ __launch_bounds__(64 * kCountWaves) void spgemm_ws_count_kernel(const PT *__restrict__ apos, const CT *__restrict__ acrd,
+                                                                           const CT *__restrict__ arowid, const PT *__restrict__ bpos,
+                                                                           const CT *__restrict__ bcrd, int64_t n, PT *__restrict__ count)
 {
     extern __shared__ uint32_t ws_bits[];
-    const int lane = threadIdx.x;
+    __shared__ int partial[kCountWaves];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t r = blockIdx.x;
     const int64_t a0 = (int64_t)apos[r], a1 = (int64_t)apos[r + 1];
-    if (a1 == a0) return;
+    if (a1 == a0) return;                                          // the whole block
     const int64_t words = (n + 31) >> 5;
-    for (int64_t w = lane; w < words; w += 64) ws_bits[w] = 0u;
+    for (int64_t w = threadIdx.x; w < words; w += 64 * kCountWaves) ws_bits[w] = 0u;
     __syncthreads();
     for (int64_t g = a0; g < a1; g += 64) {
         const int64_t e = g + lane;
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(64) void spgemm_ws_count_kernel(const PT *__restric
             b1 = (int64_t)bpos[k + 1];
         }
         const int cnt = (int)(a1 - g < 64 ? a1 - g : 64);
-        for (int x = 0; x < cnt; ++x) {                            // wave-uniform
+        for (int x = wave; x < cnt; x += kCountWaves) {            // wave-uniform
             const int64_t s0 = __shfl(b0, x, 64), s1 = __shfl(b1, x, 64);
             for (int64_t t = s0 + lane; t < s1; t += 64) {
                 const uint32_t j = (uint32_t)bcrd[t];
@@ -150,10 +154,16 @@ __global__ __launch_bounds__(64) void spgemm_ws_count_kernel(const PT *__restric
     }
     __syncthreads();
     int c = 0;
-    for (int64_t w = lane; w < words; w += 64) c += __popc(ws_bits[w]);
+    for (int64_t w = threadIdx.x; w < words; w += 64 * kCountWaves) c += __popc(ws_bits[w]);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
-    if (lane == 0) count[arowid ? (int64_t)arowid[r] : r] = (PT)c;
+    if (lane == 0) partial[wave] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < kCountWaves; ++w) total += partial[w];
+        count[arowid ? (int64_t)arowid[r] : r] = (PT)total;
+    }
 }
 
 // block = one wave = one stored row r of A; LDS: n values, the n-bit map, then a short list of chunk descriptors.
@@ -703,7 +713,7 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             // sixteen waves per row for wide results (tune value 4 asks for them from 1024 columns on), else four
             const bool wide = A->tune_spgemm == 4 ? n >= kWideWaves * 64 : (A->tune_spgemm == 0 && n >= kWideMinColumns);
             if (work) {
-                hipLaunchKernelGGL((spgemm_ws_count_kernel<PT, CT>), dim3((unsigned)arows), dim3(64), bits_bytes, st, (const PT *)A->pos[1],
+                hipLaunchKernelGGL((spgemm_ws_count_kernel<PT, CT>), dim3((unsigned)arows), dim3(64 * kCountWaves), bits_bytes, st, (const PT *)A->pos[1],
                                    (const CT *)A->crd[1], arowid, (const PT *)Br->pos[1], (const CT *)Br->crd[1], n, (PT *)t->pos[1]);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
