@@ -205,15 +205,19 @@ constexpr int kBinRB = 1 << kSpmiBinRowShift;
 // prod[e] = val[e] * x[panel * PW + lcol[e]], 16 bytes of values per lane and load.
 template <typename VT>
 __global__ __launch_bounds__(kBinThreads) void spmv_bins_multiply_kernel(const VT *__restrict__ val, const uint16_t *__restrict__ lcol,
-                                                                         const int64_t *__restrict__ off, int rowblocks, int pieces,
-                                                                         int64_t n, const VT *__restrict__ x, int64_t ldb,
+                                                                         const int64_t *__restrict__ off, int panels, int rowblocks,
+                                                                         int pieces, int64_t n, const VT *__restrict__ x, int64_t ldb,
                                                                          VT *__restrict__ prod)
 {
     constexpr int V = 16 / sizeof(VT);
     typedef VT vec_t __attribute__((ext_vector_type(V)));
     typedef uint16_t idx_t __attribute__((ext_vector_type(V)));
     __shared__ VT xs[kBinPW];
-    const int p = blockIdx.x / pieces, q = blockIdx.x % pieces;
+    // blocks go to the eight XCDs in turn: the pieces of one panel are given to blocks b, b + 8, b + 16, ... so that they
+    // share an L2 and the panel's slice of x is fetched from memory once, not once per piece
+    const int grp = 8 * pieces;
+    const int p = (int)(blockIdx.x / grp) * 8 + (int)(blockIdx.x % 8), q = (int)(blockIdx.x / 8) % pieces;
+    if (p >= panels) return;                           // whole block (the panel count is rounded up to eight)
     const int64_t pa = off[(int64_t)p * rowblocks], pb = off[(int64_t)(p + 1) * rowblocks];
     auto cut = [&](int k) -> int64_t {                 // piece boundaries: multiples of V inside the panel
         if (k <= 0) return pa;
@@ -777,8 +781,8 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             SP_TRY(spmi_build_bins(const_cast<sp_tensor *>(A), st));          // first use: builds, allocates, synchronises
             const sp_bins *g = A->bins;                                       // over the same stored rows as pos / rowid here
             sp_prof_scope prof(A, st);
-            hipLaunchKernelGGL((spmv_bins_multiply_kernel<VT>), dim3((unsigned)(g->panels * g->pieces)), dim3(kBinThreads), 0, st,
-                               (const VT *)g->val, (const uint16_t *)g->lcol, (const int64_t *)g->off, g->rowblocks, g->pieces,
+            hipLaunchKernelGGL((spmv_bins_multiply_kernel<VT>), dim3((unsigned)(ceil_div(g->panels, 8) * 8 * g->pieces)), dim3(kBinThreads), 0, st,
+                               (const VT *)g->val, (const uint16_t *)g->lcol, (const int64_t *)g->off, g->panels, g->rowblocks, g->pieces,
                                A->shape[1], B, ldb, (VT *)g->prod);
             SP_HIP(hipGetLastError());
             hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)g->rowblocks), dim3(kBinThreads), 0, st,
