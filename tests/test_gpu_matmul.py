@@ -133,6 +133,33 @@ def test_csr_spmv_binned(name, maker, dtype):
         assert np.array_equal(y.cpu().numpy(), ref)
 
 
+def test_csr_spmv_binned_random_shapes():
+    """Seeded random shapes and fills for kernel 4: from a single bucket to hundreds, buckets that are empty, last panel and
+    last row block of every raggedness, CSR and DCSR, both value types; small integers, so every sum is exact."""
+    rng = np.random.default_rng(4305)
+    for it in range(24):
+        m = int(rng.integers(1, 9000))
+        n = int(rng.integers(1, 70000))
+        nnz = int(min(m * n, rng.integers(1, 60000)))
+        lt = (int(rng.integers(0, 2)), 1)
+        dtype = np.float64 if it % 2 == 0 else np.float32
+        w = W.uniform_random(m, n, nnz, dtype=dtype, seed=W.BASE_SEED + 700 + it)
+        vals = prng.small_ints(11, it, nnz, dtype=dtype)
+        x = prng.small_ints(12, it, n, dtype=dtype).reshape(n, 1)
+        say("case binned random", it, (m, n), nnz, lt, dtype.__name__)
+        A = gpu_pack(lt, (0, 1), w.shape, [w.rows, w.cols], vals, 32, 32)
+        sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 4)
+        ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, vals, x)
+        y = torch.full((m,), float("nan"), dtype=A.dtype, device=DEV)
+        try:
+            sp.sp_matmul(A, dev(x[:, 0].copy()), y)
+        except sp.SpError as e:                      # more buckets than entries (+ 4096): refused, not wrong
+            assert e.code == oracle.ERR_UNSUPPORTED
+            assert -(-n // 8192) * -(-m // 2048) > nnz + 4096 or lt[0] == 1
+            continue
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), ref[:, 0])
+
+
 def test_csr_spmv_binned_strides_and_refusals():
     w = W.cfg2_powerlaw_csr(3000, 20000, mean=12.0, cap=900)
     A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
