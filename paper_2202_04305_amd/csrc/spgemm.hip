@@ -717,6 +717,19 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
                                    (const CT *)A->crd[1], arowid, (const PT *)Br->pos[1], (const CT *)Br->crd[1], n, (PT *)t->pos[1]);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
+            // the sixteen-wave kernel's table of panel bounds does not depend on the counts: enqueued here, ahead of the
+            // synchronisation below, so that nothing but the allocation of C stands between that and the numeric kernel
+            int pshift = 0;
+            uint32_t *bounds = nullptr;
+            if (work && wide) {
+                while (((int64_t)kWideWaves << pshift) < n) ++pshift;       // the narrowest power of two with at most sixteen panels
+                const int64_t kdim = Br->shape[0], nb = kdim * (kWideWaves + 1);
+                bounds = (uint32_t *)tmp.get((size_t)nb * 4);
+                if (!bounds) { status = SP_ERR_ALLOC; break; }
+                hipLaunchKernelGGL((spgemm_panel_bounds_kernel<PT, CT>), dim3((unsigned)ceil_div(nb, 256)), dim3(256), 0, st, (const PT *)Br->pos[1],
+                                   (const CT *)Br->crd[1], kdim, pshift, kWideWaves, bounds);
+                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            }
             if ((status = spmi_exclusive_scan(t->pos[1], m + 1, (int)sizeof(PT) * 8, tmp, st)) != SP_OK) break;
             // the longest row of C (the products choose kernels by it) comes back with the total, in one synchronisation
             if ((status = spmi_max_segment_async(t->pos[1], (int)sizeof(PT) * 8, m, (unsigned long long *)(flags + 4), st)) != SP_OK) break;
@@ -736,18 +749,9 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             if (!t->crd[1] || !t->values) { status = SP_ERR_ALLOC; break; }
             // four waves per row when the column-panel copy of B can be had (it is built on the first product with this B)
             const sp_tensor *Bseg = nullptr;
-            int pshift = 0;
-            const int pwaves = wide ? kWideWaves : kPanelWaves;
-            uint32_t *bounds = nullptr;
-            if (work && nnzc > 0 && wide) {
-                while (((int64_t)kWideWaves << pshift) < n) ++pshift;       // the narrowest power of two with at most sixteen panels
-                const int64_t kdim = Br->shape[0], nb = kdim * (kWideWaves + 1);
-                bounds = (uint32_t *)tmp.get((size_t)nb * 4);
-                if (!bounds) { status = SP_ERR_ALLOC; break; }
-                hipLaunchKernelGGL((spgemm_panel_bounds_kernel<PT, CT>), dim3((unsigned)ceil_div(nb, 256)), dim3(256), 0, st, (const PT *)Br->pos[1],
-                                   (const CT *)Br->crd[1], kdim, pshift, kWideWaves, bounds);
-                if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
-            } else if (work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
+            const int pwaves = kPanelWaves;
+            if (nnzc == 0) bounds = nullptr;
+            if (!bounds && work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
                 while (((int64_t)pwaves << pshift) < n) ++pshift;           // the narrowest power of two with at most that many panels
                 sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(Br), 1, (int64_t)1 << pshift, st);
                 if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= pwaves) Bseg = Br->segments->seg;
