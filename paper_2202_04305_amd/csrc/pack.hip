@@ -299,17 +299,20 @@ __global__ __launch_bounds__(kThreads) void mark_children_kernel(const uint64_t 
 // compressed level, step 2: write crd, count children per parent (one add per run end, one
 // subtract per run start: integer atomics, so the result does not depend on their order),
 // and hand each entry its child position.  child_excl = exclusive scan of the marks, or
-// nullptr on the innermost level, where every entry is its own child.
+// nullptr on the innermost level, where every entry is its own child.  dup_flags (may be null): the duplicate check of the
+// sorted keys, done here on the way when the builder has not run it yet.
 template <typename PT, typename CT>
 __global__ __launch_bounds__(kThreads) void emit_level_kernel(const uint64_t *__restrict__ keys, int64_t nnz, divisor stride,
                                                               divisor size, const uint32_t *__restrict__ child_excl,
                                                               const uint64_t *__restrict__ parent_in, uint64_t *__restrict__ parent_out,
-                                                              PT *__restrict__ cnt, CT *__restrict__ crd)
+                                                              PT *__restrict__ cnt, CT *__restrict__ crd, int *__restrict__ dup_flags)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= nnz) return;
-    const uint64_t pre = div_by(keys[e], stride);
-    const uint64_t pre_before = e > 0 ? div_by(keys[e - 1], stride) : 0;
+    const uint64_t key = keys[e], key_before = e > 0 ? keys[e - 1] : 0;
+    if (dup_flags && e > 0 && key == key_before) atomicOr(&dup_flags[1], 1);      // an entry given twice (see check_duplicates_kernel)
+    const uint64_t pre = div_by(key, stride);
+    const uint64_t pre_before = e > 0 ? div_by(key_before, stride) : 0;
     const bool first = (e == 0) || (pre_before != pre);
     const uint64_t child = child_excl ? (uint64_t)child_excl[e] + (first ? 1u : 0u) - 1u : (uint64_t)e;
     const uint64_t up = div_by(pre, size);
@@ -885,10 +888,10 @@ extern "C" void sp_tensor_free(sp_tensor *t)
 
 template <typename PT, typename CT>
 static sp_status launch_emit(const uint64_t *keys, int64_t nnz, divisor stride, divisor size, const uint32_t *child_excl,
-                             const uint64_t *pin, uint64_t *pout, void *cnt, void *crd, hipStream_t st)
+                             const uint64_t *pin, uint64_t *pout, void *cnt, void *crd, int *dup_flags, hipStream_t st)
 {
     hipLaunchKernelGGL((emit_level_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, keys, nnz, stride, size, child_excl,
-                       pin, pout, (PT *)cnt, (CT *)crd);
+                       pin, pout, (PT *)cnt, (CT *)crd, dup_flags);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -905,7 +908,7 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
     if (want_max) {
         unsigned long long *mx = (unsigned long long *)(flags + 4);
         const int64_t nseg = t->npos[rank - 1] - 1;
-        const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
+        const unsigned seg_blocks = blocks_for(nseg) < 256u ? blocks_for(nseg) : 256u;      // one atomic per block, all to one address: few blocks
         if (enc->pw == 32)
             hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[rank - 1], nseg, mx);
         else
@@ -935,7 +938,7 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
 sp_status spmi_max_segment_async(const void *pos, int pw, int64_t nseg, unsigned long long *out, hipStream_t st)
 {
     if (nseg <= 0) return SP_OK;
-    const unsigned seg_blocks = blocks_for(nseg) < 2048u ? blocks_for(nseg) : 2048u;
+    const unsigned seg_blocks = blocks_for(nseg) < 256u ? blocks_for(nseg) : 256u;      // one atomic per block, all to one address: few blocks
     if (pw == 32) hipLaunchKernelGGL(max_segment_kernel<int32_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int32_t *)pos, nseg, out);
     else hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)pos, nseg, out);
     SP_HIP(hipGetLastError());
@@ -995,16 +998,23 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
     if (!child) return SP_ERR_ALLOC;
     if (nnz > 0) {
         SP_TRY(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st, &keys, &payload));
-        if (!sum_duplicates) {
-            hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
-            SP_HIP(hipGetLastError());
-        }
     }
+    // The duplicate check rides along with the first compressed level's kernel (it reads the same neighbouring keys); it
+    // runs on its own only where no such kernel comes before its result is needed.
+    bool dup_pending = !sum_duplicates && nnz > 0;
+    auto run_dup_check = [&]() -> sp_status {
+        if (!dup_pending) return SP_OK;
+        dup_pending = false;
+        hipLaunchKernelGGL(check_duplicates_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)keys, nnz, flags);
+        SP_HIP(hipGetLastError());
+        return SP_OK;
+    };
     // The input checks (a coordinate out of range, an entry given twice) come back to the host with the last read-back
     // of the build, not here: a host synchronisation in the middle costs a tenth of a small pack.  Every kernel below stays
     // in bounds on such input (bad coordinates were replaced by 0 when the keys were made; equal keys only make equal
     // writes).  input_error() reads them early where another error would otherwise be reported in their place.
     auto input_error = [&]() -> sp_status {
+        SP_TRY(run_dup_check());
         int h[2] = {0, 0};
         if (hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return SP_ERR_HIP;
         return h[0] ? SP_ERR_COORD_RANGE : h[1] ? SP_ERR_DUPLICATE : SP_OK;
@@ -1098,10 +1108,11 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
             if (!t->pos[l] || !t->crd[l]) return SP_ERR_ALLOC;
             SP_TRY(spmi_fill_zero(t->pos[l], pbytes, st));
             if (nnz > 0) {
-                if (enc->pw == 32 && enc->cw == 32) SP_TRY((launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
-                else if (enc->pw == 32) SP_TRY((launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
-                else if (enc->cw == 32) SP_TRY((launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
-                else SP_TRY((launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], st)));
+                if (enc->pw == 32 && enc->cw == 32) SP_TRY((launch_emit<int32_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], dup_pending ? flags : nullptr, st)));
+                else if (enc->pw == 32) SP_TRY((launch_emit<int32_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], dup_pending ? flags : nullptr, st)));
+                else if (enc->cw == 32) SP_TRY((launch_emit<int64_t, int32_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], dup_pending ? flags : nullptr, st)));
+                else SP_TRY((launch_emit<int64_t, int64_t>(keys, nnz, stride, size, child_excl, pin, pout, t->pos[l], t->crd[l], dup_pending ? flags : nullptr, st)));
+                dup_pending = false;
             }
             SP_TRY(spmi_exclusive_scan(t->pos[l], P + 1, enc->pw, tmp, st));
             P = nchild;
@@ -1161,6 +1172,7 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
             SP_HIP(hipGetLastError());
         }
     }
+    SP_TRY(run_dup_check());
     int hf[2] = {0, 0};
     SP_TRY(spmi_finish_tensor(t, flags, tmp, st, sum_duplicates ? nullptr : hf));
     if (hf[0]) return SP_ERR_COORD_RANGE;
