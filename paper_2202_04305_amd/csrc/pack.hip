@@ -108,10 +108,22 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint64_t *__
     h[threadIdx.x] = 0;
     __syncthreads();
     const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
-#pragma unroll 4
-    for (int r = 0; r < kSortRounds; ++r) {
-        const int64_t i = tile0 + (int64_t)r * kThreads + threadIdx.x;
-        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    if (tile0 + kSortTile <= n) {                      // a whole tile: two keys per lane and load, all loads of a thread first
+        typedef unsigned long long u2 __attribute__((ext_vector_type(2)));
+        const u2 *__restrict__ kk = (const u2 *)(keys + tile0);
+        u2 k[kSortRounds / 2];
+#pragma unroll
+        for (int r = 0; r < kSortRounds / 2; ++r) k[r] = kk[r * kThreads + threadIdx.x];
+#pragma unroll
+        for (int r = 0; r < kSortRounds / 2; ++r) {
+            atomicAdd(&h[(k[r][0] >> shift) & 255u], 1u);
+            atomicAdd(&h[(k[r][1] >> shift) & 255u], 1u);
+        }
+    } else {
+        for (int r = 0; r < kSortRounds; ++r) {
+            const int64_t i = tile0 + (int64_t)r * kThreads + threadIdx.x;
+            if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+        }
     }
     __syncthreads();
     hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];   // digit-major: one scan gives global offsets
