@@ -576,7 +576,18 @@ __global__ __launch_bounds__(kThreads) void max_span_kernel(const int32_t *__res
     if ((threadIdx.x & 63) == 0 && span) atomicMax(out, span);
 }
 
-static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
+// The list of non-empty rows is built in two steps so that its questions to the device can share one synchronisation
+// with whatever else the caller reads back: enqueue (marks, their scan, the longest run of rows in one window; the
+// answers land in the probe once the stream has been synchronised), then decide (and compact, when worth it).
+struct nonempty_probe {
+    uint32_t *mark = nullptr;
+    int64_t nrows = 0;
+    uint32_t last_mark = 0, last_excl = 0;
+    unsigned long long span = 0;
+    bool active = false;
+};
+
+static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st, nonempty_probe &q)
 {
     if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
     const int64_t nrows = t->npos[1] - 1;
@@ -588,11 +599,9 @@ static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t 
     else
         hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
     SP_HIP(hipGetLastError());
-    uint32_t last_mark = 0, last_excl = 0;
-    unsigned long long span = 0;
-    SP_HIP(hipMemcpyAsync(&last_mark, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    SP_HIP(hipMemcpyAsync(&q.last_mark, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
     SP_TRY(spmi_exclusive_scan(mark, nrows, 32, tmp, st));
-    SP_HIP(hipMemcpyAsync(&last_excl, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    SP_HIP(hipMemcpyAsync(&q.last_excl, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
     if (t->rowblocks.start) {
         unsigned long long *dspan = (unsigned long long *)tmp.get(64);
         if (!dspan) return SP_ERR_ALLOC;
@@ -600,21 +609,31 @@ static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t 
         hipLaunchKernelGGL(max_span_kernel, dim3(blocks_for(t->rowblocks.nblocks)), dim3(kThreads), 0, st, (const int32_t *)t->rowblocks.start,
                            t->rowblocks.nblocks, dspan);
         SP_HIP(hipGetLastError());
-        SP_HIP(hipMemcpyAsync(&span, dspan, 8, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipMemcpyAsync(&q.span, dspan, 8, hipMemcpyDeviceToHost, st));
     }
-    SP_HIP(hipStreamSynchronize(st));
-    const int64_t nz = (int64_t)last_excl + last_mark;
+    q.mark = mark; q.nrows = nrows; q.active = true;
+    return SP_OK;
+}
+
+// after the stream has been synchronised; *launched = kernels were enqueued
+static sp_status nonempty_decide(sp_tensor *t, hipStream_t st, const nonempty_probe &q, bool *launched)
+{
+    *launched = false;
+    if (!q.active) return SP_OK;
+    const int64_t nrows = q.nrows;
+    const int64_t nz = (int64_t)q.last_excl + q.last_mark;
     // not worth it when at least half of the rows hold something, unless one window of the streaming kernels would have to walk
     // over a very long run of empty rows all by itself
-    if (nz * 2 > nrows && span < 65536) return SP_OK;
+    if (nz * 2 > nrows && q.span < 65536) return SP_OK;
     sp_mem mem{t->alloc, t->free_, t->ctx};
     const int ps = t->enc.pw / 8, cs = t->enc.cw / 8;
     void *rid = mem.get(pad16((size_t)(nz > 0 ? nz : 1) * cs));
     void *npos = mem.get(pad16((size_t)(nz + 1) * ps));
     if (!rid || !npos) { mem.put(rid); mem.put(npos); return SP_ERR_ALLOC; }
+    *launched = true;
 #define SPMI_COMPACT(PT, CT)                                                                                                  \
     hipLaunchKernelGGL((compact_rows_kernel<PT, CT>), dim3(blocks_for(nrows + 1)), dim3(kThreads), 0, st, (const PT *)t->pos[1], nrows, \
-                       (const uint32_t *)mark, nz, (CT *)rid, (PT *)npos)
+                       (const uint32_t *)q.mark, nz, (CT *)rid, (PT *)npos)
     if (t->enc.pw == 32 && t->enc.cw == 32) SPMI_COMPACT(int32_t, int32_t);
     else if (t->enc.pw == 32) SPMI_COMPACT(int32_t, int64_t);
     else if (t->enc.cw == 32) SPMI_COMPACT(int64_t, int32_t);
@@ -625,6 +644,16 @@ static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t 
     if (s != SP_OK) { mem.put(rid); mem.put(npos); if (e != hipSuccess) g_last_hip_error = (int)e; return s; }
     t->nz_rowid = rid; t->nz_pos = npos; t->nz_rows = nz;
     return SP_OK;
+}
+
+static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
+{
+    nonempty_probe q;
+    SP_TRY(nonempty_enqueue(t, tmp, st, q));
+    if (!q.active) return SP_OK;
+    SP_HIP(hipStreamSynchronize(st));
+    bool launched = false;
+    return nonempty_decide(t, st, q, &launched);
 }
 
 // Column-segmented copy of a CSR tensor (see sp_segments): entries keyed by (panel, row, column) and packed
@@ -927,22 +956,25 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
             hipLaunchKernelGGL(max_segment_kernel<int64_t>, dim3(seg_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[rank - 1], nseg, mx);
         SP_HIP(hipGetLastError());
     }
-    if (want_max || input_flags) {
-        int h[6] = {0, 0, 0, 0, 0, 0};
-        SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
-        SP_HIP(hipStreamSynchronize(st));
-        if (input_flags) {
-            input_flags[0] = h[0];
-            input_flags[1] = h[1];
-            if (h[0] || h[1]) return SP_OK;
-        }
-        unsigned long long hmx = 0;
-        memcpy(&hmx, &h[4], 8);
-        if (want_max) t->max_segment = (int64_t)hmx;
-    }
+    // everything that can be enqueued before the host has to look at an answer: the row blocks and the questions of the
+    // non-empty-rows list (all in bounds whatever the input checks say), then one synchronisation for all read-backs
     SP_TRY(spmi_build_rowblocks(t, st));
-    SP_TRY(build_nonempty_rows(t, tmp, st));
+    nonempty_probe q;
+    SP_TRY(nonempty_enqueue(t, tmp, st, q));
+    int h[6] = {0, 0, 0, 0, 0, 0};
+    if (want_max || input_flags) SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
+    if (input_flags) {
+        input_flags[0] = h[0];
+        input_flags[1] = h[1];
+        if (h[0] || h[1]) return SP_OK;
+    }
+    unsigned long long hmx = 0;
+    memcpy(&hmx, &h[4], 8);
+    if (want_max) t->max_segment = (int64_t)hmx;
+    bool launched = false;
+    SP_TRY(nonempty_decide(t, st, q, &launched));
+    if (launched) SP_HIP(hipStreamSynchronize(st));
     return SP_OK;
 }
 
