@@ -585,9 +585,15 @@ struct nonempty_probe {
     uint32_t last_mark = 0, last_excl = 0;
     unsigned long long span = 0;
     bool active = false;
+    // the answers come back inside the builder's 64-byte flags block (one copy to the host for everything):
+    // ints 8 and 9 = the last mark and the last exclusive count, ints 10-11 = the longest run as a 64-bit value
+    void take(const int *h) { last_mark = (uint32_t)h[8]; last_excl = (uint32_t)h[9]; memcpy(&span, &h[10], 8); }
 };
 
-static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st, nonempty_probe &q)
+__global__ void copy_word_kernel(const uint32_t *__restrict__ src, int *__restrict__ dst) { *dst = (int)*src; }
+
+// flags: the 64 zeroed device bytes of the build (see nonempty_probe for the slots used here)
+static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st, int *flags, nonempty_probe &q)
 {
     if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
     const int64_t nrows = t->npos[1] - 1;
@@ -599,17 +605,15 @@ static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st,
     else
         hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
     SP_HIP(hipGetLastError());
-    SP_HIP(hipMemcpyAsync(&q.last_mark, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(1), 0, st, (const uint32_t *)(mark + (nrows - 1)), flags + 8);   // the scan overwrites the marks
+    SP_HIP(hipGetLastError());
     SP_TRY(spmi_exclusive_scan(mark, nrows, 32, tmp, st));
-    SP_HIP(hipMemcpyAsync(&q.last_excl, mark + (nrows - 1), 4, hipMemcpyDeviceToHost, st));
+    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(1), 0, st, (const uint32_t *)(mark + (nrows - 1)), flags + 9);
+    SP_HIP(hipGetLastError());
     if (t->rowblocks.start) {
-        unsigned long long *dspan = (unsigned long long *)tmp.get(64);
-        if (!dspan) return SP_ERR_ALLOC;
-        SP_TRY(spmi_fill_zero(dspan, 64, st));
         hipLaunchKernelGGL(max_span_kernel, dim3(blocks_for(t->rowblocks.nblocks)), dim3(kThreads), 0, st, (const int32_t *)t->rowblocks.start,
-                           t->rowblocks.nblocks, dspan);
+                           t->rowblocks.nblocks, (unsigned long long *)(flags + 10));
         SP_HIP(hipGetLastError());
-        SP_HIP(hipMemcpyAsync(&q.span, dspan, 8, hipMemcpyDeviceToHost, st));
     }
     q.mark = mark; q.nrows = nrows; q.active = true;
     return SP_OK;
@@ -648,10 +652,16 @@ static sp_status nonempty_decide(sp_tensor *t, hipStream_t st, const nonempty_pr
 
 static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
 {
+    int *flags = (int *)tmp.get(64);
+    if (!flags) return SP_ERR_ALLOC;
+    SP_TRY(spmi_fill_zero(flags, 64, st));
     nonempty_probe q;
-    SP_TRY(nonempty_enqueue(t, tmp, st, q));
+    SP_TRY(nonempty_enqueue(t, tmp, st, flags, q));
     if (!q.active) return SP_OK;
+    int h[16];
+    SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
+    q.take(h);
     bool launched = false;
     return nonempty_decide(t, st, q, &launched);
 }
@@ -960,10 +970,11 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
     // non-empty-rows list (all in bounds whatever the input checks say), then one synchronisation for all read-backs
     SP_TRY(spmi_build_rowblocks(t, st));
     nonempty_probe q;
-    SP_TRY(nonempty_enqueue(t, tmp, st, q));
-    int h[6] = {0, 0, 0, 0, 0, 0};
-    if (want_max || input_flags) SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
+    SP_TRY(nonempty_enqueue(t, tmp, st, flags, q));
+    int h[16] = {0};
+    if (want_max || input_flags || q.active) SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
+    q.take(h);
     if (input_flags) {
         input_flags[0] = h[0];
         input_flags[1] = h[1];
