@@ -117,6 +117,11 @@ sp_status spgemm_t(const sp_tensor *A, const sp_tensor *Br, const sp_encoding *e
 // ---- a row of C at a time in an LDS workspace ---------------------------------------------------------------------
 constexpr int64_t kWorkspaceBytes = 72 * 1024;          // dense row of C + its bit map; two such waves fit a CU's LDS
 
+// *out = the last entry of a scanned pos array (the number of stored entries), sign-extended: a 32-bit count that wrapped
+// stays negative
+template <typename PT>
+__global__ void spgemm_last_pos_kernel(const PT *__restrict__ last, long long *__restrict__ out) { *out = (long long)*last; }
+
 // block = one stored row r of A, four waves that take the selected rows of B in turn (marking a column is an OR: the order
 // does not matter).  count[i] = number of distinct columns the row reaches.
 constexpr int kCountWaves = 4;
@@ -733,13 +738,14 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             if ((status = spmi_exclusive_scan(t->pos[1], m + 1, (int)sizeof(PT) * 8, tmp, st)) != SP_OK) break;
             // the longest row of C (the products choose kernels by it) comes back with the total, in one synchronisation
             if ((status = spmi_max_segment_async(t->pos[1], (int)sizeof(PT) * 8, m, (unsigned long long *)(flags + 4), st)) != SP_OK) break;
-            PT total = 0;
-            unsigned long long longest = 0;
-            if (hipMemcpyAsync(&total, (const PT *)t->pos[1] + m, sizeof(PT), hipMemcpyDeviceToHost, st) != hipSuccess ||
-                hipMemcpyAsync(&longest, flags + 4, 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+            // the total goes into the flags block next to the longest row: one copy to the host for both
+            hipLaunchKernelGGL((spgemm_last_pos_kernel<PT>), dim3(1), dim3(1), 0, st, (const PT *)t->pos[1] + m, (long long *)(flags + 8));
+            if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
+            long long back[6] = {0, 0, 0, 0, 0, 0};                // bytes 0..47 of the block: [2] = longest row, [4] = total
+            if (hipMemcpyAsync(back, flags, sizeof(back), hipMemcpyDeviceToHost, st) != hipSuccess ||
                 hipStreamSynchronize(st) != hipSuccess) { status = SP_ERR_HIP; break; }
-            t->max_segment = (int64_t)longest;
-            const int64_t nnzc = (int64_t)total;
+            t->max_segment = (int64_t)back[2];
+            const int64_t nnzc = (int64_t)back[4];
             if (nnzc < 0 || nnzc >= ((int64_t)1 << 31)) { status = SP_ERR_TOO_LARGE; break; }     // a 32-bit pos that wrapped shows as negative
             t->crd[1] = mem.get((((size_t)(nnzc > 0 ? nnzc : 1) * sizeof(CT)) + 15) & ~(size_t)15);
             t->values = mem.get((((size_t)(nnzc > 0 ? nnzc : 1) * sizeof(VT)) + 15) & ~(size_t)15);
