@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per product (bytes) from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # same counter reads for the plain copy kernel of known size); the summaries are under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", 32, 4): 542.1e6,      # profiles/spmv_binned_cfg2_w32_hbm_traffic.txt
+    ("cfg2", 32, 4): 516.7e6,      # profiles/spmv_binned_cfg2_w32_hbm_traffic.txt
     ("cfg2", 32, 3): 378.9e6,      # profiles/spmv_segmented_cfg2_w32_hbm_traffic.txt
     ("cfg2", 32, 2): 1447.0e6,     # profiles/spmv_stream_cfg2_w32_hbm_traffic.txt
     ("cfg3", 32, 0): 9.47e9,       # profiles/spmm_windows_cfg3_w32_profile.txt
