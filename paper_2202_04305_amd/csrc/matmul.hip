@@ -277,7 +277,11 @@ __global__ __launch_bounds__(kBinThreads) void spmv_bins_reduce_kernel(const VT 
 {
     __shared__ VT ys[kBinRB];
     constexpr int W = kBinThreads / 64, U = 4;
-    const int rb = blockIdx.x;
+    // blocks go to the eight XCDs in turn: XCD x gets the row blocks [x * per, (x + 1) * per), so that the buckets of
+    // neighbouring row blocks, which share their first and last lines, are read through the same L2
+    const int per = (rowblocks + 7) / 8;
+    const int rb = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (rb >= rowblocks) return;                       // whole block (the grid is rounded up to eight times per)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     for (int i = threadIdx.x; i < kBinRB; i += kBinThreads) ys[i] = (VT)0;
@@ -785,7 +789,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
                                (const VT *)g->val, (const uint16_t *)g->lcol, (const int64_t *)g->off, g->panels, g->rowblocks, g->pieces,
                                A->shape[1], B, ldb, (VT *)g->prod);
             SP_HIP(hipGetLastError());
-            hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)g->rowblocks), dim3(kBinThreads), 0, st,
+            hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)(ceil_div(g->rowblocks, 8) * 8)), dim3(kBinThreads), 0, st,
                                (const VT *)g->prod, (const uint16_t *)g->lrow, (const int64_t *)g->off, g->panels, g->rowblocks,
                                g->nrows, rowid, C, ldc, accumulate);
             SP_HIP(hipGetLastError());
