@@ -553,7 +553,8 @@ def main():
     if args.format:
         wl += ", stored as " + args.format
     out = {
-        "metric": "effective HBM GB/s for f64 CSR SpMV/SpMM (algorithmic bytes / time per product)",
+        "metric": "effective HBM GB/s (+GFLOP/s) for f64 CSR SpMV/SpMM, fraction of peak",
+        "metric_note": "value = algorithmic bytes / time per product; GFLOP/s in gflops, fraction of the 8 TB/s peak in frac_of_peak",
         "value": abytes / (ms_cold * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
