@@ -67,24 +67,6 @@ def build_c_client():
     return C_CLIENT
 
 
-def build_microbenchmarks():
-    """The standalone measurement programs under microbench/ (their results are quoted in profiles/)."""
-    outs = []
-    procs = []
-    for src in sorted(glob.glob(os.path.join(HERE, "microbench", "*.hip"))):
-        out = src[:-4]
-        outs.append(out)
-        procs.append((src, subprocess.Popen(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                                             "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", out, src],
-                                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
-    for src, p in procs:
-        out, _ = p.communicate()
-        if p.returncode != 0:
-            raise RuntimeError("hipcc failed on %s:\n%s" % (src, out.decode()))
-    return outs
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_c_client())
-    print(build_microbenchmarks())
