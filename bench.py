@@ -25,17 +25,40 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per product (bytes) from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
-# same counter reads for the plain copy kernel of known size); the summaries are under profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", 32, 4): 516.7e6,      # profiles/spmv_binned_cfg2_w32_hbm_traffic.txt
-    ("cfg2", 32, 3): 378.9e6,      # profiles/spmv_segmented_cfg2_w32_hbm_traffic.txt
-    ("cfg2", 32, 2): 1447.0e6,     # profiles/spmv_stream_cfg2_w32_hbm_traffic.txt
-    ("cfg3", 32, 0): 9.47e9,       # profiles/spmm_windows_cfg3_w32_profile.txt
-    ("cfg4", 32, 2): 0.43e9,       # profiles/spmv_dcsr_cfg4_w32_profile.txt
-    ("cfg5", 32, 0): 1.77e9,       # profiles/spmm_csc_cfg5_w32_profile.txt
-    ("mttkrp", 32, "dss"): 11.67e9,  # profiles/mttkrp_windows_tensor3_w32_profile.txt
-}
+REPS = 5          # timed blocks of `steps` products each: the line carries their median and their minimum
+
+
+def measured_traffic(workload, width, kernel):
+    """HBM bytes per product from the counter runs: the table in profiles/hbm_traffic_per_product.md (one row per workload,
+    width and kernel, with the commit it was measured at).  None when there is no row."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_product.md")
+    try:
+        rows = [[c.strip() for c in l.strip().strip("|").split("|")] for l in open(path) if l.startswith("|")]
+    except OSError:
+        return None, None
+    for r in rows[2:]:
+        if len(r) >= 6 and r[0] == workload and r[1] == str(width) and r[2] == str(kernel):
+            return float(r[3]), {"commit": r[4], "summary": r[5]}
+    return None, None
+
+
+def timed_blocks(torch, run, steps, reps=REPS):
+    """`reps` blocks of exactly `steps` steps, each between its own pair of events: ms per step of every block."""
+    out = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(steps)
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / steps)
+    return out
+
+
+def median(v):
+    v = sorted(v)
+    return v[len(v) // 2]
 
 
 def make_workload(name, small):
@@ -100,6 +123,23 @@ def copy_yardstick(torch, sp, dev):
     return 2.0 * nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def read_yardstick(torch, sp, dev):
+    """GB/s of the library's plain read-only streaming kernel on 1 GiB."""
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+    sink = torch.zeros(4, dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        sp.sp_stream_read(src, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        sp.sp_stream_read(src, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    return 1.0 * nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def bench_mttkrp(args, torch, sp, dev):
     """A[i,j] = B[i,k,l] * D[l,j] * C[k,j] (Section 6.3) on a synthetic tensor with the shape, entry count and output
     width of the paper's experiment; one step = one sp_mttkrp."""
@@ -141,19 +181,12 @@ def bench_mttkrp(args, torch, sp, dev):
             B, Cd, Dd, Ad = copies[i % len(copies)] if rotate else copies[0]
             sp.sp_mttkrp(B, Cd, Dd, Ad, accumulate=acc)
 
-    def timed(k, rotate=True):
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        run_steps(k, rotate)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / k
-
+    run_steps(len(copies))             # the first product of a tensor builds its tables and scratch: every copy, whatever --warmup says
     run_steps(warmup)
-    ms_cold = timed(steps)
+    cold = timed_blocks(torch, run_steps, steps)
+    ms_cold = median(cold)
     run_steps(warmup, rotate=False)
-    ms_warm = timed(steps, rotate=False)
+    ms_warm = median(timed_blocks(torch, lambda k: run_steps(k, rotate=False), steps))
     for c in copies:
         sp.sp_tensor_tune(c[0], sp.SP_TUNE_PROFILE, 1)
     run_steps(steps)
@@ -185,14 +218,16 @@ def bench_mttkrp(args, torch, sp, dev):
     out = {
         "metric": "effective HBM GB/s (algorithmic bytes / time per product)",
         "value": abytes / (ms_cold * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_cold, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "ms_per_step": ms_cold, "ms_per_step_min": min(cold), "ms_per_step_blocks": cold,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "MTTKRP A[i,j]=B[i,k,l]*D[l,j]*C[k,j] (Section 6.3), B %dx%dx%d f64 synthetic with %d stored entries "
                                "(shape, entry count and J=%d of the paper's experiment), stored as %s, pos/crd %d-bit" % (
                                    I, K, L, nnz, J, fmt, args.width),
                    "regime": "cold: rotating over %d copies (%.2f GB)" % (ncopies, ncopies * abytes / 1e9), "kernel": kernel_name,
                    "accumulate": acc, "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("mttkrp", args.width, fmt)), "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
+                     "traffic": None if args.small else measured_traffic("mttkrp", args.width, fmt)[0],
+                     "traffic_source": None if args.small else measured_traffic("mttkrp", args.width, fmt)[1], "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
         "cpu_baseline": cpu,
         "gflops": flops / (ms_cold * 1e-3) / 1e9,
         "frac_of_peak": abytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -398,9 +433,28 @@ def main():
     t0 = time.time()
     w = make_workload(name, args.small)
     gen_s = time.time() - t0
+    out = bench_matmul(args, torch, sp, dev, name, w, args.width, full=True)
+    out["gen_s"] = gen_s
+    # the paper's default widths are 64 bits (width 0 = native), its best strategies use 32: both are measured on the headline workload
+    if name == "cfg2" and args.width == 32 and not args.kernel and not args.format:
+        o = bench_matmul(args, torch, sp, dev, name, w, 64, full=False)
+        out["w64"] = {"ms_per_step": o["ms_per_step"], "ms_per_step_min": o["ms_per_step_min"], "value": o["value"], "unit": "GB/s",
+                      "frac": o["roofline"]["frac"], "kernel_us": o["roofline"]["kernel_us"], "algorithmic_bytes": o["roofline"]["algorithmic_bytes"],
+                      "kernel": o["roofline"]["kernel"], "storage_multiplier": o["storage_multiplier"], "inspector_ms": o["inspector_ms"],
+                      "note": "the same workload with 64-bit pos/crd (the paper's native width)"}
+    print(json.dumps(out))
+
+
+SPMV_KERNELS = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
+                3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel",
+                4: "binned SpMV: spmv_bins_multiply_kernel + spmv_bins_reduce_kernel"}
+
+
+def bench_matmul(args, torch, sp, dev, name, w, wbits, full):
+    """One workload at one pos/crd width: pack the copies, run the inspector on every one of them (sp_prepare), then time
+    REPS blocks of `steps` products.  full = False leaves out the extras (warm regime, graph replay, CPU leg)."""
     m, n = w.shape
     nnz, N = w.nnz, w.N
-    wbits = args.width
     tdtype = torch.float64 if w.dtype == np.float64 else torch.float32
     vbytes = 8 if w.dtype == np.float64 else 4
     sddmm = name == "sddmm"
@@ -413,12 +467,12 @@ def main():
     rows_d = torch.from_numpy(w.rows).to(dev)
     cols_d = torch.from_numpy(w.cols).to(dev)
     vals_d = torch.from_numpy(w.vals).to(dev)
+    lt, order = w.level_types, w.dim_ordering
     if args.format:
-        w.level_types = {"csr": (0, 1), "dcsr": (1, 1), "cdr": (1, 0), "dense": (0, 0)}[args.format]
-        w.dim_ordering = (0, 1)
-    enc = sp.sp_encode(w.level_types, w.dim_ordering, wbits, wbits)
+        lt, order = {"csr": (0, 1), "dcsr": (1, 1), "cdr": (1, 0), "dense": (0, 0)}[args.format], (0, 1)
+    enc = sp.sp_encode(lt, order, wbits, wbits)
     copies = []
-    pack_ms = []
+    pack_ms, inspector_ms = [], []
     for c in range(ncopies):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -429,6 +483,14 @@ def main():
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, args.kernel)
         sp.sp_tensor_tune(A, sp.SP_TUNE_CSC_MODE, args.csc_mode)
         sp.sp_tensor_tune(A, sp.SP_TUNE_SPMM_KERNEL, args.spmm_kernel)
+        if not sddmm:
+            # the inspector: kernel choice, regrouped copies, scratch.  Once per tensor, outside every timed region, timed on its own.
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            sp.sp_prepare(A, N)
+            e1.record()
+            torch.cuda.synchronize()
+            inspector_ms.append(e0.elapsed_time(e1))
         if sddmm:
             from gen import prng
             A_host = prng.uniform_pm1(w.seed, 8, m * N, dtype=w.dtype).reshape(m, N)
@@ -452,40 +514,26 @@ def main():
             else:
                 sp.sp_matmul(A, Bd, Cd, accumulate=acc)
 
-    def timed(k, rotate=True):
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        run_steps(k, rotate)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / k
-
-    run_steps(warmup)          # also builds whatever the first product of a tensor builds and keeps
-    ms_cold = timed(steps)
-    run_steps(warmup, rotate=False)
-    ms_warm = timed(steps, rotate=False)
-
-    # the same rotation recorded once into a HIP graph and replayed: what a caller with a launch-bound loop would do
-    graph_ms = None
-    if not sddmm:
-        g = torch.cuda.CUDAGraph()
-        per_graph = min(steps, 100)
-        with torch.cuda.graph(g):
-            run_steps(per_graph)
-        g.replay()
-        torch.cuda.synchronize()
-        reps = max(1, steps // per_graph)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
+    run_steps(len(copies))     # one product on every copy whatever --warmup says (SDDMM has no inspector call: its first call allocates)
+    run_steps(warmup)
+    cold = timed_blocks(torch, run_steps, steps)
+    ms_cold = median(cold)
+    lazy = sum(sp.sp_tensor_info(A).lazyPrepares for A, _, _ in copies)
+    ms_warm, graph_ms = None, None
+    if full:
+        run_steps(warmup, rotate=False)
+        ms_warm = median(timed_blocks(torch, lambda k: run_steps(k, rotate=False), steps))
+        # the same rotation recorded once into a HIP graph and replayed: what a caller with a launch-bound loop would do
+        if not sddmm:
+            g = torch.cuda.CUDAGraph()
+            per_graph = min(steps, 100)
+            with torch.cuda.graph(g):
+                run_steps(per_graph)
             g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        graph_ms = e0.elapsed_time(e1) / (reps * per_graph)
-        del g
+            graph_ms = median(timed_blocks(torch, lambda k: [g.replay() for _ in range(k)], max(1, steps // per_graph))) / per_graph
+            del g
 
-    # the kernels that stream A, timed by the library's own event pairs around them (separate pass)
+    # the kernels that stream A, timed by the library's own event pairs around them on the stream they run on (separate pass)
     for A, _, _ in copies:
         sp.sp_tensor_tune(A, sp.SP_TUNE_PROFILE, 1)
     run_steps(steps)
@@ -506,11 +554,12 @@ def main():
     torch.cuda.synchronize()
 
     copy_gbs = copy_yardstick(torch, sp, dev)
+    read_gbs = read_yardstick(torch, sp, dev)
 
     # CPU checker on the same input, one host core; also the parity check of this very run
     cpu = None
     parity = None
-    if not args.no_cpu:
+    if full and not args.no_cpu:
         import oracle
         reps = 3 if spmv else 1
         times = []
@@ -535,32 +584,39 @@ def main():
                    nnz, N, reps, cpu_s),
                "gflops": flops / cpu_s / 1e9}
 
+    # which kernel ran: the library's own answer for SpMV (sp_tensor_info), the dispatch rule for the rest
     kk = 0
     if spmv:
-        kk = args.kernel
-        if kk == 0:
-            kk = 4 if (name == "cfg2" and not args.small) else (1 if name == "cfg1" else 2)
-        kernel_name = {1: "spmv_rows_kernel", 2: "spmv_stream_kernel (+ fix-up)",
-                       3: "column-segmented SpMV: spmv_stream_kernel on the panel copy + fix-up + spmv_panel_sum_kernel",
-                       4: "binned SpMV: spmv_bins_multiply_kernel + spmv_bins_reduce_kernel"}[kk]
-        if w.level_types[1] == 0:
+        kk = int(info.spmvKernel)
+        kernel_name = SPMV_KERNELS.get(kk, "spmv kernel %d" % kk)
+        if lt[1] == 0:
             kernel_name = "dense_rows_kernel"
     else:
         kernel_name = "sddmm_rows_vec_kernel" if sddmm else "spmm_scatter_kernel" if (name == "cfg5" and args.csc_mode == 1) else (
             "spmm_rows_kernel" if args.spmm_kernel == 1 else "spmm_rows_vec_kernel" if args.spmm_kernel == 2 else "spmm_windows_vec_kernel (+ fix-up)")
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    traffic, traffic_source = (None, None) if args.small else measured_traffic(name, wbits, kk if spmv else 0)
+    # what the kernel's own design has to move (the binned SpMV streams 28 bytes per stored entry instead of CSR's 12), priced at
+    # the rate of the plain read-only streaming kernel of this run (optimistic for the part that is written): how close the
+    # kernel is to the floor of its design, next to `frac`
+    design_bytes = abytes
+    if spmv and kk == 4:
+        design_bytes = nnz * (2 * vbytes + 2 * 2 + vbytes) + n * vbytes + m * vbytes
+    floor_us = design_bytes / read_gbs * 1e-3
     wl = DESCRIPTIONS[name] % dict(m=m, n=n, nnz=nnz, N=N) + ", pos/crd %d-bit" % wbits
     if args.format:
         wl += ", stored as " + args.format
     out = {
         "metric": "effective HBM GB/s (+GFLOP/s) for f64 CSR SpMV/SpMM, fraction of peak",
-        "metric_note": "value = algorithmic bytes / time per product; GFLOP/s in gflops, fraction of the 8 TB/s peak in frac_of_peak",
+        "metric_note": "value = algorithmic bytes / time per product (median of %d blocks of `steps` products); GFLOP/s in gflops, fraction of the 8 TB/s peak in frac_of_peak" % REPS,
         "value": abytes / (ms_cold * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
         "ms_per_step": ms_cold,
+        "ms_per_step_min": min(cold),
+        "ms_per_step_blocks": cold,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -569,23 +625,32 @@ def main():
         "config": {"workload": wl, "regime": "cold: rotating over %d copies of A, B, C (%.2f GB)" % (
             ncopies, ncopies * abytes / 1e9), "kernel": kernel_name, "accumulate": acc, "small": bool(args.small)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get((name, wbits, kk if spmv else 0)),
-                     "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": kernel_name, "kernel_us": kernel_ms * 1e3, "algorithmic_bytes": abytes,
+                     "design_bytes": design_bytes, "floor_us": floor_us, "frac_of_floor": floor_us / (kernel_ms * 1e3),
+                     "floor_note": "design_bytes = what the kernel's data layout streams per product; floor_us = that at the plain read-only streaming kernel's rate of this run (read_kernel_gbs)"},
         "cpu_baseline": cpu,
         "gflops": flops / (ms_cold * 1e-3) / 1e9,
         "frac_of_peak": abytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "warm": {"ms_per_step": ms_warm, "value": abytes / (ms_warm * 1e-3) / 1e9,
-                 "note": "same buffers every step: part of the working set stays in the last-level cache"},
+        "inspector_ms": None if not inspector_ms else median(inspector_ms),
+        "inspector_note": "sp_prepare per tensor (kernel choice, regrouped copy, scratch), outside the timed region; break-even after inspector_ms / ms_per_step products",
+        "lazy_prepares": lazy,      # products that had to build something first (sp_tensor_info): none after sp_prepare
+        "storage_multiplier": (info.storageBytes + info.derivedBytes) / float(info.storageBytes),
+        "storage_bytes": int(info.storageBytes), "derived_bytes": int(info.derivedBytes),
+        "warm": None if ms_warm is None else {"ms_per_step": ms_warm, "value": abytes / (ms_warm * 1e-3) / 1e9,
+                                               "note": "same buffers every step: part of the working set stays in the last-level cache"},
         "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "value": abytes / (graph_ms * 1e-3) / 1e9,
                                                        "note": "the same products recorded once into a HIP graph and replayed (cold rotation)"},
         "copy_kernel_gbs": copy_gbs,
+        "read_kernel_gbs": read_gbs,
         "frac_of_copy": abytes / (ms_cold * 1e-3) / 1e9 / copy_gbs,
-        "pack": {"ms": sorted(pack_ms)[len(pack_ms) // 2], "mnnz_per_s": nnz / (sorted(pack_ms)[len(pack_ms) // 2] * 1e-3) / 1e6},
+        "pack": {"ms": median(pack_ms), "mnnz_per_s": nnz / (median(pack_ms) * 1e-3) / 1e6},
         "matrix": dict(w.stats, storage_bytes=int(info.storageBytes)),
         "parity_ok": parity,
-        "gen_s": gen_s,
     }
-    print(json.dumps(out))
+    for A, _, _ in copies:
+        A.free()
+    return out
 
 
 if __name__ == "__main__":

@@ -82,21 +82,34 @@ sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64_t nnz,
                   sp_alloc_fn alloc, sp_free_fn free_, void *ctx, void *stream, sp_tensor **out);
 void sp_tensor_free(sp_tensor *t);
 
+/* The inspector step of the products below (Section 6.2 measures the matrix-times-vector and SpMM kernels on tensors
+ * that were read and packed beforehand; what a kernel needs beyond the packed storage is prepared here, once, outside
+ * the products).  For a product of `A` with a dense operand of N columns it decides which kernel will run (for N = 1
+ * it measures, in one pass over the innermost crd array, how scattered the columns are), builds the copy of the
+ * entries that kernel reads (row-major copy of a column-major tensor; for a large matrix with scattered columns
+ * a copy regrouped by column panel and row block), and allocates the scratch the kernel uses.  Everything is obtained
+ * from the tensor's allocator and kept by the handle until sp_tensor_free; sp_tensor_info reports its size (derivedBytes)
+ * and the choice (spmvKernel).  Synchronises `stream`.  Calling it again with the same N is a no-op; a larger N
+ * grows the scratch; sp_tensor_tune with a kernel key makes the next sp_prepare (or product) decide again.
+ * After sp_prepare(A, N), sp_matmul(A, .., N' <= N columns ..) neither allocates nor synchronises, so it may be recorded
+ * into a HIP graph from its first call on.  Errors: NULL, RANK (not rank 2), SHAPE (N < 0), UNSUPPORTED (a kernel forced
+ * with sp_tensor_tune cannot run on this tensor), ALLOC, HIP. */
+sp_status sp_prepare(sp_tensor *A, int64_t N, void *stream);
+
 /* C[i,j] = sum_k A[i,k] * B[k,j] (Section 1, the SpMM kernel; Section 6.2, matrix times vector
  * is the case N = 1), A a packed rank-2 tensor of shape m x n.
  *   B  DEVICE, row-major n x N with leading dimension ldb >= N, A's dtype.
  *   C  DEVICE, row-major m x N with leading dimension ldc >= N, A's dtype.
  *   accumulate = 0: C is overwritten (rows of A without stored entries become zero);
  *   accumulate = 1: C += A.B and rows without stored entries are not touched.
- * Enqueues on `stream` and returns without synchronising, except that the first product of a
- * tensor may first build tables or a regrouped copy of the entries that later products reuse
- * (it then allocates through the tensor's allocator and synchronises `stream` once; the handle
- * keeps what was built until sp_tensor_free).  Because of that cache a handle must not be used
- * by two host threads at the same time, and the scratch buffers it holds are shared by all
- * products on it: products of one tensor that run concurrently on different streams race.
- * B and C must not overlap.  Summation order inside a row is unspecified (floating-point
- * reassociation, Section 5.2); whether it is the same from call to call depends on the kernel
- * (see SP_TUNE_SPMV_KERNEL). */
+ * Enqueues on `stream` and returns without synchronising or allocating, provided sp_prepare(A, N) ran before.
+ * Without it the product still works: whatever sp_prepare would have built is built by the first product that needs
+ * it (that call then allocates and synchronises `stream`), and sp_tensor_info counts such calls in lazyPrepares, so
+ * a caller can assert that its loop ran without any.  The handle's derived state is a cache that a product may fill
+ * in although it takes the handle as const: a handle must not be used by two host threads at the same time, and the
+ * scratch it holds is shared by all products on it, so products of one tensor that run concurrently on different
+ * streams race.  B and C must not overlap.  Summation order inside a row is unspecified (floating-point reassociation,
+ * Section 5.2); whether it is the same from call to call depends on the kernel (see SP_TUNE_SPMV_KERNEL). */
 sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                     void *C, int64_t ldc, int accumulate, void *stream);
 
@@ -107,10 +120,12 @@ sp_status sp_pos(const sp_tensor *t, int level, const void **ptr, int64_t *len);
 sp_status sp_crd(const sp_tensor *t, int level, const void **ptr, int64_t *len);
 sp_status sp_values(const sp_tensor *t, const void **ptr, int64_t *len);
 
-/* Back to the coordinate scheme: every stored position in storage order (padding zeros of a
- * dense level under a compressed one included), coordinates in the original dimension
- * order.  coords: HOST array of `rank` DEVICE int64 arrays, each with room for the
- * values length; values: DEVICE array of the tensor's dtype, same length.  Asynchronous. */
+/* Back to the coordinate scheme (Section 4.2: the intermediate form every conversion passes through; it is the first
+ * half of the paper's convert operation, whose second half is sp_pack): every stored position in storage order
+ * (padding zeros of a dense level under a compressed one included), coordinates in the original dimension order.
+ * coords: HOST array of `rank` DEVICE int64 arrays, each with room for sp_values' length (sp_tensor_info: nvalues) entries;
+ * values: DEVICE array of the tensor's dtype, same length.  The number of entries written is that length: nothing comes
+ * back to the host, so the call is asynchronous. */
 sp_status sp_unpack(const sp_tensor *t, int64_t *const *coords, void *values, void *stream);
 
 /* Sampled dense-dense product X[i,j] = S[i,j] * sum_k A[i,k] * B[k,j] (Section 6.2, the SDDMM kernel of the
@@ -175,6 +190,9 @@ typedef struct {
     int64_t nvalues;                 /* length of the values array */
     int64_t maxSegment;              /* longest innermost pos segment (rank 2: longest row/column) */
     int64_t storageBytes;            /* pos + crd + values */
+    int64_t derivedBytes;            /* what the handle keeps beyond that: tables, regrouped copies, scratch (see sp_prepare) */
+    int spmvKernel;                  /* the SpMV kernel a product with one column runs (values of SP_TUNE_SPMV_KERNEL); 0 = not decided yet */
+    int lazyPrepares;                /* products that had to build, allocate or decide something first (0 when sp_prepare covered them) */
 } sp_info;
 sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
 
@@ -201,20 +219,8 @@ sp_status sp_tensor_info(const sp_tensor *t, sp_info *info /* HOST */);
  *                        waves add into one workspace in an order that depends on timing, so the values of C agree
  *                        from call to call only to rounding; never chosen automatically
  * Unknown keys or values give SP_ERR_UNSUPPORTED. */
-enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_PROFILE = 4, SP_TUNE_SPGEMM_KERNEL = 5 };
+enum { SP_TUNE_SPMV_KERNEL = 1, SP_TUNE_CSC_MODE = 2, SP_TUNE_SPMM_KERNEL = 3, SP_TUNE_SPGEMM_KERNEL = 5 };   /* 4: see spmi_bench.h */
 sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value);
-
-/* Kernel timing for measurements.  After sp_tensor_tune(t, SP_TUNE_PROFILE, 1) every sp_matmul on
- * t brackets its main kernel (the one that streams A; not the zero fill, not the fix-up; both passes of
- * the binned SpMV, all three launches of the column-segmented one) with a
- * pair of HIP events on the caller's stream.  sp_profile_read waits for those events, returns
- * the summed kernel time in milliseconds and the number of launches, and clears the record.
- * Profiling costs two event records per call; leave it off in production. */
-sp_status sp_profile_read(sp_tensor *t, double *ms_total /* HOST */, int64_t *launches /* HOST */);
-
-/* dst[i] = src[i] for `bytes` bytes (multiple of 16), a plain streaming copy kernel: the
- * yardstick the benchmark scales its bandwidth figures and hardware counters by. */
-sp_status sp_stream_copy(void *dst /* DEVICE */, const void *src /* DEVICE */, size_t bytes, void *stream);
 
 const char *sp_status_str(sp_status s);
 int sp_last_hip_error(void);          /* hipError_t of the last SP_ERR_HIP on this thread */

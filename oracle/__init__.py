@@ -12,6 +12,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+_LIB_SANITIZED = os.path.join(_HERE, "liboracle_sanitized.so")
 
 OK, ERR_NULL, ERR_RANK, ERR_LEVEL_TYPE, ERR_ORDERING, ERR_WIDTH, ERR_COORD_RANGE, ERR_DUPLICATE, \
     ERR_SHAPE, ERR_DTYPE, ERR_UNSUPPORTED, ERR_TOO_LARGE, ERR_ALLOC = range(13)
@@ -30,10 +31,20 @@ def build(force=False):
     return _LIB
 
 
+def build_sanitized():
+    """The same source under gcc's address and undefined-behaviour sanitizers (host code only; any finding aborts).  A
+    process that loads it must have been started with the sanitizer runtime preloaded (see tests/test_oracle_sanitizers.py)."""
+    tmp = _LIB_SANITIZED + ".tmp%d" % os.getpid()
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-Wall", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, _LIB_SANITIZED)
+    return _LIB_SANITIZED
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        L = ctypes.CDLL(_LIB_SANITIZED if os.environ.get("ORACLE_SANITIZED") == "1" else build())
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.oracle_pack.restype = ci
         L.oracle_pack.argtypes = [ci, vp, vp, ci, ci, vp, i64, vp, vp, ci, ctypes.POINTER(vp)]

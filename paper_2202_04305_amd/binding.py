@@ -15,8 +15,8 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_COORD_RANGE", "SP_ERR_DUPLICATE", "SP_ERR_SHAPE", "SP_ERR_DTYPE", "SP_ERR_UNSUPPORTED",
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
-EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_status_str", "sp_last_hip_error"]
+EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_prepare", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
+           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_stream_read", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -26,7 +26,8 @@ class SpInfo(ctypes.Structure):
     _fields_ = [("rank", ctypes.c_int), ("levelTypes", ctypes.c_int * SP_MAX_RANK), ("dimOrdering", ctypes.c_int * SP_MAX_RANK),
                 ("posWidth", ctypes.c_int), ("crdWidth", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("shape", ctypes.c_int64 * SP_MAX_RANK), ("nnz", ctypes.c_int64), ("nvalues", ctypes.c_int64),
-                ("maxSegment", ctypes.c_int64), ("storageBytes", ctypes.c_int64)]
+                ("maxSegment", ctypes.c_int64), ("storageBytes", ctypes.c_int64), ("derivedBytes", ctypes.c_int64),
+                ("spmvKernel", ctypes.c_int), ("lazyPrepares", ctypes.c_int)]
 
 
 class SpError(RuntimeError):
@@ -43,11 +44,12 @@ _lib = None
 
 
 def load_library():
-    """Loads libspmi.so; builds it only when no built library exists.  Fails loudly otherwise."""
+    """Loads libspmi.so; builds it first when there is none or when a source or header is newer than it.  Fails loudly
+    when it can neither be loaded nor built: there is no other path."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _build.is_stale():
         _build.build()
     L = ctypes.CDLL(_build.LIB)
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
@@ -61,6 +63,8 @@ def load_library():
     L.sp_tensor_free.argtypes = [vp]
     L.sp_matmul.restype = ci
     L.sp_matmul.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
+    L.sp_prepare.restype = ci
+    L.sp_prepare.argtypes = [vp, i64, vp]
     for f in (L.sp_pos, L.sp_crd):
         f.restype = ci
         f.argtypes = [vp, ci, ctypes.POINTER(vp), ctypes.POINTER(i64)]
@@ -86,6 +90,8 @@ def load_library():
     L.sp_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     L.sp_stream_copy.restype = ci
     L.sp_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.sp_stream_read.restype = ci
+    L.sp_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     L.sp_status_str.restype = ctypes.c_char_p
     L.sp_status_str.argtypes = [ci]
     L.sp_last_hip_error.restype = ci
@@ -182,6 +188,13 @@ def sp_pack(enc, shape, coords, values, allocator=None):
                      _stream_ptr(), ctypes.byref(h))
     _check(code, "in sp_pack")
     return Tensor(h, allocator, values.dtype, values.device)
+
+
+def sp_prepare(A, N=1):
+    """The inspector step: builds and keeps whatever a product of A with N columns needs (synchronises)."""
+    L = load_library()
+    _check(L.sp_prepare(A._h, int(N), _stream_ptr()), "in sp_prepare")
+    return A
 
 
 def sp_matmul(A, B, C, accumulate=False, N=None, ldb=None, ldc=None):
@@ -314,3 +327,8 @@ def sp_profile_read(A):
 def sp_stream_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     _check(load_library().sp_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr()), "in sp_stream_copy")
+
+
+def sp_stream_read(src, sink):
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().sp_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr()), "in sp_stream_read")

@@ -107,6 +107,24 @@ extern "C" sp_status sp_tensor_info(const sp_tensor *t, sp_info *info)
     info->nvalues = t->nvalues;
     info->maxSegment = t->max_segment;
     info->storageBytes = bytes;
+    // what the handle keeps beyond the paper's storage: tables, regrouped copies, scratch
+    const int64_t v = t->dtype == SP_F64 ? 8 : 4;
+    int64_t extra = (t->rowblocks.nblocks + t->nz_rowblocks.nblocks) * (4 + v) + (int64_t)t->dense_partial_bytes + (int64_t)t->spmm_carry_bytes +
+                    (int64_t)t->sddmm_bt_bytes + (int64_t)t->mttkrp_carry_bytes + (int64_t)t->mttkrp_pad_bytes[0] + (int64_t)t->mttkrp_pad_bytes[1];
+    if (t->nz_pos) extra += t->nz_rows * (t->enc.cw / 8) + (t->nz_rows + 1) * (t->enc.pw / 8);
+    if (t->bins) extra += t->bins->nnz * (2 * v + 4) + ((int64_t)t->bins->panels * t->bins->rowblocks + 1) * 8;
+    const sp_tensor *copies[2] = {t->segments ? t->segments->seg : nullptr, t->transposed};
+    for (const sp_tensor *c : copies)
+        if (c) {
+            sp_info ci;
+            (void)sp_tensor_info(c, &ci);
+            extra += ci.storageBytes + ci.derivedBytes;
+        }
+    if (t->segments) extra += (int64_t)t->segments->panels * t->segments->nrows * v;
+    info->derivedBytes = extra;
+    const sp_tensor *prod = t->transposed ? t->transposed : t;       // the tensor whose kernels a product of `t` runs
+    info->spmvKernel = prod->plan_spmv;
+    info->lazyPrepares = t->lazy_prepares + (t->transposed ? t->transposed->lazy_prepares : 0);
     return SP_OK;
 }
 
@@ -117,7 +135,8 @@ extern "C" sp_status sp_tensor_tune(sp_tensor *t, int key, int64_t value)
     case SP_TUNE_SPMV_KERNEL:
         if (value < 0 || value > 4) return SP_ERR_UNSUPPORTED;
         t->tune_spmv = (int)value;
-        if (t->transposed) t->transposed->tune_spmv = (int)value;
+        t->plan_spmv = 0;                                // decided again by sp_prepare or the next product (copies already built are kept)
+        if (t->transposed) { t->transposed->tune_spmv = (int)value; t->transposed->plan_spmv = 0; }
         return SP_OK;
     case SP_TUNE_CSC_MODE:
         if (value < 0 || value > 2) return SP_ERR_UNSUPPORTED;
@@ -164,7 +183,7 @@ extern "C" sp_status sp_profile_read(sp_tensor *t, double *ms_total, int64_t *la
 
 // Row-major copy of a column-major tensor, through the coordinate scheme (the paper's route for
 // conversions, Section 4.2).  Built on first use and kept by the handle.
-sp_status spmi_build_transposed(sp_tensor *A, hipStream_t st)
+sp_status spmi_build_transposed(const sp_tensor *A, hipStream_t st)
 {
     if (A->transposed) return SP_OK;
     sp_mem mem{A->alloc, A->free_, A->ctx};
@@ -188,6 +207,7 @@ sp_status spmi_build_transposed(sp_tensor *A, hipStream_t st)
     if (s != SP_OK) return s;
     T->tune_spmv = A->tune_spmv;
     T->tune_spmm = A->tune_spmm;
+    T->lazy_prepares = 0;
     if (A->profile) (void)sp_tensor_tune(T, SP_TUNE_PROFILE, 1);
     A->transposed = T;
     return SP_OK;
@@ -266,13 +286,33 @@ extern "C" sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int
     if (N == 0 || m == 0) return SP_OK;
     if (!C || (!B && n > 0)) return SP_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
-    SP_TRY(spmi_ensure_tables(A, st));
+    if (A->tables_pending) { ++A->lazy_prepares; SP_TRY(spmi_ensure_tables(A, st)); }
     if (A->enc.lt[1] != SP_COMPRESSED) return spmi_matmul_dense_inner(A, B, N, ldb, C, ldc, accumulate, st);
     if (A->enc.perm[0] == 0) return spmi_matmul_rowmajor(A, B, N, ldb, C, ldc, accumulate, st);
     int mode = A->tune_csc ? A->tune_csc : 2;
     if (mode == 1) return spmi_matmul_colmajor_scatter(A, B, N, ldb, C, ldc, accumulate, st);
-    SP_TRY(spmi_build_transposed(const_cast<sp_tensor *>(A), st));
+    if (!A->transposed) { ++A->lazy_prepares; SP_TRY(spmi_build_transposed(A, st)); }
     return spmi_matmul_rowmajor(A->transposed, B, N, ldb, C, ldc, accumulate, st);
+}
+
+extern "C" sp_status sp_prepare(sp_tensor *A, int64_t N, void *stream)
+{
+    if (!A) return SP_ERR_NULL;
+    if (A->enc.rank != 2) return SP_ERR_RANK;
+    if (N < 0) return SP_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (N == 0 || A->shape[0] == 0) return SP_OK;
+    SP_TRY(spmi_ensure_tables(A, st));
+    sp_status s = SP_OK;
+    if (A->enc.lt[1] != SP_COMPRESSED) s = spmi_prepare_dense_inner(A, N, st);
+    else if (A->enc.perm[0] == 0) s = spmi_prepare_rowmajor(A, N, st);
+    else if ((A->tune_csc ? A->tune_csc : 2) == 2) {
+        s = spmi_build_transposed(A, st);
+        if (s == SP_OK) s = spmi_prepare_rowmajor(A->transposed, N, st);
+    }
+    SP_TRY(s);
+    SP_HIP(hipStreamSynchronize(st));
+    return SP_OK;
 }
 
 // ---- plain streaming copy: the bandwidth yardstick ----------------------------------------
@@ -292,6 +332,33 @@ extern "C" sp_status sp_stream_copy(void *dst, const void *src, size_t bytes, vo
     size_t nb = (n16 + 255) / 256;
     if (nb > 256 * 32) nb = 256 * 32;
     hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)nb), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst, (const uint4 *)src, n16);
+    SP_HIP(hipGetLastError());
+    return SP_OK;
+}
+
+// ---- plain streaming read: the read-only bandwidth yardstick --------------------------------
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16, unsigned *__restrict__ sink)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    unsigned acc = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+    if (acc == 0x9e3779b9u) *sink = acc;               // practically never: keeps the loads alive
+}
+
+extern "C" sp_status sp_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink) return SP_ERR_NULL;
+    if (bytes % 16) return SP_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return SP_OK;
+    size_t nb = (n16 + 255) / 256;
+    if (nb > 256 * 32) nb = 256 * 32;
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)nb), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, n16, (unsigned *)sink);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }

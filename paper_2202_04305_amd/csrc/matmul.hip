@@ -702,56 +702,114 @@ sp_status zero_c(VT *C, int64_t m, int64_t N, int64_t ldc, hipStream_t st)
     return SP_OK;
 }
 
+// Which stored rows a product walks: all positions of the outer level, or only the stored / non-empty ones through a row-id list
+// (a compressed outer level, or a dense one that is mostly empty and therefore carries the list of its non-empty rows).
+template <typename PT, typename CT>
+struct row_view {
+    const PT *pos; const CT *rowid; int64_t nrows; const sp_rowblocks *rowblocks; bool dcsr;
+    explicit row_view(const sp_tensor *A)
+    {
+        pos = (const PT *)A->pos[1];
+        dcsr = A->enc.lt[0] == SP_COMPRESSED;
+        rowid = dcsr ? (const CT *)A->crd[0] : nullptr;
+        nrows = A->npos[1] - 1;
+        rowblocks = &A->rowblocks;
+        if (!dcsr && A->nz_pos) {
+            dcsr = true;
+            pos = (const PT *)A->nz_pos; rowid = (const CT *)A->nz_rowid; nrows = A->nz_rows; rowblocks = &A->nz_rowblocks;
+        }
+    }
+};
+
+// The inspector step of the matrix-times-vector product (Section 6.2): decides which SpMV kernel the tensor's products run
+// and builds the regrouped copy that kernel reads.  Measures once how scattered the columns are (one pass over crd, one
+// synchronisation), may allocate through the tensor's allocator.  The decision is kept in A->plan_spmv.
+template <typename PT, typename CT, typename VT>
+sp_status prepare_spmv_t(const sp_tensor *A, hipStream_t st)
+{
+    if (A->plan_spmv) return SP_OK;
+    const row_view<PT, CT> rv(A);
+    const int64_t nnz = A->ncrd[1], nrows = rv.nrows;
+    int kernel = A->tune_spmv;
+    const bool fixed = kernel != 0;
+    if (kernel == 0) {
+        // small and even (no row beyond one wave's stride): one launch of the rows kernel beats stream + fix-up
+        const bool small_even = nnz < ((int64_t)1 << 18) && A->max_segment <= 64;
+        kernel = (rv.rowblocks->start && nnz >= 8 * kStreamT && !small_even) ? 2 : 1;
+        // a large matrix whose gathers are scattered over a large x: no gather should leave the chip's caches.  The
+        // binned copy keeps them inside the LDS (measured 103 us against 122 us on the 1M x 1M matrix); where it cannot
+        // be built, L2-sized column panels.  Gathers that mostly fall into the line of their predecessor stay as they are.
+        if (kernel == 2 && nnz >= ((int64_t)1 << 21) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) {
+            double share = 0;
+            SP_TRY(spmi_column_scatter(A, st, &share));
+            // ... and buckets of at least 32 entries on average (the second pass reads them a bucket at a time), in enough
+            // row blocks to give every CU one (the hypersparse 8M x 8M workload has 41: 85 us binned, 73 us streamed)
+            const int64_t rowblocks = ceil_div(nrows, (int64_t)kBinRB);
+            const double buckets = (double)ceil_div(A->shape[1], (int64_t)kBinPW) * (double)rowblocks;
+            if (share >= 0.5) kernel = ((double)nnz >= 32.0 * buckets && rowblocks >= 256) ? 4 : (!rv.dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
+        }
+    }
+    if (kernel == 4) {
+        const sp_status sb = spmi_build_bins(A, st);
+        if (sb == SP_ERR_UNSUPPORTED && !fixed) kernel = (!rv.dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
+        else if (sb != SP_OK) return sb;
+    }
+    if (kernel == 3) {
+        if (A->enc.lt[0] == SP_COMPRESSED) return SP_ERR_UNSUPPORTED;
+        const sp_status sb = spmi_build_segments(A, sizeof(VT), kSpmvSliceBytes, st);
+        if (sb == SP_ERR_UNSUPPORTED && !fixed) kernel = 2;
+        else if (sb != SP_OK) return sb;
+    }
+    if (kernel == 2 && !rv.rowblocks->start) return SP_ERR_UNSUPPORTED;
+    A->plan_spmv = kernel;
+    return SP_OK;
+}
+
+// Scratch of the SpMM cut by stored entries: one row of N values per block, kept by the tensor and grown on demand.
+template <typename PT, typename CT, typename VT>
+sp_status prepare_spmm_t(const sp_tensor *A, int64_t N, hipStream_t st)
+{
+    const row_view<PT, CT> rv(A);
+    if (!rv.rowblocks->start || A->tune_spmm == 1 || A->tune_spmm == 2) return SP_OK;
+    const size_t need = (size_t)rv.rowblocks->nblocks * N * sizeof(VT);
+    if (A->spmm_carry_bytes >= need) return SP_OK;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    if (A->spmm_carry) { SP_HIP(hipStreamSynchronize(st)); mem.put(A->spmm_carry); A->spmm_carry = nullptr; A->spmm_carry_bytes = 0; }
+    A->spmm_carry = mem.get((need + 255) & ~(size_t)255);
+    if (!A->spmm_carry) return SP_ERR_ALLOC;
+    A->spmm_carry_bytes = need;
+    return SP_OK;
+}
+
+template <typename PT, typename CT, typename VT>
+sp_status prepare_rowmajor_t(const sp_tensor *A, const VT *, int64_t N, int64_t, VT *, int64_t, int, hipStream_t st)
+{
+    if (A->npos[1] - 1 <= 0) return SP_OK;
+    if (N == 1) return prepare_spmv_t<PT, CT, VT>(A, st);
+    return prepare_spmm_t<PT, CT, VT>(A, N, st);
+}
+
 template <typename PT, typename CT, typename VT>
 sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
 {
-    const PT *pos = (const PT *)A->pos[1];
+    const row_view<PT, CT> rv(A);
+    const PT *pos = rv.pos;
     const CT *crd = (const CT *)A->crd[1];
     const VT *val = (const VT *)A->values;
-    // "dcsr": only stored rows are visited, through a row-id list: a compressed outer level, or a dense one that is
-    // mostly empty and therefore carries the list of its non-empty rows
-    bool dcsr = A->enc.lt[0] == SP_COMPRESSED;
-    const CT *rowid = dcsr ? (const CT *)A->crd[0] : nullptr;
-    int64_t nrows = A->npos[1] - 1;              // stored rows
-    const sp_rowblocks *rowblocks = &A->rowblocks;
-    if (!dcsr && A->nz_pos) {
-        dcsr = true;
-        pos = (const PT *)A->nz_pos; rowid = (const CT *)A->nz_rowid; nrows = A->nz_rows; rowblocks = &A->nz_rowblocks;
-    }
+    const bool dcsr = rv.dcsr;
+    const CT *rowid = rv.rowid;
+    const int64_t nrows = rv.nrows;              // stored rows
+    const sp_rowblocks *rowblocks = rv.rowblocks;
     const int64_t m = A->shape[0];
     const int64_t nnz = A->ncrd[1];
     if (dcsr && !accumulate) SP_TRY((zero_c<PT, CT, VT>(C, m, N, ldc, st)));   // rows that are not stored become zero
     if (nrows == 0) return SP_OK;
     if (N == 1) {
-        int kernel = A->tune_spmv;
-        if (kernel == 0) {
-            // small and even (no row beyond one wave's stride): one launch of the rows kernel beats stream + fix-up
-            const bool small_even = nnz < ((int64_t)1 << 18) && A->max_segment <= 64;
-            kernel = (rowblocks->start && nnz >= 8 * kStreamT && !small_even) ? 2 : 1;
-            // a large matrix whose gathers are scattered over a large x: no gather should leave the chip's caches.  The
-            // binned copy keeps them inside the LDS (measured 103 us against 122 us on the 1M x 1M matrix); where it cannot
-            // be built, L2-sized column panels.  Gathers that mostly fall into the line of their predecessor stay as they are.
-            if (kernel == 2 && nnz >= ((int64_t)1 << 21) && A->shape[1] * (int64_t)sizeof(VT) > ((int64_t)3 << 20)) {
-                double share = 0;
-                SP_TRY(spmi_column_scatter(const_cast<sp_tensor *>(A), st, &share));
-                // ... and buckets of at least 32 entries on average (the second pass reads them a bucket at a time), in enough
-                // row blocks to give every CU one (the hypersparse 8M x 8M workload has 41: 85 us binned, 73 us streamed)
-                const int64_t rowblocks = ceil_div(nrows, (int64_t)kBinRB);
-                const double buckets = (double)ceil_div(A->shape[1], (int64_t)kBinPW) * (double)rowblocks;
-                if (share >= 0.5) kernel = ((double)nnz >= 32.0 * buckets && rowblocks >= 256) ? 4 : (!dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
-            }
+        if (!A->plan_spmv) {                     // no sp_prepare before this product: the inspector runs now (may allocate and synchronise)
+            ++A->lazy_prepares;
+            SP_TRY((prepare_spmv_t<PT, CT, VT>(A, st)));
         }
-        if (kernel == 4 && A->tune_spmv == 0) {
-            const sp_status sb = spmi_build_bins(const_cast<sp_tensor *>(A), st);
-            if (sb == SP_ERR_UNSUPPORTED) kernel = (!dcsr && nnz >= ((int64_t)1 << 22)) ? 3 : 2;
-            else if (sb != SP_OK) return sb;
-        }
-        if (kernel == 3) {
-            if (A->enc.lt[0] == SP_COMPRESSED) return SP_ERR_UNSUPPORTED;
-            sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(A), sizeof(VT), kSpmvSliceBytes, st);   // first use: builds, allocates, synchronises
-            if (sb == SP_ERR_UNSUPPORTED && A->tune_spmv == 0) kernel = 2;
-            else if (sb != SP_OK) return sb;
-        }
+        const int kernel = A->plan_spmv;
         if (kernel == 3) {
             // the segmented copy is an ordinary CSR over panels*nrows virtual rows: stream it into the per-panel
             // partial vector (consecutive blocks gather from the same <= 2 MB slice of x), then add the panels up
@@ -782,7 +840,6 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             return SP_OK;
         }
         if (kernel == 4) {
-            SP_TRY(spmi_build_bins(const_cast<sp_tensor *>(A), st));          // first use: builds, allocates, synchronises
             const sp_bins *g = A->bins;                                       // over the same stored rows as pos / rowid here
             sp_prof_scope prof(A, st);
             hipLaunchKernelGGL((spmv_bins_multiply_kernel<VT>), dim3((unsigned)(ceil_div(g->panels, 8) * 8 * g->pieces)), dim3(kBinThreads), 0, st,
@@ -795,7 +852,6 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             SP_HIP(hipGetLastError());
             return SP_OK;
         }
-        if (kernel == 2 && !rowblocks->start) return SP_ERR_UNSUPPORTED;
         if (kernel == 2) {
             const int64_t nb = rowblocks->nblocks;
             {
@@ -843,14 +899,9 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
         const bool by_entries = A->tune_spmm == 3 || (A->tune_spmm == 0 && rowblocks->start);
         if (fits_any && by_entries) {
             const int64_t nb = rowblocks->nblocks;
-            sp_tensor *At = const_cast<sp_tensor *>(A);
-            const size_t need = (size_t)nb * N * sizeof(VT);
-            if (At->spmm_carry_bytes < need) {
-                sp_mem mem{A->alloc, A->free_, A->ctx};
-                if (At->spmm_carry) { SP_HIP(hipStreamSynchronize(st)); mem.put(At->spmm_carry); At->spmm_carry = nullptr; At->spmm_carry_bytes = 0; }
-                At->spmm_carry = mem.get((need + 255) & ~(size_t)255);
-                if (!At->spmm_carry) return SP_ERR_ALLOC;
-                At->spmm_carry_bytes = need;
+            if (A->spmm_carry_bytes < (size_t)nb * N * sizeof(VT)) {       // no sp_prepare for this many columns: the scratch is made now
+                ++A->lazy_prepares;
+                SP_TRY((prepare_spmm_t<PT, CT, VT>(A, N, st)));
             }
             const bool small = sizeof(CT) == 4 && (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B (64-bit coordinates keep 64-bit offsets)
 #define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
@@ -934,6 +985,24 @@ sp_status scatter_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT 
     return SP_OK;
 }
 
+// Scratch of the streaming product of fully stored rows with a vector: one partial sum per 2048-value chunk.
+template <typename PT, typename CT, typename VT>
+sp_status prepare_dense_inner_t(const sp_tensor *A, const VT *, int64_t N, int64_t, VT *, int64_t, int, hipStream_t st)
+{
+    const bool outer_compressed = A->enc.lt[0] == SP_COMPRESSED;
+    const int64_t nstored = outer_compressed ? A->ncrd[0] : A->size[0];
+    const int64_t inner = A->size[1];
+    if (A->enc.perm[0] != 0 || N != 1 || inner < kDenseChunk || nstored <= 0 || nstored > 65535) return SP_OK;
+    const size_t need = (size_t)(nstored * ceil_div(inner, kDenseChunk)) * sizeof(VT);
+    if (A->dense_partial_bytes >= need) return SP_OK;
+    sp_mem mem{A->alloc, A->free_, A->ctx};
+    if (A->dense_partial) { SP_HIP(hipStreamSynchronize(st)); mem.put(A->dense_partial); A->dense_partial = nullptr; A->dense_partial_bytes = 0; }
+    A->dense_partial = mem.get((need + 255) & ~(size_t)255);
+    if (!A->dense_partial) return SP_ERR_ALLOC;
+    A->dense_partial_bytes = need;
+    return SP_OK;
+}
+
 template <typename PT, typename CT, typename VT>
 sp_status dense_inner_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
 {
@@ -954,14 +1023,9 @@ sp_status dense_inner_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb,
         (uintptr_t)B % 16 == 0 && (uintptr_t)val % 16 == 0) {
         // fully stored rows times a vector: the streaming path (16-byte loads need every row 16-byte aligned)
         const int64_t nchunks = ceil_div(inner, kDenseChunk);
-        const size_t need = (size_t)(nstored * nchunks) * sizeof(VT);
-        sp_tensor *At = const_cast<sp_tensor *>(A);
-        if (At->dense_partial_bytes < need) {
-            sp_mem mem{A->alloc, A->free_, A->ctx};
-            if (At->dense_partial) { SP_HIP(hipStreamSynchronize(st)); mem.put(At->dense_partial); At->dense_partial = nullptr; At->dense_partial_bytes = 0; }
-            At->dense_partial = mem.get((need + 255) & ~(size_t)255);
-            if (!At->dense_partial) return SP_ERR_ALLOC;
-            At->dense_partial_bytes = need;
+        if (A->dense_partial_bytes < (size_t)(nstored * nchunks) * sizeof(VT)) {
+            ++A->lazy_prepares;
+            SP_TRY((prepare_dense_inner_t<PT, CT, VT>(A, B, N, ldb, C, ldc, accumulate, st)));
         }
         hipLaunchKernelGGL((dense_rows_spmv_partial_kernel<VT>), dim3((unsigned)nchunks, (unsigned)nstored), dim3(kThreads), 0, st, val, inner,
                            B, nchunks, (VT *)A->dense_partial);
@@ -1011,6 +1075,18 @@ sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int
                                hipStream_t st)
 {
     SPMI_DISPATCH_TYPES(rowmajor_t, A);
+}
+
+sp_status spmi_prepare_rowmajor(const sp_tensor *A, int64_t N, hipStream_t st)
+{
+    const void *B = nullptr; void *C = nullptr; const int64_t ldb = N, ldc = N; const int accumulate = 0;
+    SPMI_DISPATCH_TYPES(prepare_rowmajor_t, A);
+}
+
+sp_status spmi_prepare_dense_inner(const sp_tensor *A, int64_t N, hipStream_t st)
+{
+    const void *B = nullptr; void *C = nullptr; const int64_t ldb = N, ldc = N; const int accumulate = 0;
+    SPMI_DISPATCH_TYPES(prepare_dense_inner_t, A);
 }
 
 sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc,

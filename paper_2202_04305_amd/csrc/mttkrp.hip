@@ -269,18 +269,23 @@ sp_status mttkrp_t(const sp_tensor *B, const VT *M, int64_t ldm, const VT *X, in
     const CT *crd0 = (const CT *)B->crd[0], *crd1 = (const CT *)B->crd[1], *crd2 = (const CT *)B->crd[2];
     const int64_t nslc = B->npos[1] - 1, nfib = B->npos[2] - 1;
     const int64_t nwin = ceil_div(nnz, kTW);
-    sp_tensor *Bt = const_cast<sp_tensor *>(B);
+    const sp_tensor *Bt = B;                    // the handle's scratch and tables are its cache (mutable members)
     sp_mem mem{B->alloc, B->free_, B->ctx};
     const int64_t ncross = nslc < nwin - 1 ? nslc : nwin - 1;        // a slice has at most one first crossing
     const size_t table_bytes = (size_t)(2 * nwin + 4 + (ncross > 0 ? 2 * ncross : 0)) * 4;
     if (!Bt->mttkrp_windows) {
-        Bt->mttkrp_windows = mem.get(table_bytes);
-        if (!Bt->mttkrp_windows) return SP_ERR_ALLOC;
-        int32_t *wfib = (int32_t *)Bt->mttkrp_windows, *wslc = wfib + nwin, *cross = wslc + nwin + 4;
-        SP_TRY(spmi_fill_zero(wslc + nwin, 16, st));               // cross[-1] = 0: the length of the list
-        hipLaunchKernelGGL(mttkrp_windows_table_kernel<PT>, dim3((unsigned)ceil_div(nwin, kThreads)), dim3(kThreads), 0, st, pos1, nslc,
-                           pos2, nfib, nwin, wfib, wslc, cross);
-        SP_HIP(hipGetLastError());
+        // the handle takes the table only once its build has been enqueued: a failure on the way leaves no half-built table behind
+        void *table = mem.get(table_bytes);
+        if (!table) return SP_ERR_ALLOC;
+        int32_t *wfib = (int32_t *)table, *wslc = wfib + nwin, *cross = wslc + nwin + 4;
+        sp_status built = spmi_fill_zero(wslc + nwin, 16, st);     // cross[-1] = 0: the length of the list
+        if (built == SP_OK) {
+            hipLaunchKernelGGL(mttkrp_windows_table_kernel<PT>, dim3((unsigned)ceil_div(nwin, kThreads)), dim3(kThreads), 0, st, pos1, nslc,
+                               pos2, nfib, nwin, wfib, wslc, cross);
+            if (hipGetLastError() != hipSuccess) built = SP_ERR_HIP;
+        }
+        if (built != SP_OK) { (void)hipStreamSynchronize(st); mem.put(table); return built; }
+        Bt->mttkrp_windows = table;
     }
     const size_t need = (size_t)nwin * J * sizeof(VT);
     if (Bt->mttkrp_carry_bytes < need) {

@@ -538,7 +538,7 @@ static sp_status build_rowblocks_for(const void *pos, int pw, int64_t nrows, int
     return SP_OK;
 }
 
-sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st)
+sp_status spmi_build_rowblocks(const sp_tensor *t, hipStream_t st)
 {
     // only for rank 2 with a compressed innermost level
     if (t->enc.rank != 2 || t->enc.lt[1] != SP_COMPRESSED || t->rowblocks.start) return SP_OK;
@@ -593,7 +593,7 @@ struct nonempty_probe {
 __global__ void copy_word_kernel(const uint32_t *__restrict__ src, int *__restrict__ dst) { *dst = (int)*src; }
 
 // flags: the 64 zeroed device bytes of the build (see nonempty_probe for the slots used here)
-static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st, int *flags, nonempty_probe &q)
+static sp_status nonempty_enqueue(const sp_tensor *t, sp_scratch &tmp, hipStream_t st, int *flags, nonempty_probe &q)
 {
     if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
     const int64_t nrows = t->npos[1] - 1;
@@ -620,7 +620,7 @@ static sp_status nonempty_enqueue(sp_tensor *t, sp_scratch &tmp, hipStream_t st,
 }
 
 // after the stream has been synchronised; *launched = kernels were enqueued
-static sp_status nonempty_decide(sp_tensor *t, hipStream_t st, const nonempty_probe &q, bool *launched)
+static sp_status nonempty_decide(const sp_tensor *t, hipStream_t st, const nonempty_probe &q, bool *launched)
 {
     *launched = false;
     if (!q.active) return SP_OK;
@@ -650,7 +650,7 @@ static sp_status nonempty_decide(sp_tensor *t, hipStream_t st, const nonempty_pr
     return SP_OK;
 }
 
-static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t st)
+static sp_status build_nonempty_rows(const sp_tensor *t, sp_scratch &tmp, hipStream_t st)
 {
     int *flags = (int *)tmp.get(64);
     if (!flags) return SP_ERR_ALLOC;
@@ -668,7 +668,7 @@ static sp_status build_nonempty_rows(sp_tensor *t, sp_scratch &tmp, hipStream_t 
 
 // Column-segmented copy of a CSR tensor (see sp_segments): entries keyed by (panel, row, column) and packed
 // again as a CSR over panels*nrows virtual rows, through the coordinate scheme like any other conversion.
-static void free_segments(sp_tensor *t)
+static void free_segments(const sp_tensor *t)
 {
     if (!t->segments) return;
     sp_mem mem{t->alloc, t->free_, t->ctx};
@@ -680,7 +680,7 @@ static void free_segments(sp_tensor *t)
 
 // `slice_bytes`: how many bytes of the dense operand one panel may cover (a power-of-two number of its rows
 // is taken).  The handle keeps one segmented copy; asking for another panel width rebuilds it.
-sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st)
+sp_status spmi_build_segments(const sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st)
 {
     if (A->enc.rank != 2 || A->enc.lt[0] != SP_DENSE || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
     const int64_t nrows = A->shape[0], n = A->shape[1];
@@ -740,7 +740,7 @@ __global__ __launch_bounds__(kThreads) void count_jumps_kernel(const CT *__restr
     }
 }
 
-sp_status spmi_column_scatter(sp_tensor *A, hipStream_t st, double *share)
+sp_status spmi_column_scatter(const sp_tensor *A, hipStream_t st, double *share)
 {
     const int last = A->enc.rank - 1;
     if (A->scatter < 0) {
@@ -769,7 +769,7 @@ sp_status spmi_column_scatter(sp_tensor *A, hipStream_t st, double *share)
 }
 
 // ---- binned copy (see sp_bins) ------------------------------------------------------------
-static void free_bins(sp_tensor *t)
+static void free_bins(const sp_tensor *t)
 {
     if (!t->bins) return;
     sp_mem mem{t->alloc, t->free_, t->ctx};
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *_
 // Synchronises.  Rows are counted among the stored ones (all of them for CSR; the compressed outer level's for DCSR;
 // the non-empty ones where the tensor carries their list), the caller maps them back.  SP_ERR_UNSUPPORTED for other
 // encodings, for an empty tensor and when the bucket table would be larger than the tensor itself.
-sp_status spmi_build_bins(sp_tensor *A, hipStream_t st)
+sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
 {
     if (A->bins) return SP_OK;
     if (A->enc.rank != 2 || A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0) return SP_ERR_UNSUPPORTED;
@@ -916,6 +916,7 @@ static void release_tensor_arrays(sp_tensor *t)
     mem.put(t->rowblocks.carry); t->rowblocks.carry = nullptr;
     mem.put(t->dense_partial); t->dense_partial = nullptr; t->dense_partial_bytes = 0;
     mem.put(t->spmm_carry); t->spmm_carry = nullptr; t->spmm_carry_bytes = 0;
+    mem.put(t->sddmm_bt); t->sddmm_bt = nullptr; t->sddmm_bt_bytes = 0;
     mem.put(t->mttkrp_windows); t->mttkrp_windows = nullptr;
     mem.put(t->mttkrp_carry); t->mttkrp_carry = nullptr; t->mttkrp_carry_bytes = 0;
     for (int w = 0; w < 2; ++w) { mem.put(t->mttkrp_pad[w]); t->mttkrp_pad[w] = nullptr; t->mttkrp_pad_bytes[w] = 0; }
@@ -1000,10 +1001,9 @@ sp_status spmi_max_segment_async(const void *pos, int pw, int64_t nseg, unsigned
     return SP_OK;
 }
 
-sp_status spmi_ensure_tables(const sp_tensor *ct, hipStream_t st)
+sp_status spmi_ensure_tables(const sp_tensor *t, hipStream_t st)
 {
-    if (!ct->tables_pending) return SP_OK;
-    sp_tensor *t = const_cast<sp_tensor *>(ct);
+    if (!t->tables_pending) return SP_OK;
     sp_mem mem{t->alloc, t->free_, t->ctx};
     sp_scratch tmp(mem);
     SP_TRY(spmi_build_rowblocks(t, st));

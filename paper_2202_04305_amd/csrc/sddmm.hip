@@ -180,14 +180,21 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
     if (K == 0) return spmi_fill_zero(X, (size_t)S->nvalues * sizeof(VT), st);   // X was allocated by the caller: exact size, 4-byte multiple
 
     sp_mem mem{S->alloc, S->free_, S->ctx};
-    sp_scratch tmp(mem);
     constexpr int64_t V = 16 / sizeof(VT);
     const VT *Bt = B;
     int64_t ldt = ldb;
     if (!b_is_transposed) {
         ldt = (K + V - 1) / V * V;                         // rows of the scratch start 16-byte aligned
-        VT *scratch = (VT *)tmp.get((size_t)(n > 0 ? n : 1) * ldt * sizeof(VT));
-        if (!scratch) return SP_ERR_ALLOC;
+        // the transposed operand lives in scratch the tensor keeps and grows on demand: only a call that needs more than any
+        // call before it allocates (and then waits for the stream, since the old block may still be read)
+        const size_t need = (size_t)(n > 0 ? n : 1) * ldt * sizeof(VT);
+        if (S->sddmm_bt_bytes < need) {
+            if (S->sddmm_bt) { SP_HIP(hipStreamSynchronize(st)); mem.put(S->sddmm_bt); S->sddmm_bt = nullptr; S->sddmm_bt_bytes = 0; }
+            S->sddmm_bt = mem.get((need + 255) & ~(size_t)255);
+            if (!S->sddmm_bt) return SP_ERR_ALLOC;
+            S->sddmm_bt_bytes = need;
+        }
+        VT *scratch = (VT *)S->sddmm_bt;
         hipLaunchKernelGGL(transpose_kernel<VT>, dim3(grid_for(n, 32), grid_for(K, 32)), dim3(256), 0, st, B, K, n, ldb, scratch, ldt);
         SP_HIP(hipGetLastError());
         Bt = scratch;
@@ -229,9 +236,6 @@ sp_status sddmm_t(const sp_tensor *S, const VT *A, int64_t lda, const VT *B, int
         }
         SP_HIP(hipGetLastError());
     }
-    // the scratch goes back to the allocator when `tmp` leaves scope; with a stream-ordered allocator that is safe,
-    // with hipFree it waits for the device
-    if (!S->alloc && !b_is_transposed) SP_HIP(hipStreamSynchronize(st));
     return SP_OK;
 }
 

@@ -759,7 +759,7 @@ sp_status spgemm_workspace_t(const sp_tensor *A, const sp_tensor *Br, const sp_e
             if (nnzc == 0) bounds = nullptr;
             if (!bounds && work && nnzc > 0 && A->tune_spgemm != 3 && A->tune_spgemm != 5 && n >= 4 * 64) {
                 while (((int64_t)pwaves << pshift) < n) ++pshift;           // the narrowest power of two with at most that many panels
-                sp_status sb = spmi_build_segments(const_cast<sp_tensor *>(Br), 1, (int64_t)1 << pshift, st);
+                sp_status sb = spmi_build_segments(Br, 1, (int64_t)1 << pshift, st);
                 if (sb == SP_OK && Br->segments && Br->segments->shift == pshift && Br->segments->panels <= pwaves) Bseg = Br->segments->seg;
                 else if (sb != SP_OK && sb != SP_ERR_UNSUPPORTED) { status = sb; break; }
             }
@@ -845,7 +845,7 @@ extern "C" sp_status sp_spgemm(const sp_tensor *A, const sp_tensor *B, const sp_
     const sp_tensor *Br = B;
     if (B->enc.lt[1] != SP_COMPRESSED) return SP_ERR_UNSUPPORTED;
     if (B->enc.perm[0] != 0) {
-        SP_TRY(spmi_build_transposed(const_cast<sp_tensor *>(B), st));
+        SP_TRY(spmi_build_transposed(B, st));
         Br = B->transposed;
     }
     const int pw = Br->enc.pw, cw = Br->enc.cw;

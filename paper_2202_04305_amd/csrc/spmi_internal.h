@@ -7,6 +7,7 @@
 #include <type_traits>
 #include <vector>
 #include "spmi.h"
+#include "spmi_bench.h"
 
 struct sp_encoding {
     int rank;
@@ -67,26 +68,32 @@ struct sp_tensor {
     sp_alloc_fn alloc;
     sp_free_fn free_;
     void *ctx;
-    // derived, built lazily by sp_matmul or eagerly by sp_pack
-    sp_rowblocks rowblocks;
+    // Derived state: tables, regrouped copies and scratch that the product kernels use.  None of it is part of the paper's
+    // storage; sp_pack builds some of it, sp_prepare (or, lazily, the first product that needs it) the rest.  It is a cache
+    // in the C++ sense, hence `mutable`: a product takes the handle as const and may still fill it in.
+    mutable sp_rowblocks rowblocks;
     // a dense outer level whose segments are mostly empty: ids and pos entries of the non-empty ones (else nullptr)
-    void *nz_rowid, *nz_pos;
-    int64_t nz_rows;
-    sp_rowblocks nz_rowblocks;
-    sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
-    sp_segments *segments;           // owned, built on first use
-    sp_bins *bins;                   // owned, built on first use
-    double scatter;                  // share of stored entries whose successor lies in another 128-byte line of x; < 0: not measured yet
-    void *dense_partial;             // DEVICE scratch of the dense-row SpMV (per-chunk partial sums), grown on demand
-    size_t dense_partial_bytes;
-    void *spmm_carry;                // DEVICE scratch of the SpMM cut by entries (N values per block), grown on demand
-    size_t spmm_carry_bytes;
-    void *mttkrp_windows;            // DEVICE int32[2 * windows]: fibre and slice holding the first entry of each window (rank 3)
-    void *mttkrp_carry;              // DEVICE scratch of the MTTKRP (J values per window), grown on demand
-    size_t mttkrp_carry_bytes;
-    void *mttkrp_pad[2];             // DEVICE scratch of the MTTKRP: inner / mid factor matrix with rows padded to whole cache lines
-    size_t mttkrp_pad_bytes[2];
-    int tables_pending;              // rowblocks / non-empty rows not built yet (a result of sp_spgemm): built on first use by a product
+    mutable void *nz_rowid, *nz_pos;
+    mutable int64_t nz_rows;
+    mutable sp_rowblocks nz_rowblocks;
+    mutable sp_tensor *transposed;           // CSC/DCSC viewed through a row-major copy (owned)
+    mutable sp_segments *segments;           // owned, built on first use
+    mutable sp_bins *bins;                   // owned, built on first use
+    mutable double scatter;                  // share of stored entries whose successor lies in another 128-byte line of x; < 0: not measured yet
+    mutable void *dense_partial;             // DEVICE scratch of the dense-row SpMV (per-chunk partial sums), grown on demand
+    mutable size_t dense_partial_bytes;
+    mutable void *spmm_carry;                // DEVICE scratch of the SpMM cut by entries (N values per block), grown on demand
+    mutable size_t spmm_carry_bytes;
+    mutable void *sddmm_bt;                  // DEVICE scratch of the SDDMM: the transposed dense operand (n x K), grown on demand
+    mutable size_t sddmm_bt_bytes;
+    mutable void *mttkrp_windows;            // DEVICE int32[2 * windows]: fibre and slice holding the first entry of each window (rank 3)
+    mutable void *mttkrp_carry;              // DEVICE scratch of the MTTKRP (J values per window), grown on demand
+    mutable size_t mttkrp_carry_bytes;
+    mutable void *mttkrp_pad[2];             // DEVICE scratch of the MTTKRP: inner / mid factor matrix with rows padded to whole cache lines
+    mutable size_t mttkrp_pad_bytes[2];
+    mutable int tables_pending;              // rowblocks / non-empty rows not built yet (a result of sp_spgemm): built on first use by a product
+    mutable int plan_spmv;                   // SpMV kernel a product with one column runs (1..4); 0 = not decided yet (sp_prepare or the first product decides)
+    mutable int lazy_prepares;               // how many products had to build, allocate or decide something first (none after sp_prepare)
     int tune_spmv, tune_csc, tune_spmm, tune_spgemm;
     int profile;
     std::vector<hipEvent_t> *prof_events;   // start/stop pairs, owned
@@ -166,14 +173,14 @@ sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
 // with the value bits as payload, both temporaries of `tmp`; entries with equal keys are added up in the order given.
 sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,
                          int64_t n, uint64_t *keys, void *payload, sp_scratch &tmp, hipStream_t st, sp_tensor **out);
-sp_status spmi_build_rowblocks(sp_tensor *t, hipStream_t st);
-sp_status spmi_build_segments(sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
+sp_status spmi_build_rowblocks(const sp_tensor *t, hipStream_t st);
+sp_status spmi_build_segments(const sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
 constexpr int kSpmiBinPanelShift = 13;                       // columns per panel of the binned copy: 8192 (a 64 KB slice of an f64 x)
 constexpr int kSpmiBinRowShift = 11;                         // rows per row block: 2048 (a 16 KB slice of an f64 y)
-sp_status spmi_build_bins(sp_tensor *A, hipStream_t st);
+sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st);
 // How scattered the gathers of a product are: the share of stored entries of the innermost level whose successor is 16 or
 // more coordinates away (or belongs to the next segment).  Measured once per tensor, then cached; synchronises the first time.
-sp_status spmi_column_scatter(sp_tensor *A, hipStream_t st, double *share);
+sp_status spmi_column_scatter(const sp_tensor *A, hipStream_t st, double *share);
 #ifndef SPMI_ST
 #define SPMI_ST 128
 #endif
@@ -203,11 +210,15 @@ sp_status spmi_finish_pack(sp_tensor *t, sp_status status, hipStream_t st, sp_te
 
 // ---- api.hip -----------------------------------------------------------------------------
 // Builds and keeps the row-major copy of a column-major tensor (A->transposed); no-op when it exists.
-sp_status spmi_build_transposed(sp_tensor *A, hipStream_t st);
+sp_status spmi_build_transposed(const sp_tensor *A, hipStream_t st);
 
 // ---- matmul.hip --------------------------------------------------------------------------
 sp_status spmi_matmul_rowmajor(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                                void *C, int64_t ldc, int accumulate, hipStream_t st);
+// Everything a product of a row-major tensor (compressed / dense innermost level) with N columns would otherwise build on
+// first use: the kernel choice, regrouped copies, scratch.  May allocate and synchronise; a no-op when nothing is missing.
+sp_status spmi_prepare_rowmajor(const sp_tensor *A, int64_t N, hipStream_t st);
+sp_status spmi_prepare_dense_inner(const sp_tensor *A, int64_t N, hipStream_t st);
 sp_status spmi_matmul_dense_inner(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc,
                                   int accumulate, hipStream_t st);
 sp_status spmi_matmul_colmajor_scatter(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,

@@ -130,3 +130,89 @@ def test_products_replayed_from_a_hip_graph():
             assert bool(torch.isfinite(scratch))
     ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, Bh)
     assert_product_close(C, ref, mag, np.float64, "graph replay vs the checker")
+
+
+def _binned_case():
+    """Big enough, and scattered enough, for the automatic SpMV choice to take the copy binned by column panel and row
+    block: at least 2^21 stored entries, x above 3 MB, 256 row blocks of 2048 rows, 32 entries per bucket on average."""
+    return W.cfg2_powerlaw_csr(1 << 19, 1 << 19, mean=24.0, cap=4000)
+
+
+@pytest.mark.parametrize("fmt", ["csr", "csc"])
+def test_first_product_after_prepare_goes_into_a_hip_graph(fmt):
+    """sp_prepare builds everything a product needs: the very first sp_matmul afterwards neither allocates nor
+    synchronises, so it can be captured, and the handle reports that no product had to prepare anything."""
+    w = _binned_case() if fmt == "csr" else W.cfg5_zipf_csc_spmm(1 << 15, 1 << 15)
+    N = 8
+    Bh = w.dense_operand(N)
+    x, Bd = dev(Bh[:, 0].copy()), dev(Bh)
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals)
+    assert sp.sp_tensor_info(A).spmvKernel == 0
+    sp.sp_prepare(A, 1)
+    sp.sp_prepare(A, N)
+    info = sp.sp_tensor_info(A)
+    say("case prepare then capture", fmt, "spmv kernel", info.spmvKernel, "derived bytes", info.derivedBytes, "storage", info.storageBytes)
+    assert info.lazyPrepares == 0 and info.spmvKernel in (1, 2, 3, 4) and info.derivedBytes > 0
+    if fmt == "csr":
+        assert info.spmvKernel == 4
+    y = torch.full((w.shape[0],), float("nan"), dtype=x.dtype, device=DEV)
+    C = torch.full((w.shape[0], N), float("nan"), dtype=x.dtype, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                      # the first products of this tensor
+        sp.sp_matmul(A, x, y)
+        sp.sp_matmul(A, Bd, C)
+    assert sp.sp_tensor_info(A).lazyPrepares == 0
+    ref, mag = oracle.matmul_coo(w.shape, w.rows, w.cols, w.vals, Bh)
+    for replay in range(3):
+        y.fill_(float("nan")); C.fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device=DEV).sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_product_close(C, ref, mag, w.dtype, "captured first SpMM, replay %d" % replay)
+        assert_product_close(y, ref[:, :1], mag[:, :1], w.dtype, "captured first SpMV, replay %d" % replay)
+        assert bool(torch.isfinite(scratch))
+    sp.sp_prepare(A, N)                                # again: nothing to do
+    assert sp.sp_tensor_info(A).derivedBytes == info.derivedBytes
+
+
+def test_without_prepare_the_first_product_prepares_and_says_so():
+    w = _binned_case()
+    x = dev(w.dense_operand(1)[:, 0].copy())
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
+    y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+    for call in range(3):
+        sp.sp_matmul(A, x, y)
+    info = sp.sp_tensor_info(A)
+    assert info.lazyPrepares == 1 and info.spmvKernel == 4
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 2)    # another kernel is asked for: decided again, once
+    assert sp.sp_tensor_info(A).spmvKernel == 0
+    sp.sp_matmul(A, x, y); sp.sp_matmul(A, x, y)
+    info = sp.sp_tensor_info(A)
+    assert info.lazyPrepares == 2 and info.spmvKernel == 2
+
+
+@pytest.mark.parametrize("maker,expect", [
+    (lambda: W.cfg1_uniform_csr(), 1),                                           # small and even: lanes per row
+    (lambda: W.cfg2_powerlaw_csr(20000, 20000, cap=3000), 2),                    # medium: the stream kernel
+    (lambda: W.cfg2_powerlaw_csr(1 << 17, 1 << 17), 2),                          # 2 M entries but x is only 1 MB: still the stream kernel
+    (lambda: W.cfg4_hypersparse_dcsr(1 << 21, 1 << 21), 2),                      # few stored rows: no binned copy
+])
+def test_automatic_spmv_choice_below_the_binned_threshold_is_reproducible(maker, expect):
+    """The binned kernel adds a row's products in an order that depends on timing; every automatic choice below its
+    size threshold (2^21 entries, x above 3 MB, 256 row blocks) must give the same bits on every call."""
+    w = maker()
+    A = gpu_pack(w.level_types, w.dim_ordering, w.shape, [w.rows, w.cols], w.vals)
+    x = dev(w.dense_operand(1)[:, 0].copy())
+    sp.sp_prepare(A, 1)
+    k = sp.sp_tensor_info(A).spmvKernel
+    say("case automatic choice", w.shape, w.nnz, "-> kernel", k)
+    assert k == expect
+    first = None
+    for call in range(4):
+        y = torch.empty(w.shape[0], dtype=torch.float64, device=DEV)
+        sp.sp_matmul(A, x, y)
+        torch.cuda.synchronize()
+        if first is None:
+            first = y
+        assert torch.equal(y, first), "call %d differs" % call
