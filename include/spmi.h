@@ -113,6 +113,20 @@ sp_status sp_prepare(sp_tensor *A, int64_t N, void *stream);
 sp_status sp_matmul(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
                     void *C, int64_t ldc, int accumulate, void *stream);
 
+/* sp_matmul for callers that cannot allocate device memory or have it allocated on their behalf: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as sp_matmul, for a
+ * row-major tensor with a compressed innermost level (CSR, DCSR) and N >= 2 columns with N * element size a multiple of
+ * 16 and at most 64 such 16-byte pieces per row, B, C and their leading dimensions 16-byte aligned (the product cut by
+ * stored entries; SP_ERR_UNSUPPORTED otherwise, also for a tensor whose tables a product would still have to build).
+ * The per-block partial rows that kernel keeps between its two launches live in a fixed array of 16 MiB inside the
+ * library's code object on each GPU instead of a buffer from the tensor's allocator: the call needs
+ * (stored entries / 1024, rounded up) * N * element size bytes of it and returns SP_ERR_TOO_LARGE beyond 16 MiB.  It calls no
+ * allocator, neither the tensor's nor HIP's, and does not synchronise.  All calls on one GPU share that array: calls that
+ * overlap on one GPU (different streams, different tensors) race; stream-ordered calls do not.  Results are the same
+ * bits as sp_matmul's with SP_TUNE_SPMM_KERNEL 0 or 3. */
+sp_status sp_matmul_noalloc(const sp_tensor *A, const void *B, int64_t N, int64_t ldb,
+                            void *C, int64_t ldc, int accumulate, void *stream);
+
 /* The paper's pointers / indices / values operations (Section 4.2): borrowed DEVICE
  * pointers, valid until sp_tensor_free.  `level` is a storage level, not a dimension.  *len is in
  * elements of the tensor's pos / crd width (sp_tensor_info) or dtype. */

@@ -15,7 +15,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_COORD_RANGE", "SP_ERR_DUPLICATE", "SP_ERR_SHAPE", "SP_ERR_DTYPE", "SP_ERR_UNSUPPORTED",
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
-EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_prepare", "sp_matmul", "sp_pos", "sp_crd", "sp_values",
+EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_prepare", "sp_matmul", "sp_matmul_noalloc", "sp_pos", "sp_crd", "sp_values",
            "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_stream_read", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
@@ -63,6 +63,8 @@ def load_library():
     L.sp_tensor_free.argtypes = [vp]
     L.sp_matmul.restype = ci
     L.sp_matmul.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
+    L.sp_matmul_noalloc.restype = ci
+    L.sp_matmul_noalloc.argtypes = [vp, vp, i64, i64, vp, i64, ci, vp]
     L.sp_prepare.restype = ci
     L.sp_prepare.argtypes = [vp, i64, vp]
     for f in (L.sp_pos, L.sp_crd):
@@ -208,6 +210,15 @@ def sp_matmul(A, B, C, accumulate=False, N=None, ldb=None, ldc=None):
     if ldc is None:
         ldc = 1 if C.dim() == 1 else int(C.stride(0))
     _check(L.sp_matmul(A._h, B.data_ptr(), N, ldb, C.data_ptr(), ldc, int(bool(accumulate)), _stream_ptr()), "in sp_matmul")
+    return C
+
+
+def sp_matmul_noalloc(A, B, C, accumulate=False):
+    """sp_matmul through the entry point that allocates nothing (SpMM of a CSR / DCSR tensor, scratch inside the library)."""
+    L = load_library()
+    assert B.is_cuda and C.is_cuda and B.dtype == A.dtype and C.dtype == A.dtype and B.dim() == 2 and C.dim() == 2
+    _check(L.sp_matmul_noalloc(A._h, B.data_ptr(), int(B.shape[1]), int(B.stride(0)), C.data_ptr(), int(C.stride(0)), int(bool(accumulate)),
+                               _stream_ptr()), "in sp_matmul_noalloc")
     return C
 
 

@@ -721,6 +721,49 @@ struct row_view {
     }
 };
 
+// The SpMM cut by stored entries plus its fix-up, with the per-block carries in `carry` (room for N values per block).
+// N * sizeof(VT) is a multiple of 16 with at most 64 such pieces per row; B, C and their leading dimensions are 16-byte aligned.
+template <typename PT, typename CT, typename VT>
+sp_status spmm_windows_launch(const sp_tensor *A, const row_view<PT, CT> &rv, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc,
+                              int accumulate, VT *carry, hipStream_t st)
+{
+    constexpr int64_t V = 16 / sizeof(VT);
+    const int64_t lr = N / V;
+    const PT *pos = rv.pos;
+    const CT *crd = (const CT *)A->crd[1];
+    const VT *val = (const VT *)A->values;
+    const CT *rowid = rv.rowid;
+    const int64_t nrows = rv.nrows, nnz = A->ncrd[1];
+    const sp_rowblocks *rowblocks = rv.rowblocks;
+    const int64_t nb = rowblocks->nblocks;
+    const bool small = sizeof(CT) == 4 && (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B (64-bit coordinates keep 64-bit offsets)
+#define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
+    hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,    \
+                       (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, carry, accumulate, (int)lr)
+#define SPMI_SPMM_WIN(LR)                           \
+    do {                                            \
+        if (small) SPMI_SPMM_WIN_O(LR, uint32_t);   \
+        else SPMI_SPMM_WIN_O(LR, uint64_t);         \
+    } while (0)
+    if (lr == 1) SPMI_SPMM_WIN(1);
+    else if (lr == 2) SPMI_SPMM_WIN(2);
+    else if (lr == 4) SPMI_SPMM_WIN(4);
+    else if (lr == 8) SPMI_SPMM_WIN(8);
+    else if (lr == 16) SPMI_SPMM_WIN(16);
+    else if (lr == 32) SPMI_SPMM_WIN(32);
+    else if (lr == 64) SPMI_SPMM_WIN(64);
+    else SPMI_SPMM_WIN(0);                    // any other number of 16-byte pieces per row, up to 64
+#undef SPMI_SPMM_WIN
+#undef SPMI_SPMM_WIN_O
+    SP_HIP(hipGetLastError());
+    if (nb > 1) {
+        hipLaunchKernelGGL((spmm_windows_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads / 64)), dim3(kThreads), 0, st, pos,
+                           rowid, (const int32_t *)rowblocks->start, nb, N, (const VT *)carry, C, ldc);
+        SP_HIP(hipGetLastError());
+    }
+    return SP_OK;
+}
+
 // The inspector step of the matrix-times-vector product (Section 6.2): decides which SpMV kernel the tensor's products run
 // and builds the regrouped copy that kernel reads.  Measures once how scattered the columns are (one pass over crd, one
 // synchronisation), may allocate through the tensor's allocator.  The decision is kept in A->plan_spmv.
@@ -903,32 +946,7 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
                 ++A->lazy_prepares;
                 SP_TRY((prepare_spmm_t<PT, CT, VT>(A, N, st)));
             }
-            const bool small = sizeof(CT) == 4 && (uint64_t)A->shape[1] * (uint64_t)ldb * sizeof(VT) < ((uint64_t)1 << 32);     // 32-bit byte offsets into B (64-bit coordinates keep 64-bit offsets)
-#define SPMI_SPMM_WIN_O(LR, OT)                                                                                               \
-    hipLaunchKernelGGL((spmm_windows_vec_kernel<PT, CT, VT, LR, OT>), dim3((unsigned)nb), dim3(kThreads), 0, st, pos, crd, val, rowid,    \
-                       (const int32_t *)rowblocks->start, nrows, nnz, B, ldb, C, ldc, (VT *)A->spmm_carry, accumulate, (int)lr)
-#define SPMI_SPMM_WIN(LR)                           \
-    do {                                            \
-        if (small) SPMI_SPMM_WIN_O(LR, uint32_t);   \
-        else SPMI_SPMM_WIN_O(LR, uint64_t);         \
-    } while (0)
-            if (lr == 1) SPMI_SPMM_WIN(1);
-            else if (lr == 2) SPMI_SPMM_WIN(2);
-            else if (lr == 4) SPMI_SPMM_WIN(4);
-            else if (lr == 8) SPMI_SPMM_WIN(8);
-            else if (lr == 16) SPMI_SPMM_WIN(16);
-            else if (lr == 32) SPMI_SPMM_WIN(32);
-            else if (lr == 64) SPMI_SPMM_WIN(64);
-            else SPMI_SPMM_WIN(0);                    // any other number of 16-byte pieces per row, up to 64
-#undef SPMI_SPMM_WIN
-#undef SPMI_SPMM_WIN_O
-            SP_HIP(hipGetLastError());
-            if (nb > 1) {
-                hipLaunchKernelGGL((spmm_windows_fixup_kernel<PT, CT, VT>), dim3(grid_for(nb - 1, kThreads / 64)), dim3(kThreads), 0, st, pos,
-                                   rowid, (const int32_t *)rowblocks->start, nb, N, (const VT *)A->spmm_carry, C, ldc);
-                SP_HIP(hipGetLastError());
-            }
-            return SP_OK;
+            return spmm_windows_launch<PT, CT, VT>(A, rv, B, N, ldb, C, ldc, accumulate, (VT *)A->spmm_carry, st);
         }
         if (fits && A->tune_spmm != 1) {
 #define SPMI_SPMM_VEC(LR)                                                                                                     \
@@ -1099,4 +1117,61 @@ sp_status spmi_matmul_dense_inner(const sp_tensor *A, const void *B, int64_t N, 
                                   hipStream_t st)
 {
     SPMI_DISPATCH_TYPES(dense_inner_t, A);
+}
+
+// ---- the product for callers that cannot allocate ------------------------------------------------------------------
+// The per-block carries of the SpMM cut by stored entries live in this array instead of a buffer from the tensor's
+// allocator.  Every GPU the library runs on holds its own copy until the process ends; host code reaches it only through
+// the address hipGetSymbolAddress returns for the current device (the name itself is a host-side stand-in).
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];               // per device, filled in on the first call on that device
+
+static sp_status static_scratch(void **out)
+{
+    int device = -1;
+    SP_HIP(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return SP_ERR_UNSUPPORTED;
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        SP_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return SP_ERR_HIP;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return SP_OK;
+}
+
+namespace {
+template <typename PT, typename CT, typename VT>
+sp_status noalloc_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT *C, int64_t ldc, int accumulate, hipStream_t st)
+{
+    const row_view<PT, CT> rv(A);
+    constexpr int64_t V = 16 / sizeof(VT);
+    const int64_t lr = N / V;
+    const bool aligned = N % V == 0 && ldb % V == 0 && ldc % V == 0 && (uintptr_t)B % 16 == 0 && (uintptr_t)C % 16 == 0;
+    if (!rv.rowblocks->start || !aligned || lr < 1 || lr > 64) return SP_ERR_UNSUPPORTED;
+    if ((size_t)rv.rowblocks->nblocks * (size_t)N * sizeof(VT) > kStaticScratchBytes) return SP_ERR_TOO_LARGE;
+    void *carry = nullptr;
+    SP_TRY(static_scratch(&carry));
+    if (rv.dcsr && !accumulate) SP_TRY((zero_c<PT, CT, VT>(C, A->shape[0], N, ldc, st)));   // rows that are not stored become zero
+    if (rv.nrows == 0) return SP_OK;
+    // nothing in the carries has to start at zero: a block writes its carry before the fix-up reads it, and the fix-up
+    // reads only carries of blocks whose first row began in an earlier block
+    return spmm_windows_launch<PT, CT, VT>(A, rv, B, N, ldb, C, ldc, accumulate, (VT *)carry, st);
+}
+}  // namespace
+
+extern "C" sp_status sp_matmul_noalloc(const sp_tensor *A, const void *B, int64_t N, int64_t ldb, void *C, int64_t ldc, int accumulate,
+                                       void *stream)
+{
+    if (!A) return SP_ERR_NULL;
+    if (A->enc.rank != 2) return SP_ERR_RANK;
+    if (N < 0 || ldb < N || ldc < N || ldb < 1 || ldc < 1) return SP_ERR_SHAPE;
+    if (N == 0 || A->shape[0] == 0) return SP_OK;
+    if (!C || (!B && A->shape[1] > 0)) return SP_ERR_NULL;
+    if (A->enc.lt[1] != SP_COMPRESSED || A->enc.perm[0] != 0 || A->tables_pending) return SP_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    SPMI_DISPATCH_TYPES(noalloc_t, A);
 }
