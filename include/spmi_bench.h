@@ -29,6 +29,13 @@ sp_status sp_stream_copy(void *dst /* DEVICE */, const void *src /* DEVICE */, s
  * written): the read-only streaming rate, the yardstick for kernels whose traffic is mostly reads. */
 sp_status sp_stream_read(const void *src /* DEVICE */, size_t bytes, void *sink /* DEVICE */, void *stream);
 
+/* Which sort the storage builder (sp_pack, sp_pack_sum) uses from now on, process-wide: 0 = it chooses (the default: most
+ * significant digit first with an LDS finishing pass for a million entries or more whose top key bits are spread evenly
+ * enough, least significant digit first otherwise), 1 = always least significant digit first, 2 = always most significant
+ * digit first (any size below 2^31 entries: how the tests reach its rare paths with small inputs).  Both sorts are stable
+ * and give the same storage bit for bit.  Returns SP_ERR_UNSUPPORTED for another value. */
+sp_status sp_pack_sort_mode(int mode);
+
 #ifdef __cplusplus
 }
 #endif

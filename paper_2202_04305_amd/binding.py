@@ -16,7 +16,7 @@ STATUS_NAMES = ["SP_OK", "SP_ERR_NULL", "SP_ERR_RANK", "SP_ERR_LEVEL_TYPE", "SP_
                 "SP_ERR_TOO_LARGE", "SP_ERR_ALLOC", "SP_ERR_HIP"]
 
 EXPORTS = ["sp_encode", "sp_encoding_free", "sp_pack", "sp_tensor_free", "sp_prepare", "sp_matmul", "sp_matmul_noalloc", "sp_pos", "sp_crd", "sp_values",
-           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_stream_read", "sp_status_str", "sp_last_hip_error"]
+           "sp_unpack", "sp_convert", "sp_sddmm", "sp_mttkrp", "sp_spgemm", "sp_add", "sp_tensor_info", "sp_tensor_tune", "sp_profile_read", "sp_stream_copy", "sp_stream_read", "sp_pack_sort_mode", "sp_status_str", "sp_last_hip_error"]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -92,6 +92,8 @@ def load_library():
     L.sp_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     L.sp_stream_copy.restype = ci
     L.sp_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.sp_pack_sort_mode.restype = ci
+    L.sp_pack_sort_mode.argtypes = [ci]
     L.sp_stream_read.restype = ci
     L.sp_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     L.sp_status_str.restype = ctypes.c_char_p
@@ -343,3 +345,8 @@ def sp_stream_copy(dst, src):
 def sp_stream_read(src, sink):
     nbytes = src.numel() * src.element_size()
     _check(load_library().sp_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr()), "in sp_stream_read")
+
+
+def sp_pack_sort_mode(mode):
+    """0 = the storage builder chooses its sort, 1 = least significant digit first, 2 = most significant digit first."""
+    _check(load_library().sp_pack_sort_mode(int(mode)), "in sp_pack_sort_mode")

@@ -362,3 +362,10 @@ extern "C" sp_status sp_stream_read(const void *src, size_t bytes, void *sink, v
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
+
+extern "C" sp_status sp_pack_sort_mode(int mode)
+{
+    if (mode < 0 || mode > 2) return SP_ERR_UNSUPPORTED;
+    g_pack_sort_mode.store(mode, std::memory_order_relaxed);
+    return SP_OK;
+}

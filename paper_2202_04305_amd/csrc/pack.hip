@@ -249,6 +249,40 @@ __global__ __launch_bounds__(kThreads) void make_keys_kernel(level_args a, int64
     if (bad) atomicOr(&flags[0], 1);
 }
 
+// The same, a block per tile of kSpmiMsdTile entries, filling in on the way what the most-significant-digit-first sort would
+// otherwise read the keys for once more (sp_msd_plan): the tile's counts by the top digit and the sampled histogram.
+__global__ __launch_bounds__(kThreads) void make_keys_counting_kernel(level_args a, int64_t nnz, uint64_t *__restrict__ keys, int *__restrict__ flags,
+                                                                      sp_msd_plan plan)
+{
+    __shared__ uint32_t h[256];
+    static_assert(kThreads == 256, "one thread per digit");
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t tile0 = (int64_t)blockIdx.x * kSpmiMsdTile;
+    bool any_bad = false;
+#pragma unroll 4
+    for (int r = 0; r < kSpmiMsdTile / kThreads; ++r) {
+        const int64_t e = tile0 + r * kThreads + threadIdx.x;
+        if (e < nnz) {
+            uint64_t key = 0;
+            bool bad = false;
+            for (int l = 0; l < a.rank; ++l) {
+                const int64_t c = a.coord[l][e];
+                bad |= (c < 0) | (c >= a.size[l]);
+                key = key * (uint64_t)a.size[l] + (uint64_t)c;
+            }
+            if (bad) key = 0;
+            any_bad |= bad;
+            keys[e] = key;
+            atomicAdd(&h[(uint32_t)(key >> plan.digit_shift) & 255u], 1u);
+            if ((e & 63) == 0) atomicAdd(&plan.samp[(uint32_t)(key >> plan.samp_shift) & 0xffffu], 1u);
+        }
+    }
+    if (any_bad) atomicOr(&flags[0], 1);
+    __syncthreads();
+    plan.ctr[(size_t)threadIdx.x * plan.tiles + blockIdx.x] = h[threadIdx.x];
+}
+
 __global__ __launch_bounds__(kThreads) void check_duplicates_kernel(const uint64_t *__restrict__ keys, int64_t nnz, int *__restrict__ flags)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -502,6 +536,20 @@ static sp_status radix_sort_pairs_t(uint64_t *keys, const P *vals_in, int64_t n,
     *keys_out = kin;
     *vals_out = vin;
     return SP_OK;
+}
+
+std::atomic<int> g_pack_sort_mode{0};
+
+sp_status spmi_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                          const sp_msd_plan *plan, uint64_t **keys_out, const void **vals_out)
+{
+    const int mode = g_pack_sort_mode.load(std::memory_order_relaxed);
+    uint32_t *ctr = plan ? plan->ctr : nullptr, *samp = plan ? plan->samp : nullptr;
+    bool msd = false;
+    if (mode == 2) msd = n >= 1 && n < ((int64_t)1 << 31);
+    else if (mode == 0) SP_TRY(spmi_msd_sort_suits(keys, n, key_bits, tmp, st, samp, &msd));
+    if (msd) return spmi_msd_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, ctr, keys_out, vals_out);
+    return spmi_radix_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, keys_out, vals_out);
 }
 
 sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
@@ -888,7 +936,7 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
         SP_HIP(hipGetLastError());
         uint64_t *sorted_keys = nullptr;
         const void *sorted_vals = nullptr;
-        SP_TRY(spmi_radix_sort_pairs(keys, A->values, vbytes, nnz, key_bits, tmp, st, &sorted_keys, &sorted_vals));
+        SP_TRY(spmi_sort_pairs(keys, A->values, vbytes, nnz, key_bits, tmp, st, nullptr, &sorted_keys, &sorted_vals));
         hipLaunchKernelGGL(bin_decode_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift, rshift,
                            make_divisor((uint64_t)m), rowblocks, g->lcol, g->lrow);
         SP_HIP(hipGetLastError());
@@ -1041,7 +1089,7 @@ __global__ __launch_bounds__(kThreads) void mark_heads_kernel(const uint64_t *__
 }
 
 static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void *payload, int key_bits, bool sum_duplicates, int *flags,
-                           sp_scratch &tmp, const sp_mem &mem, hipStream_t st)
+                           sp_scratch &tmp, const sp_mem &mem, hipStream_t st, const sp_msd_plan *plan = nullptr)
 {
     const sp_encoding *enc = &t->enc;
     const int rank = enc->rank;
@@ -1051,9 +1099,7 @@ static sp_status pack_core(sp_tensor *t, int64_t nnz, uint64_t *keys, const void
     uint64_t *parentA = nullptr, *parentB = nullptr;      // allocated when a level needs them
     uint32_t *child = (uint32_t *)tmp.get(cnt * 4);
     if (!child) return SP_ERR_ALLOC;
-    if (nnz > 0) {
-        SP_TRY(spmi_radix_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st, &keys, &payload));
-    }
+    if (nnz > 0) SP_TRY(spmi_sort_pairs(keys, payload, vsz0, nnz, key_bits, tmp, st, plan, &keys, &payload));
     // The duplicate check rides along with the first compressed level's kernel (it reads the same neighbouring keys); it
     // runs on its own only where no such kernel comes before its result is needed.
     bool dup_pending = !sum_duplicates && nnz > 0;
@@ -1302,6 +1348,8 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
         const size_t cnt = (size_t)(nnz > 0 ? nnz : 1);
         uint64_t *keys = (uint64_t *)tmp.get(cnt * 8);
         int *flags = (int *)tmp.get(64);
+        sp_msd_plan plan;
+        memset(&plan, 0, sizeof(plan));
         do {
             if (!keys || !flags) { status = SP_ERR_ALLOC; break; }
             if ((status = spmi_fill_zero(flags, 64, st)) != SP_OK) break;
@@ -1310,10 +1358,14 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
                 memset(&la, 0, sizeof(la));
                 la.rank = rank;
                 for (int l = 0; l < rank; ++l) { la.coord[l] = coords[enc->perm[l]]; la.size[l] = t->size[l]; }
-                hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz, keys, flags);
+                if ((status = spmi_msd_plan(nnz, key_bits, tmp, st, &plan)) != SP_OK) break;
+                if (plan.ctr)
+                    hipLaunchKernelGGL(make_keys_counting_kernel, dim3(plan.tiles), dim3(kThreads), 0, st, la, nnz, keys, flags, plan);
+                else
+                    hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, la, nnz, keys, flags);
                 if (hipGetLastError() != hipSuccess) { status = SP_ERR_HIP; break; }
             }
-            status = pack_core(t, nnz, keys, values, key_bits, false, flags, tmp, mem, st);   // the values are the sort's payload
+            status = pack_core(t, nnz, keys, values, key_bits, false, flags, tmp, mem, st, &plan);   // the values are the sort's payload
         } while (0);
         if (status != SP_OK) (void)hipStreamSynchronize(st);   // temporaries may still be in use by queued kernels
     }

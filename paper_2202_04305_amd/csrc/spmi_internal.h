@@ -5,6 +5,7 @@
 #include <stddef.h>
 #include <string.h>
 #include <type_traits>
+#include <atomic>
 #include <vector>
 #include "spmi.h"
 #include "spmi_bench.h"
@@ -169,6 +170,28 @@ sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, 
 sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
                                 hipStream_t st, uint64_t **keys_out, const void **vals_out);
 sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
+// ---- msd_sort.hip ----
+// The same sort (same arguments, same stability) with the most significant digits first: two passes over device memory, the
+// rest inside the LDS.  Only for inputs that spmi_msd_sort_suits() accepted: enough entries, keys wide enough, and (from a
+// sampled histogram of the top 16 key bits, samp_ready when the caller has it already; synchronises the stream) few entries
+// in groups of equal top 16 key bits too large for the LDS, none of them huge.
+//
+// Whoever makes the keys can fill in, on the way, what the first pass would otherwise read them for (sp_msd_plan, empty when
+// this sort is out of the question): for the tile e / kSpmiMsdTile of entry e, ctr[digit * tiles + tile] counts the entries
+// whose digit is (key >> digit_shift) & 255 (every word written, zero included), and samp[(key >> samp_shift) & 0xffff]
+// counts every 64th entry (e % 64 == 0; samp arrives zeroed).
+constexpr int kSpmiMsdTile = 4096;
+struct sp_msd_plan { uint32_t *ctr, *samp; uint32_t tiles; int digit_shift, samp_shift; };
+sp_status spmi_msd_plan(int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, sp_msd_plan *plan);
+sp_status spmi_msd_sort_suits(const uint64_t *keys, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, uint32_t *samp_ready, bool *suits);
+sp_status spmi_msd_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                              uint32_t *ctr_ready, uint64_t **keys_out, const void **vals_out);
+// Whichever of the two suits (or the one that sp_pack_sort_mode() of the bench header forces); plan: null, or what
+// spmi_msd_plan() handed out and the maker of the keys filled in.
+sp_status spmi_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                          const sp_msd_plan *plan, uint64_t **keys_out, const void **vals_out);
+extern std::atomic<int> g_pack_sort_mode;
+// ---- pack.hip ----
 // The storage of a tensor whose n entries are given as linearised keys (level order, mixed radix over the level sizes)
 // with the value bits as payload, both temporaries of `tmp`; entries with equal keys are added up in the order given.
 sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype dt, sp_alloc_fn alloc, sp_free_fn free_, void *ctx,

@@ -20,7 +20,7 @@ def test_header_symbols_are_exported():
     """Both headers: the product interface (spmi.h) and the measurement hooks (spmi_bench.h)."""
     L = sp.load_library()
     product, hooks = declared_in("spmi.h"), declared_in("spmi_bench.h")
-    assert hooks == {"sp_profile_read", "sp_stream_copy", "sp_stream_read"}
+    assert hooks == {"sp_profile_read", "sp_stream_copy", "sp_stream_read", "sp_pack_sort_mode"}
     assert not (product & hooks)
     assert "sp_prepare" in product
     assert product | hooks == set(binding.EXPORTS)
