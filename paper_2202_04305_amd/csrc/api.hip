@@ -112,7 +112,7 @@ extern "C" sp_status sp_tensor_info(const sp_tensor *t, sp_info *info)
     int64_t extra = (t->rowblocks.nblocks + t->nz_rowblocks.nblocks) * (4 + v) + (int64_t)t->dense_partial_bytes + (int64_t)t->spmm_carry_bytes +
                     (int64_t)t->sddmm_bt_bytes + (int64_t)t->mttkrp_carry_bytes + (int64_t)t->mttkrp_pad_bytes[0] + (int64_t)t->mttkrp_pad_bytes[1];
     if (t->nz_pos) extra += t->nz_rows * (t->enc.cw / 8) + (t->nz_rows + 1) * (t->enc.pw / 8);
-    if (t->bins) extra += t->bins->nnz * (2 * v + 4) + ((int64_t)t->bins->panels * t->bins->rowblocks + 1) * 8;
+    if (t->bins) extra += t->bins->np * (2 * v + 4) + t->bins->np / 8 * 4 + ((int64_t)t->bins->panels + t->bins->rowblocks + 2) * 8;
     const sp_tensor *copies[2] = {t->segments ? t->segments->seg : nullptr, t->transposed};
     for (const sp_tensor *c : copies)
         if (c) {

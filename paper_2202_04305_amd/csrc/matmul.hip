@@ -201,124 +201,98 @@ constexpr int kBinThreads = 1024;
 constexpr int kBinPW = 1 << kSpmiBinPanelShift;
 constexpr int kBinRB = 1 << kSpmiBinRowShift;
 
-// First pass: block (panel, piece) loads the panel's slice of x into LDS, then streams its share of the panel's entries:
-// prod[e] = val[e] * x[panel * PW + lcol[e]], 16 bytes of values per lane and load.
+// First pass: block (panel, piece) loads the panel's slice of x into LDS, then streams its share of the panel's entries, 16 bytes
+// of values per lane and load: the product of entry e = val[e] * x[panel * PW + lcol[e]] goes to the row-block-major array, to
+// slot e % 8 of the group that gdst names for e's group of 8.  Padding entries carry value 0 and column PW, where the slice
+// holds a zero, so that they give 0 whatever x holds.
 template <typename VT>
 __global__ __launch_bounds__(kBinThreads) void spmv_bins_multiply_kernel(const VT *__restrict__ val, const uint16_t *__restrict__ lcol,
-                                                                         const int64_t *__restrict__ off, int panels, int rowblocks,
-                                                                         int pieces, int64_t n, const VT *__restrict__ x, int64_t ldb,
+                                                                         const uint32_t *__restrict__ gdst, const int64_t *__restrict__ pstart,
+                                                                         int panels, int pieces, int64_t n, const VT *__restrict__ x, int64_t ldb,
                                                                          VT *__restrict__ prod)
 {
     constexpr int V = 16 / sizeof(VT);
     typedef VT vec_t __attribute__((ext_vector_type(V)));
     typedef uint16_t idx_t __attribute__((ext_vector_type(V)));
-    __shared__ VT xs[kBinPW];
+    __shared__ VT xs[kBinPW + V];
     // blocks go to the eight XCDs in turn: the pieces of one panel are given to blocks b, b + 8, b + 16, ... so that they
     // share an L2 and the panel's slice of x is fetched from memory once, not once per piece
     const int grp = 8 * pieces;
     const int p = (int)(blockIdx.x / grp) * 8 + (int)(blockIdx.x % 8), q = (int)(blockIdx.x / 8) % pieces;
     if (p >= panels) return;                           // whole block (the panel count is rounded up to eight)
-    const int64_t pa = off[(int64_t)p * rowblocks], pb = off[(int64_t)(p + 1) * rowblocks];
-    auto cut = [&](int k) -> int64_t {                 // piece boundaries: multiples of V inside the panel
+    const int64_t pa = pstart[p], pb = pstart[p + 1];  // multiples of 8
+    auto cut = [&](int k) -> int64_t {                 // piece boundaries: multiples of 8 inside the panel
         if (k <= 0) return pa;
         if (k >= pieces) return pb;
-        const int64_t c = (pa + (pb - pa) * k / pieces) & ~(int64_t)(V - 1);
-        return c < pa ? pa : c;
+        return (pa + (pb - pa) * k / pieces) & ~(int64_t)7;
     };
     const int64_t a = cut(q), b = cut(q + 1);
     if (a >= b) return;                                // whole block
     const int64_t c0 = (int64_t)p * kBinPW;
-    for (int i = threadIdx.x; i < kBinPW; i += kBinThreads) xs[i] = c0 + i < n ? x[(c0 + i) * ldb] : (VT)0;
+    for (int i = threadIdx.x; i < kBinPW + V; i += kBinThreads) xs[i] = (i < kBinPW && c0 + i < n) ? x[(c0 + i) * ldb] : (VT)0;
     __syncthreads();
-    int64_t a1 = (a + V - 1) & ~(int64_t)(V - 1);      // [a1, b0): whole aligned vectors
-    if (a1 > b) a1 = b;
-    int64_t b0 = b & ~(int64_t)(V - 1);
-    if (b0 < a1) b0 = a1;
-    if ((int64_t)threadIdx.x < a1 - a) { const int64_t e = a + threadIdx.x; prod[e] = val[e] * xs[lcol[e]]; }
-    if ((int64_t)threadIdx.x < b - b0) { const int64_t e = b0 + threadIdx.x; prod[e] = val[e] * xs[lcol[e]]; }
-    const int64_t nvec = (b0 - a1) / V;
-    const vec_t *__restrict__ vv = (const vec_t *)(val + a1);
-    const idx_t *__restrict__ cc = (const idx_t *)(lcol + a1);
-    vec_t *__restrict__ pp = (vec_t *)(prod + a1);
-    constexpr int U = 2;
+    const int64_t nvec = (b - a) / V;
+    const vec_t *__restrict__ vv = (const vec_t *)(val + a);
+    const idx_t *__restrict__ cc = (const idx_t *)(lcol + a);
+    const uint32_t *__restrict__ gg = gdst + (a >> 3);
+    constexpr int U = 2, GV = 8 / V;                   // GV lanes share a group
+    auto store = [&](int64_t j, uint32_t g, const vec_t &r) { *(vec_t *)(prod + ((int64_t)g * 8 + (int64_t)(j % GV) * V)) = r; };
     int64_t j = threadIdx.x;
     for (; j + (U - 1) * kBinThreads < nvec; j += U * kBinThreads) {
         vec_t v[U];
         idx_t c[U];
+        uint32_t g[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) { v[u] = vv[j + u * kBinThreads]; c[u] = cc[j + u * kBinThreads]; }
+        for (int u = 0; u < U; ++u) { v[u] = vv[j + u * kBinThreads]; c[u] = cc[j + u * kBinThreads]; g[u] = gg[(j + u * kBinThreads) / GV]; }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             vec_t r;
 #pragma unroll
             for (int t = 0; t < V; ++t) r[t] = v[u][t] * xs[c[u][t]];
-            pp[j + u * kBinThreads] = r;
+            store(j + u * kBinThreads, g[u], r);
         }
     }
     for (; j < nvec; j += kBinThreads) {
         const vec_t v = vv[j];
         const idx_t c = cc[j];
+        const uint32_t g = gg[j / GV];
         vec_t r;
 #pragma unroll
         for (int t = 0; t < V; ++t) r[t] = v[t] * xs[c[t]];
-        pp[j] = r;
+        store(j, g, r);
     }
 }
 
-// Second pass: block = row block.  Its waves take the panels in turn; the products of bucket (panel, row block) are
-// added into the block's slice of y in LDS (atomic adds: the order in which a row's products meet is not fixed), and
-// the slice is written out at the end.  Every stored row of the row block is written (m of them; rowid[q] is the matrix
-// row of stored row q when not all rows are stored, and the caller has then zeroed the others).
+// Second pass: block = row block.  It streams the row block's products and 16-bit rows, which the first pass left side by side
+// (a lane takes a group of 8 with 16-byte loads), and adds them into the block's slice of y in LDS (atomic adds: the order in
+// which a row's products meet is not fixed); the slice is written out at the end.  Every stored row of the row block is
+// written (m of them; rowid[q] is the matrix row of stored row q when not all rows are stored, and the caller has then
+// zeroed the others).
 template <typename CT, typename VT>
 __global__ __launch_bounds__(kBinThreads) void spmv_bins_reduce_kernel(const VT *__restrict__ prod, const uint16_t *__restrict__ lrow,
-                                                                       const int64_t *__restrict__ off, int panels, int rowblocks,
-                                                                       int64_t m, const CT *__restrict__ rowid, VT *__restrict__ y,
-                                                                       int64_t ldc, int accumulate)
+                                                                       const int64_t *__restrict__ rbstart, int rowblocks, int64_t m,
+                                                                       const CT *__restrict__ rowid, VT *__restrict__ y, int64_t ldc,
+                                                                       int accumulate)
 {
+    constexpr int V = 16 / sizeof(VT), NV = 8 / V;
+    typedef VT vec_t __attribute__((ext_vector_type(V)));
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
     __shared__ VT ys[kBinRB];
-    constexpr int W = kBinThreads / 64, U = 4;
-    // blocks go to the eight XCDs in turn: XCD x gets the row blocks [x * per, (x + 1) * per), so that the buckets of
-    // neighbouring row blocks, which share their first and last lines, are read through the same L2
-    const int per = (rowblocks + 7) / 8;
-    const int rb = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (rb >= rowblocks) return;                       // whole block (the grid is rounded up to eight times per)
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int rb = (int)blockIdx.x;
     for (int i = threadIdx.x; i < kBinRB; i += kBinThreads) ys[i] = (VT)0;
     __syncthreads();
-    constexpr int R = 2;                              // buckets a wave works on side by side
-    for (int p0 = wave; p0 < panels; p0 += 64 * W) {
-        // lane l of the wave fetches the bounds of the bucket of panel p0 + l * W; the loop below hands them out
-        const int pl = p0 + lane * W;
-        int64_t la = 0, lb = 0;
-        if (pl < panels) { la = off[(int64_t)pl * rowblocks + rb]; lb = off[(int64_t)pl * rowblocks + rb + 1]; }
-        for (int l = 0; l < 64 && p0 + l * W < panels; l += R) {
-            int64_t a[R], b[R];
-            int64_t longest = 0;
+    const int64_t g0 = rbstart[rb] >> 3, g1 = rbstart[rb + 1] >> 3;
+    const vec_t *__restrict__ pp = (const vec_t *)prod;
+    const uint4v *__restrict__ rr = (const uint4v *)lrow;
+    for (int64_t g = g0 + threadIdx.x; g < g1; g += kBinThreads) {
+        vec_t v[NV];
 #pragma unroll
-            for (int k = 0; k < R; ++k) {                 // lanes beyond the last panel hold an empty bucket
-                a[k] = __shfl(la, (l + k) & 63, 64);
-                b[k] = l + k < 64 ? __shfl(lb, (l + k) & 63, 64) : a[k];
-                longest = b[k] - a[k] > longest ? b[k] - a[k] : longest;
-            }
-            for (int64_t d = 0; d < longest; d += 64 * U) {
-                VT v[R][U];
-                int r[R][U];
+        for (int k = 0; k < NV; ++k) v[k] = pp[g * NV + k];
+        const uint4v r = rr[g];
 #pragma unroll
-                for (int k = 0; k < R; ++k)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int64_t e = a[k] + d + u * 64 + lane;
-                        const bool in = e < b[k];
-                        v[k][u] = in ? prod[e] : (VT)0;
-                        r[k][u] = in ? (int)lrow[e] : -1;
-                    }
-#pragma unroll
-                for (int k = 0; k < R; ++k)
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (r[k][u] >= 0) atomicAdd(&ys[r[k][u]], v[k][u]);
-            }
+        for (int t = 0; t < 8; ++t) {
+            const unsigned w = (t >> 1) == 0 ? r.x : (t >> 1) == 1 ? r.y : (t >> 1) == 2 ? r.z : r.w;
+            atomicAdd(&ys[(t & 1) ? (w >> 16) : (w & 0xffffu)], v[t / V][t % V]);
         }
     }
     __syncthreads();
@@ -886,12 +860,11 @@ sp_status rowmajor_t(const sp_tensor *A, const VT *B, int64_t N, int64_t ldb, VT
             const sp_bins *g = A->bins;                                       // over the same stored rows as pos / rowid here
             sp_prof_scope prof(A, st);
             hipLaunchKernelGGL((spmv_bins_multiply_kernel<VT>), dim3((unsigned)(ceil_div(g->panels, 8) * 8 * g->pieces)), dim3(kBinThreads), 0, st,
-                               (const VT *)g->val, (const uint16_t *)g->lcol, (const int64_t *)g->off, g->panels, g->rowblocks, g->pieces,
-                               A->shape[1], B, ldb, (VT *)g->prod);
+                               (const VT *)g->val, (const uint16_t *)g->lcol, (const uint32_t *)g->gdst, (const int64_t *)g->pstart, g->panels,
+                               g->pieces, A->shape[1], B, ldb, (VT *)g->prod);
             SP_HIP(hipGetLastError());
-            hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)(ceil_div(g->rowblocks, 8) * 8)), dim3(kBinThreads), 0, st,
-                               (const VT *)g->prod, (const uint16_t *)g->lrow, (const int64_t *)g->off, g->panels, g->rowblocks,
-                               g->nrows, rowid, C, ldc, accumulate);
+            hipLaunchKernelGGL((spmv_bins_reduce_kernel<CT, VT>), dim3((unsigned)g->rowblocks), dim3(kBinThreads), 0, st, (const VT *)g->prod,
+                               (const uint16_t *)g->lrow, (const int64_t *)g->rbstart, g->rowblocks, g->nrows, rowid, C, ldc, accumulate);
             SP_HIP(hipGetLastError());
             return SP_OK;
         }

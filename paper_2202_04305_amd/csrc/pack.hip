@@ -6,6 +6,7 @@
 // prefix-sums the marks into child positions, counts children per parent and prefix-sums
 // the counts into pos; a dense level only folds the coordinate into the position.  The
 // values travel through the sort as the payload and are put in place last.  Only level sizes and the error flags travel to the host.
+#include <algorithm>
 #include "spmi_internal.h"
 
 namespace {
@@ -821,7 +822,8 @@ static void free_bins(const sp_tensor *t)
 {
     if (!t->bins) return;
     sp_mem mem{t->alloc, t->free_, t->ctx};
-    mem.put(t->bins->val); mem.put(t->bins->prod); mem.put(t->bins->lcol); mem.put(t->bins->lrow); mem.put(t->bins->off);
+    mem.put(t->bins->val); mem.put(t->bins->prod); mem.put(t->bins->lcol); mem.put(t->bins->lrow); mem.put(t->bins->gdst);
+    mem.put(t->bins->pstart); mem.put(t->bins->rbstart);
     delete t->bins;
     t->bins = nullptr;
 }
@@ -854,18 +856,63 @@ __device__ inline int64_t bin_bucket_of(uint64_t key, int pshift, int rshift, co
     return (int64_t)(p * (uint64_t)rowblocks + (row >> rshift));
 }
 
-// From the sorted keys: the 16-bit coordinates of every entry.
-__global__ __launch_bounds__(kThreads) void bin_decode_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int rshift,
-                                                              divisor nrows, int64_t rowblocks,
-                                                              uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow)
+// Padded bucket sizes (multiples of 8 entries) in both orders: pcnt[panel * rowblocks + rb] and rcnt[rb * panels + panel];
+// one more element, zero, at the end of each, so that the exclusive scans also give the total.
+__global__ __launch_bounds__(kThreads) void bin_padded_sizes_kernel(const int64_t *__restrict__ off, int64_t panels, int64_t rowblocks,
+                                                                    uint64_t *__restrict__ pcnt, uint64_t *__restrict__ rcnt)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t nbuckets = panels * rowblocks;
+    if (b > nbuckets) return;
+    if (b == nbuckets) { pcnt[b] = 0; rcnt[b] = 0; return; }
+    const uint64_t sz = (uint64_t)((off[b + 1] - off[b] + 7) & ~(int64_t)7);
+    const int64_t p = b / rowblocks, rb = b - p * rowblocks;
+    pcnt[b] = sz;
+    rcnt[rb * panels + p] = sz;
+}
+
+// From the sorted keys: every entry to its place in the padded panel-major arrays (value bits, column inside the panel) and
+// in the padded row-block-major array of rows inside the row block.  The padding keeps what the arrays were filled with.
+template <typename W>
+__global__ __launch_bounds__(kThreads) void bin_place_kernel(const uint64_t *__restrict__ keys, const W *__restrict__ vals, int64_t n, int pshift,
+                                                             int rshift, divisor nrows, int64_t panels, int64_t rowblocks,
+                                                             const int64_t *__restrict__ off, const uint64_t *__restrict__ poff,
+                                                             const uint64_t *__restrict__ roff, W *__restrict__ val,
+                                                             uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow)
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= n) return;
     const uint64_t key = keys[e];
     uint64_t row;
-    (void)bin_bucket_of(key, pshift, rshift, nrows, rowblocks, &row);
-    lcol[e] = (uint16_t)(key & (((uint64_t)1 << pshift) - 1));
-    lrow[e] = (uint16_t)(row & (((uint64_t)1 << rshift) - 1));
+    const int64_t b = bin_bucket_of(key, pshift, rshift, nrows, rowblocks, &row);
+    const int64_t p = b / rowblocks, rb = b - p * rowblocks;
+    const int64_t i = e - off[b];
+    const uint64_t d = poff[b] + (uint64_t)i;
+    val[d] = vals[e];
+    lcol[d] = (uint16_t)(key & (((uint64_t)1 << pshift) - 1));
+    lrow[roff[rb * panels + p] + (uint64_t)i] = (uint16_t)(row & (((uint64_t)1 << rshift) - 1));
+}
+
+// Thread = bucket: where each of its groups of 8 products goes in the row-block-major array (in groups); thread b < panels + 1
+// and b < rowblocks + 1 also write where panel b / row block b start (in entries).
+__global__ __launch_bounds__(kThreads) void bin_groups_kernel(int64_t panels, int64_t rowblocks, const uint64_t *__restrict__ poff,
+                                                              const uint64_t *__restrict__ roff, uint32_t *__restrict__ gdst,
+                                                              int64_t *__restrict__ pstart, int64_t *__restrict__ rbstart)
+{
+    const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t nbuckets = panels * rowblocks;
+    if (b <= panels) pstart[b] = (int64_t)poff[b * rowblocks];
+    if (b <= rowblocks) rbstart[b] = (int64_t)roff[b * panels];
+    if (b >= nbuckets) return;
+    const int64_t p = b / rowblocks, rb = b - p * rowblocks;
+    const uint64_t g0 = poff[b] >> 3, g1 = poff[b + 1] >> 3, r0 = roff[rb * panels + p] >> 3;
+    for (uint64_t g = g0; g < g1; ++g) gdst[g] = (uint32_t)(r0 + (g - g0));
+}
+
+__global__ __launch_bounds__(kThreads) void fill_u16_kernel(uint16_t *__restrict__ p, int64_t n, uint16_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = v;
 }
 
 // off[b] = number of entries in buckets before b (the bucket of a key never decreases along the sorted keys), for
@@ -915,16 +962,13 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
     const int64_t per_panel = nnz / panels;
     g->pieces = (int)(per_panel / 32768 < 1 ? 1 : per_panel / 32768 > 64 ? 64 : per_panel / 32768);
     while (panels * g->pieces < 512 && per_panel / (2 * g->pieces) >= 4096) g->pieces *= 2;      // enough blocks for every CU
-    g->val = mem.get(pad16((size_t)nnz * vbytes));
-    g->prod = mem.get(pad16((size_t)nnz * vbytes));
-    g->lcol = (uint16_t *)mem.get(pad16((size_t)nnz * 2));
-    g->lrow = (uint16_t *)mem.get(pad16((size_t)nnz * 2));
-    g->off = (int64_t *)mem.get(pad16((size_t)(nbuckets + 1) * 8));
-    sp_status status = (g->val && g->prod && g->lcol && g->lrow && g->off) ? SP_OK : SP_ERR_ALLOC;
+    sp_status status = SP_OK;
     auto build = [&]() -> sp_status {
         sp_scratch tmp(mem);
         uint64_t *keys = (uint64_t *)tmp.get((size_t)nnz * 8);
-        if (!keys) return SP_ERR_ALLOC;
+        int64_t *off = (int64_t *)tmp.get((size_t)(nbuckets + 1) * 8);
+        uint64_t *poff = (uint64_t *)tmp.get((size_t)(nbuckets + 1) * 8), *roff = (uint64_t *)tmp.get((size_t)(nbuckets + 1) * 8);
+        if (!keys || !off || !poff || !roff) return SP_ERR_ALLOC;
 #define SPMI_BIN_KEYS(PT, CT)                                                                                                 \
     hipLaunchKernelGGL((bin_keys_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const PT *)pos, m, (const CT *)A->crd[1], \
                        nnz, pshift, keys)
@@ -937,13 +981,44 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
         uint64_t *sorted_keys = nullptr;
         const void *sorted_vals = nullptr;
         SP_TRY(spmi_sort_pairs(keys, A->values, vbytes, nnz, key_bits, tmp, st, nullptr, &sorted_keys, &sorted_vals));
-        hipLaunchKernelGGL(bin_decode_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift, rshift,
-                           make_divisor((uint64_t)m), rowblocks, g->lcol, g->lrow);
-        SP_HIP(hipGetLastError());
+        const divisor dm = make_divisor((uint64_t)m);
         hipLaunchKernelGGL(bin_offsets_kernel, dim3(blocks_for(nbuckets + 1)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift,
-                           rshift, make_divisor((uint64_t)m), rowblocks, nbuckets, g->off);
+                           rshift, dm, rowblocks, nbuckets, off);
+        hipLaunchKernelGGL(bin_padded_sizes_kernel, dim3(blocks_for(nbuckets + 1)), dim3(kThreads), 0, st, (const int64_t *)off, panels, rowblocks,
+                           poff, roff);
         SP_HIP(hipGetLastError());
-        SP_HIP(hipMemcpyAsync(g->val, sorted_vals, (size_t)nnz * vbytes, hipMemcpyDeviceToDevice, st));
+        SP_TRY(spmi_exclusive_scan(poff, nbuckets + 1, 64, tmp, st));
+        SP_TRY(spmi_exclusive_scan(roff, nbuckets + 1, 64, tmp, st));
+        uint64_t total = 0;
+        SP_HIP(hipMemcpyAsync(&total, poff + nbuckets, 8, hipMemcpyDeviceToHost, st));
+        SP_HIP(hipStreamSynchronize(st));
+        const int64_t np = (int64_t)total;                       // entries with every bucket padded to a multiple of 8
+        if (np < nnz || np > nnz + 7 * nbuckets || (np >> 3) > 0xffffffffll) return SP_ERR_UNSUPPORTED;
+        g->np = np;
+        g->val = mem.get(pad16((size_t)np * vbytes));
+        g->prod = mem.get(pad16((size_t)np * vbytes));
+        g->lcol = (uint16_t *)mem.get(pad16((size_t)np * 2));
+        g->lrow = (uint16_t *)mem.get(pad16((size_t)np * 2));
+        g->gdst = (uint32_t *)mem.get(pad16((size_t)(np / 8) * 4));
+        g->pstart = (int64_t *)mem.get(pad16((size_t)(panels + 1) * 8));
+        g->rbstart = (int64_t *)mem.get(pad16((size_t)(rowblocks + 1) * 8));
+        if (!g->val || !g->prod || !g->lcol || !g->lrow || !g->gdst || !g->pstart || !g->rbstart) return SP_ERR_ALLOC;
+        // padding: value 0 times the zero that the first pass keeps behind its slice of x (column 2^pshift), added to row 0
+        SP_TRY(spmi_fill_zero(g->val, pad16((size_t)np * vbytes), st));
+        SP_TRY(spmi_fill_zero(g->lrow, pad16((size_t)np * 2), st));
+        hipLaunchKernelGGL(fill_u16_kernel, dim3(blocks_for(np)), dim3(kThreads), 0, st, g->lcol, np, (uint16_t)((1 << pshift)));
+        if (vbytes == 8)
+            hipLaunchKernelGGL(bin_place_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys,
+                               (const unsigned long long *)sorted_vals, nnz, pshift, rshift, dm, panels, rowblocks, (const int64_t *)off,
+                               (const uint64_t *)poff, (const uint64_t *)roff, (unsigned long long *)g->val, g->lcol, g->lrow);
+        else
+            hipLaunchKernelGGL(bin_place_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys,
+                               (const uint32_t *)sorted_vals, nnz, pshift, rshift, dm, panels, rowblocks, (const int64_t *)off,
+                               (const uint64_t *)poff, (const uint64_t *)roff, (uint32_t *)g->val, g->lcol, g->lrow);
+        const int64_t most = std::max(nbuckets, std::max(panels, rowblocks) + 1);
+        hipLaunchKernelGGL(bin_groups_kernel, dim3(blocks_for(most)), dim3(kThreads), 0, st, panels, rowblocks, (const uint64_t *)poff,
+                           (const uint64_t *)roff, g->gdst, g->pstart, g->rbstart);
+        SP_HIP(hipGetLastError());
         SP_HIP(hipStreamSynchronize(st));
         return SP_OK;
     };

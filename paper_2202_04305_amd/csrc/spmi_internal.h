@@ -42,14 +42,20 @@ struct sp_segments {
 // streaming passes: one multiplies a panel's entries by the panel's slice of x held in LDS and writes the products in
 // place (`prod`), the other adds a row block's products up in an LDS slice of y.  No gather ever leaves the LDS.
 struct sp_bins {
-    void *val = nullptr;              // DEVICE value-typed[nnz], bucket order
-    void *prod = nullptr;             // DEVICE value-typed[nnz]: the products of the running call
-    uint16_t *lcol = nullptr;         // DEVICE [nnz]: column - panel * 2^pshift
-    uint16_t *lrow = nullptr;         // DEVICE [nnz]: stored row - rowblock * 2^rshift
-    int64_t *off = nullptr;           // DEVICE [panels * rowblocks + 1]: first entry of bucket panel * rowblocks + rowblock
-    int64_t nnz = 0, nrows = 0;       // entries, stored rows
+    // Entries regrouped into buckets (column panel, row block), every bucket padded to a multiple of 8 entries (np in all).
+    // Panel-major arrays (buckets of a panel side by side, rows ascending inside a bucket):
+    void *val = nullptr;              // DEVICE value-typed[np]; padding 0
+    uint16_t *lcol = nullptr;         // DEVICE [np]: column - panel * 2^pshift; padding 2^pshift
+    uint32_t *gdst = nullptr;         // DEVICE [np / 8]: group of 8 entries -> its group in the row-block-major arrays
+    int64_t *pstart = nullptr;        // DEVICE [panels + 1]: first entry of each panel
+    // Row-block-major arrays (buckets of a row block side by side):
+    void *prod = nullptr;             // DEVICE value-typed[np]: the products of the running call
+    uint16_t *lrow = nullptr;         // DEVICE [np]: stored row - rowblock * 2^rshift; padding 0
+    int64_t *rbstart = nullptr;       // DEVICE [rowblocks + 1]: first entry of each row block
+    int64_t nnz = 0, np = 0, nrows = 0;   // entries, entries with padding, stored rows
     int panels = 0, rowblocks = 0, pieces = 0;
 };
+
 
 struct sp_tensor {
     sp_encoding enc;
@@ -198,8 +204,14 @@ sp_status spmi_pack_keys(const sp_encoding *enc, const int64_t *shape, sp_dtype 
                          int64_t n, uint64_t *keys, void *payload, sp_scratch &tmp, hipStream_t st, sp_tensor **out);
 sp_status spmi_build_rowblocks(const sp_tensor *t, hipStream_t st);
 sp_status spmi_build_segments(const sp_tensor *A, int64_t row_bytes, int64_t slice_bytes, hipStream_t st);
-constexpr int kSpmiBinPanelShift = 13;                       // columns per panel of the binned copy: 8192 (a 64 KB slice of an f64 x)
-constexpr int kSpmiBinRowShift = 11;                         // rows per row block: 2048 (a 16 KB slice of an f64 y)
+#ifndef SPMI_BIN_PSHIFT
+#define SPMI_BIN_PSHIFT 13
+#endif
+#ifndef SPMI_BIN_RSHIFT
+#define SPMI_BIN_RSHIFT 11
+#endif
+constexpr int kSpmiBinPanelShift = SPMI_BIN_PSHIFT;          // columns per panel of the binned copy: 8192 (a 64 KB slice of an f64 x)
+constexpr int kSpmiBinRowShift = SPMI_BIN_RSHIFT;            // rows per row block: 2048 (a 16 KB slice of an f64 y)
 sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st);
 // How scattered the gathers of a product are: the share of stored entries of the innermost level whose successor is 16 or
 // more coordinates away (or belongs to the next segment).  Measured once per tensor, then cached; synchronises the first time.
