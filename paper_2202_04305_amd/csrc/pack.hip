@@ -828,30 +828,55 @@ static void free_bins(const sp_tensor *t)
     t->bins = nullptr;
 }
 
-// key = ((panel * nrows + stored row) << pshift) | column inside the panel: sorting by it gives panel-major buckets with
-// rows, then columns, ascending inside.  The stored row of entry e is found in pos by binary search.
+// key = (((stored row << pshift) | column inside the panel) << pbits) | panel, pbits a multiple of 8.  The entries come in storage order (rows, then
+// columns, ascending), so a STABLE sort by the low pbits alone (one pass for up to 256 panels) gives panel-major buckets with
+// rows, then columns, ascending inside.  Block = 1024 consecutive entries: the rows they belong to are a short range of pos,
+// found by two searches per block and then searched per entry inside the LDS (a search of all of pos per entry took 4x longer).
+constexpr int kBinKeyTile = 1024, kBinKeyRows = 1024;
 template <typename PT, typename CT>
 __global__ __launch_bounds__(kThreads) void bin_keys_kernel(const PT *__restrict__ pos, int64_t nrows, const CT *__restrict__ crd, int64_t n,
-                                                            int pshift, uint64_t *__restrict__ keys)
+                                                            int pshift, int pbits, uint64_t *__restrict__ keys)
 {
-    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (e >= n) return;
-    int64_t lo = 0, hi = nrows - 1;                    // last row q with pos[q] <= e (empty rows before it share that pos: the last one wins)
-    while (lo < hi) {
-        const int64_t mid = lo + (hi - lo + 1) / 2;
-        if ((int64_t)pos[mid] <= e) lo = mid;
-        else hi = mid - 1;
+    __shared__ int64_t s_row[2];
+    __shared__ int64_t spos[kBinKeyRows];
+    const int64_t e0 = (int64_t)blockIdx.x * kBinKeyTile, e1 = e0 + kBinKeyTile < n ? e0 + kBinKeyTile : n;
+    auto row_of = [&](int64_t e, int64_t lo, int64_t hi) -> int64_t {      // last row q in [lo, hi] with pos[q] <= e (of empty rows the last one wins)
+        while (lo < hi) {
+            const int64_t mid = lo + (hi - lo + 1) / 2;
+            if ((int64_t)pos[mid] <= e) lo = mid;
+            else hi = mid - 1;
+        }
+        return lo;
+    };
+    if (threadIdx.x < 2) s_row[threadIdx.x] = row_of(threadIdx.x == 0 ? e0 : e1 - 1, 0, nrows - 1);
+    __syncthreads();
+    const int64_t r0 = s_row[0], r1 = s_row[1], nr = r1 - r0 + 1;
+    const bool staged = nr <= kBinKeyRows;
+    if (staged) for (int64_t i = threadIdx.x; i < nr; i += kThreads) spos[i] = (int64_t)pos[r0 + i];
+    __syncthreads();
+    for (int64_t e = e0 + threadIdx.x; e < e1; e += kThreads) {
+        int64_t row;
+        if (staged) {
+            int64_t lo = 0, hi = nr - 1;
+            while (lo < hi) {
+                const int64_t mid = lo + (hi - lo + 1) / 2;
+                if (spos[mid] <= e) lo = mid;
+                else hi = mid - 1;
+            }
+            row = r0 + lo;
+        } else {
+            row = row_of(e, r0, r1);
+        }
+        const uint64_t c = (uint64_t)crd[e];
+        keys[e] = (((((uint64_t)row) << pshift) | (c & (((uint64_t)1 << pshift) - 1))) << pbits) | (c >> pshift);
     }
-    const uint64_t c = (uint64_t)crd[e];
-    keys[e] = (((c >> pshift) * (uint64_t)nrows + (uint64_t)lo) << pshift) | (c & (((uint64_t)1 << pshift) - 1));
 }
 
 // bucket (panel * rowblocks + row block) of a key; *row_out = its row
-__device__ inline int64_t bin_bucket_of(uint64_t key, int pshift, int rshift, const divisor &nrows, int64_t rowblocks, uint64_t *row_out)
+__device__ inline int64_t bin_bucket_of(uint64_t key, int pshift, int pbits, int rshift, int64_t rowblocks, uint64_t *row_out)
 {
-    const uint64_t v = key >> pshift;
-    const uint64_t p = div_by(v, nrows);
-    const uint64_t row = v - p * nrows.d;
+    const uint64_t p = key & (((uint64_t)1 << pbits) - 1);
+    const uint64_t row = key >> (pbits + pshift);
     if (row_out) *row_out = row;
     return (int64_t)(p * (uint64_t)rowblocks + (row >> rshift));
 }
@@ -875,7 +900,7 @@ __global__ __launch_bounds__(kThreads) void bin_padded_sizes_kernel(const int64_
 // in the padded row-block-major array of rows inside the row block.  The padding keeps what the arrays were filled with.
 template <typename W>
 __global__ __launch_bounds__(kThreads) void bin_place_kernel(const uint64_t *__restrict__ keys, const W *__restrict__ vals, int64_t n, int pshift,
-                                                             int rshift, divisor nrows, int64_t panels, int64_t rowblocks,
+                                                             int pbits, int rshift, int64_t panels, int64_t rowblocks,
                                                              const int64_t *__restrict__ off, const uint64_t *__restrict__ poff,
                                                              const uint64_t *__restrict__ roff, W *__restrict__ val,
                                                              uint16_t *__restrict__ lcol, uint16_t *__restrict__ lrow)
@@ -884,12 +909,12 @@ __global__ __launch_bounds__(kThreads) void bin_place_kernel(const uint64_t *__r
     if (e >= n) return;
     const uint64_t key = keys[e];
     uint64_t row;
-    const int64_t b = bin_bucket_of(key, pshift, rshift, nrows, rowblocks, &row);
+    const int64_t b = bin_bucket_of(key, pshift, pbits, rshift, rowblocks, &row);
     const int64_t p = b / rowblocks, rb = b - p * rowblocks;
     const int64_t i = e - off[b];
     const uint64_t d = poff[b] + (uint64_t)i;
     val[d] = vals[e];
-    lcol[d] = (uint16_t)(key & (((uint64_t)1 << pshift) - 1));
+    lcol[d] = (uint16_t)((key >> pbits) & (((uint64_t)1 << pshift) - 1));
     lrow[roff[rb * panels + p] + (uint64_t)i] = (uint16_t)(row & (((uint64_t)1 << rshift) - 1));
 }
 
@@ -917,8 +942,8 @@ __global__ __launch_bounds__(kThreads) void fill_u16_kernel(uint16_t *__restrict
 
 // off[b] = number of entries in buckets before b (the bucket of a key never decreases along the sorted keys), for
 // b = 0 .. nbuckets: a binary search per bucket, whatever the sizes of the buckets are.
-__global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int rshift,
-                                                               divisor nrows, int64_t rowblocks, int64_t nbuckets,
+__global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *__restrict__ keys, int64_t n, int pshift, int pbits, int rshift,
+                                                               int64_t rowblocks, int64_t nbuckets,
                                                                int64_t *__restrict__ off)
 {
     const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -926,7 +951,7 @@ __global__ __launch_bounds__(kThreads) void bin_offsets_kernel(const uint64_t *_
     int64_t lo = 0, hi = n;                            // first entry whose bucket is >= b
     while (lo < hi) {
         const int64_t mid = lo + (hi - lo) / 2;
-        if (bin_bucket_of(keys[mid], pshift, rshift, nrows, rowblocks, nullptr) < b) lo = mid + 1;
+        if (bin_bucket_of(keys[mid], pshift, pbits, rshift, rowblocks, nullptr) < b) lo = mid + 1;
         else hi = mid;
     }
     off[b] = lo;
@@ -951,9 +976,11 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
     if (nb128 > (unsigned __int128)nnz + 4096) return SP_ERR_UNSUPPORTED;
     const int64_t nbuckets = (int64_t)nb128;
     const int vbytes = A->dtype == SP_F64 ? 8 : 4;
-    int key_bits = pshift;
-    while (key_bits < 64 && (((unsigned __int128)panels * (unsigned __int128)m) >> (key_bits - pshift)) != 0) ++key_bits;
-    if (key_bits > 63) return SP_ERR_UNSUPPORTED;
+    int pbits = 0, mbits = 0;
+    while (((int64_t)1 << pbits) < panels) ++pbits;
+    pbits = (pbits + 7) & ~7;                        // the sort works on whole 8-bit digits: the panel gets digits of its own
+    while (mbits < 63 && ((int64_t)1 << mbits) < m) ++mbits;
+    if (mbits + pshift + pbits > 63) return SP_ERR_UNSUPPORTED;
     sp_mem mem{A->alloc, A->free_, A->ctx};
     sp_bins *g = new sp_bins();
     A->bins = g;                                         // owned from here on: free_bins() releases whatever was allocated
@@ -970,8 +997,8 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
         uint64_t *poff = (uint64_t *)tmp.get((size_t)(nbuckets + 1) * 8), *roff = (uint64_t *)tmp.get((size_t)(nbuckets + 1) * 8);
         if (!keys || !off || !poff || !roff) return SP_ERR_ALLOC;
 #define SPMI_BIN_KEYS(PT, CT)                                                                                                 \
-    hipLaunchKernelGGL((bin_keys_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const PT *)pos, m, (const CT *)A->crd[1], \
-                       nnz, pshift, keys)
+    hipLaunchKernelGGL((bin_keys_kernel<PT, CT>), dim3((unsigned)ceil_div(nnz, kBinKeyTile)), dim3(kThreads), 0, st, (const PT *)pos, m,    \
+                       (const CT *)A->crd[1], nnz, pshift, pbits, keys)
         if (A->enc.pw == 32 && A->enc.cw == 32) SPMI_BIN_KEYS(int32_t, int32_t);
         else if (A->enc.pw == 32) SPMI_BIN_KEYS(int32_t, int64_t);
         else if (A->enc.cw == 32) SPMI_BIN_KEYS(int64_t, int32_t);
@@ -980,10 +1007,10 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
         SP_HIP(hipGetLastError());
         uint64_t *sorted_keys = nullptr;
         const void *sorted_vals = nullptr;
-        SP_TRY(spmi_sort_pairs(keys, A->values, vbytes, nnz, key_bits, tmp, st, nullptr, &sorted_keys, &sorted_vals));
-        const divisor dm = make_divisor((uint64_t)m);
+        // stable, on the panel bits alone: one pass for up to 256 panels
+        SP_TRY(spmi_radix_sort_pairs(keys, A->values, vbytes, nnz, pbits, tmp, st, &sorted_keys, &sorted_vals));
         hipLaunchKernelGGL(bin_offsets_kernel, dim3(blocks_for(nbuckets + 1)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys, nnz, pshift,
-                           rshift, dm, rowblocks, nbuckets, off);
+                           pbits, rshift, rowblocks, nbuckets, off);
         hipLaunchKernelGGL(bin_padded_sizes_kernel, dim3(blocks_for(nbuckets + 1)), dim3(kThreads), 0, st, (const int64_t *)off, panels, rowblocks,
                            poff, roff);
         SP_HIP(hipGetLastError());
@@ -1009,11 +1036,11 @@ sp_status spmi_build_bins(const sp_tensor *A, hipStream_t st)
         hipLaunchKernelGGL(fill_u16_kernel, dim3(blocks_for(np)), dim3(kThreads), 0, st, g->lcol, np, (uint16_t)((1 << pshift)));
         if (vbytes == 8)
             hipLaunchKernelGGL(bin_place_kernel<unsigned long long>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys,
-                               (const unsigned long long *)sorted_vals, nnz, pshift, rshift, dm, panels, rowblocks, (const int64_t *)off,
+                               (const unsigned long long *)sorted_vals, nnz, pshift, pbits, rshift, panels, rowblocks, (const int64_t *)off,
                                (const uint64_t *)poff, (const uint64_t *)roff, (unsigned long long *)g->val, g->lcol, g->lrow);
         else
             hipLaunchKernelGGL(bin_place_kernel<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, st, (const uint64_t *)sorted_keys,
-                               (const uint32_t *)sorted_vals, nnz, pshift, rshift, dm, panels, rowblocks, (const int64_t *)off,
+                               (const uint32_t *)sorted_vals, nnz, pshift, pbits, rshift, panels, rowblocks, (const int64_t *)off,
                                (const uint64_t *)poff, (const uint64_t *)roff, (uint32_t *)g->val, g->lcol, g->lrow);
         const int64_t most = std::max(nbuckets, std::max(panels, rowblocks) + 1);
         hipLaunchKernelGGL(bin_groups_kernel, dim3(blocks_for(most)), dim3(kThreads), 0, st, panels, rowblocks, (const uint64_t *)poff,
