@@ -20,17 +20,6 @@ constexpr int kScanItems = 8;
 constexpr int kScanTile = kThreads * kScanItems;
 
 template <typename T>
-__device__ __forceinline__ T wave_inclusive_scan(T v, int lane)
-{
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        T o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
-    return v;
-}
-
-template <typename T>
 __global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const T *__restrict__ data, int64_t n, T *__restrict__ sums)
 {
     __shared__ T wsum[kThreads / 64];
@@ -94,127 +83,6 @@ sp_status exclusive_scan_t(T *data, int64_t n, sp_scratch &tmp, hipStream_t st)
     hipLaunchKernelGGL(scan_downsweep_kernel<T>, dim3((unsigned)nt), dim3(kThreads), 0, st, data, n, (const T *)sums);
     SP_HIP(hipGetLastError());
     return SP_OK;
-}
-
-// ---------------------------------------------------------------------------------------
-// LSD radix sort, 8-bit digits, (u64 key, u32 payload)
-// ---------------------------------------------------------------------------------------
-constexpr int kSortRounds = 16;
-constexpr int kSortTile = kThreads * kSortRounds;
-
-__global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, int shift,
-                                                              uint32_t *__restrict__ hist, int nblocks)
-{
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
-    if (tile0 + kSortTile <= n) {                      // a whole tile: two keys per lane and load, all loads of a thread first
-        typedef unsigned long long u2 __attribute__((ext_vector_type(2)));
-        const u2 *__restrict__ kk = (const u2 *)(keys + tile0);
-        u2 k[kSortRounds / 2];
-#pragma unroll
-        for (int r = 0; r < kSortRounds / 2; ++r) k[r] = kk[r * kThreads + threadIdx.x];
-#pragma unroll
-        for (int r = 0; r < kSortRounds / 2; ++r) {
-            atomicAdd(&h[(k[r][0] >> shift) & 255u], 1u);
-            atomicAdd(&h[(k[r][1] >> shift) & 255u], 1u);
-        }
-    } else {
-        for (int r = 0; r < kSortRounds; ++r) {
-            const int64_t i = tile0 + (int64_t)r * kThreads + threadIdx.x;
-            if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
-        }
-    }
-    __syncthreads();
-    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];   // digit-major: one scan gives global offsets
-}
-
-// Lanes of the wave that hold the same digit as this lane (among lanes with valid set).
-__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
-{
-    uint64_t m = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const uint64_t bb = __ballot(bit);
-        m &= bit ? bb : ~bb;
-    }
-    return m;
-}
-
-// One pass of the sort for one tile of kSortTile keys.  Wave w owns the w-th quarter of the tile (stability: tile
-// order = wave, round, lane).  (1) every key gets its rank among the equal digits of its wave, with ballots and a
-// per-wave running count in LDS; (2) the four waves' counts are combined into where each digit starts inside the
-// tile; (3) keys and payloads are placed in LDS in sorted order; (4) they are copied out, so that neighbouring
-// threads write neighbouring addresses of one digit's run instead of 4096 scattered single stores.
-template <typename P>
-__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint64_t *__restrict__ kin, const P *__restrict__ vin,
-                                                                 uint64_t *__restrict__ kout, P *__restrict__ vout,
-                                                                 const uint32_t *__restrict__ offs, int64_t n, int shift, int nblocks)
-{
-    constexpr int W = kThreads / 64, PERW = kSortTile / W;
-    __shared__ uint32_t wrun[W][256];                 // running count of each digit inside each wave's quarter
-    __shared__ uint32_t wbase[W][256];                // where wave w's keys of digit d start inside the sorted tile
-    __shared__ uint32_t gbase[256];                   // global slot of the tile's first key of digit d, minus its tile slot
-    __shared__ uint32_t wsum[W];
-    __shared__ uint64_t skey[kSortTile];
-    __shared__ P sval[kSortTile];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t tile0 = (int64_t)blockIdx.x * kSortTile;
-    const int64_t in_tile = n - tile0 < kSortTile ? n - tile0 : kSortTile;
-#pragma unroll
-    for (int w = 0; w < W; ++w) wrun[w][tid] = 0;
-    uint64_t k[kSortRounds];
-    P v[kSortRounds];
-    uint32_t lpos[kSortRounds];
-#pragma unroll
-    for (int r = 0; r < kSortRounds; ++r) {
-        const int64_t i = tile0 + wave * PERW + r * 64 + lane;
-        k[r] = i < n ? kin[i] : 0;
-        v[r] = i < n ? vin[i] : 0;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < kSortRounds; ++r) {
-        const bool valid = wave * PERW + r * 64 + lane < in_tile;
-        const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
-        const uint64_t m = match_digit(d, valid);
-        const uint32_t before = wrun[wave][d];                    // written by this wave only, in program order
-        lpos[r] = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (valid && (m & ((1ull << lane) - 1ull)) == 0) wrun[wave][d] = before + (uint32_t)__popcll(m);
-    }
-    __syncthreads();
-    {   // thread d: tile count of digit d, exclusive scan over the digits, per-wave starts
-        uint32_t c[W], tot = 0;
-#pragma unroll
-        for (int w = 0; w < W; ++w) { c[w] = wrun[w][tid]; tot += c[w]; }
-        const uint32_t incl = wave_inclusive_scan(tot, lane);
-        if (lane == 63) wsum[wave] = incl;
-        __syncthreads();
-        uint32_t start = incl - tot;
-        for (int w = 0; w < wave; ++w) start += wsum[w];
-        gbase[tid] = offs[(int64_t)tid * nblocks + blockIdx.x] - start;     // unsigned wrap-around is fine: added back below
-#pragma unroll
-        for (int w = 0; w < W; ++w) { wbase[w][tid] = start; start += c[w]; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < kSortRounds; ++r) {
-        if (wave * PERW + r * 64 + lane < in_tile) {
-            const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
-            const uint32_t slot = wbase[wave][d] + lpos[r];
-            skey[slot] = k[r];
-            sval[slot] = v[r];
-        }
-    }
-    __syncthreads();
-    for (int slot = tid; slot < (int)in_tile; slot += kThreads) {
-        const uint64_t key = skey[slot];
-        const uint32_t p = gbase[(uint32_t)(key >> shift) & 255u] + (uint32_t)slot;
-        kout[p] = key;
-        vout[p] = sval[slot];
-    }
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t nwords)
@@ -498,68 +366,6 @@ sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, 
 {
     if (bits == 32) return exclusive_scan_t<uint32_t>((uint32_t *)data, n, tmp, st);
     return exclusive_scan_t<unsigned long long>((unsigned long long *)data, n, tmp, st);
-}
-
-static size_t pad16(size_t b);
-
-// keys: n entries in a temporary of `tmp`, reordered freely; vals_in: n payloads, only read (it may be the caller's own
-// array).  On return *keys_out / *vals_out point at the sorted arrays: temporaries of `tmp`, or the inputs when there
-// was nothing to sort.
-template <typename P>
-static sp_status radix_sort_pairs_t(uint64_t *keys, const P *vals_in, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
-                                    uint64_t **keys_out, const P **vals_out)
-{
-    *keys_out = keys;
-    *vals_out = vals_in;
-    if (n <= 1 || key_bits <= 0) return SP_OK;
-    const int passes = (key_bits + 7) / 8;
-    const int nblocks = (int)ceil_div(n, kSortTile);
-    uint64_t *kalt = (uint64_t *)tmp.get((size_t)n * 8);
-    P *va = (P *)tmp.get(pad16((size_t)n * sizeof(P)));
-    P *vb = passes > 1 ? (P *)tmp.get(pad16((size_t)n * sizeof(P))) : va;
-    uint32_t *hist = (uint32_t *)tmp.get((size_t)256 * nblocks * 4);
-    if (!kalt || !va || !vb || !hist) return SP_ERR_ALLOC;
-    uint64_t *kin = keys, *kout = kalt;
-    const P *vin = vals_in;
-    P *vout = va;
-    for (int p = 0; p < passes; ++p) {
-        const int shift = 8 * p;
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, n, shift, hist, nblocks);
-        SP_HIP(hipGetLastError());
-        SP_TRY(spmi_exclusive_scan(hist, (int64_t)256 * nblocks, 32, tmp, st));
-        hipLaunchKernelGGL(radix_scatter_kernel<P>, dim3(nblocks), dim3(kThreads), 0, st, (const uint64_t *)kin, vin, kout, vout,
-                           (const uint32_t *)hist, n, shift, nblocks);
-        SP_HIP(hipGetLastError());
-        uint64_t *tk = kin; kin = kout; kout = tk;
-        vin = vout;
-        vout = vout == va ? vb : va;
-    }
-    *keys_out = kin;
-    *vals_out = vin;
-    return SP_OK;
-}
-
-std::atomic<int> g_pack_sort_mode{0};
-
-sp_status spmi_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
-                          const sp_msd_plan *plan, uint64_t **keys_out, const void **vals_out)
-{
-    const int mode = g_pack_sort_mode.load(std::memory_order_relaxed);
-    uint32_t *ctr = plan ? plan->ctr : nullptr, *samp = plan ? plan->samp : nullptr;
-    bool msd = false;
-    if (mode == 2) msd = n >= 1 && n < ((int64_t)1 << 31);
-    else if (mode == 0) SP_TRY(spmi_msd_sort_suits(keys, n, key_bits, tmp, st, samp, &msd));
-    if (msd) return spmi_msd_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, ctr, keys_out, vals_out);
-    return spmi_radix_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, keys_out, vals_out);
-}
-
-sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
-                                hipStream_t st, uint64_t **keys_out, const void **vals_out)
-{
-    if (payload_bytes == 4)
-        return radix_sort_pairs_t<uint32_t>(keys, (const uint32_t *)vals, n, key_bits, tmp, st, keys_out, (const uint32_t **)vals_out);
-    return radix_sort_pairs_t<unsigned long long>(keys, (const unsigned long long *)vals, n, key_bits, tmp, st, keys_out,
-                                                  (const unsigned long long **)vals_out);
 }
 
 static size_t pad16(size_t b) { return (b + 15) & ~(size_t)15; }

@@ -1,11 +1,15 @@
-// Sort of (key, payload) pairs with distinct keys for the storage builder (arXiv 2202.04305, Section 4.2: the entries of the
-// coordinate scheme are brought into the level order of the target format before its arrays are built).
+// Stable radix sorts of (key, payload) pairs for the storage builder (arXiv 2202.04305, Section 4.2: the entries of the
+// coordinate scheme are brought into the level order of the target format before its arrays are built).  8-bit digits; one
+// pair of kernels, a histogram per tile and a scatter that ranks keys inside a wave with ballots and sorts the tile in LDS
+// before writing it, serves both orders of the digits.
 //
-// Most significant digit first: two passes over device memory split the entries by the top 16 bits of the key (8 bits per
-// pass: 256 buckets, then 256 sub-buckets inside each bucket); what is left of the key is sorted inside the LDS, a block
-// taking a run of consecutive sub-buckets of a few thousand entries.  Three reads and writes of the entries instead of one
-// per 8 key bits.  Every pass keeps the input order of entries with equal digits, so the sort is stable like the
-// least-significant-digit sort in pack.hip, and duplicates are added up in the same order after either.
+// Least significant digit first: one such pass over all entries per 8 key bits.
+//
+// Most significant digit first: two passes split the entries by the top 16 bits of the key (256 buckets, then 256
+// sub-buckets inside each bucket); what is left of the key is sorted inside the LDS, a block taking a run of consecutive
+// sub-buckets of about a thousand entries.  Three reads and writes of the entries instead of one per 8 key bits.  Every
+// pass keeps the input order of entries with equal digits, so this sort is stable as well, and duplicates are added up in
+// the same order after either.
 //
 // Skew: a run of sub-buckets that does not fit the LDS is sorted by its block through device memory, slowly; the caller asks
 // spmi_msd_sort_suits() first (a sampled histogram of the top 16 bits) and takes the other sort when that would be common.
@@ -25,30 +29,6 @@ constexpr int kFE = SPMI_MSD_FE;              // entries per thread in the LDS
 constexpr int kCap = kFT * kFE;               // entries a block sorts inside the LDS
 constexpr int kTarget = kCap / 2;             // a block takes the sub-buckets that start inside one stretch of this many entries
 constexpr int kSub = 65536;                   // sub-buckets after two passes
-
-template <typename T>
-__device__ __forceinline__ T wave_inclusive_scan(T v, int lane)
-{
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        T o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
-    return v;
-}
-
-// Lanes of the wave that hold the same digit as this lane (among lanes with valid set).
-__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
-{
-    uint64_t m = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const uint64_t bb = __ballot(bit);
-        m &= bit ? bb : ~bb;
-    }
-    return m;
-}
 
 // A partition pass works on segments (1 for the first pass, the 256 buckets for the second): segment b holds the entries
 // [seg_start[b], seg_start[b+1]) and is cut into tiles of kTile entries, numbered from seg_tile[b].  Block = tile.  The count
@@ -79,7 +59,7 @@ __device__ __forceinline__ tile_place locate_tile(const uint32_t *__restrict__ s
     return s_place;
 }
 
-__global__ __launch_bounds__(kT) void msd_hist_kernel(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ seg_start,
+__global__ __launch_bounds__(kT) void partition_hist_kernel(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ seg_start,
                                                       const uint32_t *__restrict__ seg_tile, int nseg, int shift, uint32_t *__restrict__ ctr)
 {
     __shared__ uint32_t h[256];
@@ -87,7 +67,20 @@ __global__ __launch_bounds__(kT) void msd_hist_kernel(const uint64_t *__restrict
     if (!p.any) return;
     h[threadIdx.x] = 0;
     __syncthreads();
-    for (uint32_t i = p.lo + threadIdx.x; i < p.hi; i += kT) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+    if (p.hi - p.lo == (uint32_t)kTile && (p.lo & 1u) == 0) {     // a whole, 16-byte aligned tile: two keys per lane and load, all loads first
+        typedef unsigned long long u2 __attribute__((ext_vector_type(2)));
+        const u2 *__restrict__ kk = (const u2 *)(keys + p.lo);
+        u2 k[kRounds / 2];
+#pragma unroll
+        for (int r = 0; r < kRounds / 2; ++r) k[r] = kk[r * kT + threadIdx.x];
+#pragma unroll
+        for (int r = 0; r < kRounds / 2; ++r) {
+            atomicAdd(&h[(uint32_t)(k[r][0] >> shift) & 255u], 1u);
+            atomicAdd(&h[(uint32_t)(k[r][1] >> shift) & 255u], 1u);
+        }
+    } else {
+        for (uint32_t i = p.lo + threadIdx.x; i < p.hi; i += kT) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+    }
     __syncthreads();
     ctr[p.ctr0 + threadIdx.x * p.stride] = h[threadIdx.x];
 }
@@ -95,7 +88,7 @@ __global__ __launch_bounds__(kT) void msd_hist_kernel(const uint64_t *__restrict
 // One tile of a partition pass: ranks inside the tile with ballots (tile order = wave, round, lane), the tile sorted by the
 // digit in LDS, then written so that neighbouring threads write neighbouring addresses of one digit's run.
 template <typename P>
-__global__ __launch_bounds__(kT) void msd_scatter_kernel(const uint64_t *__restrict__ kin, const P *__restrict__ vin, uint64_t *__restrict__ kout,
+__global__ __launch_bounds__(kT) void partition_scatter_kernel(const uint64_t *__restrict__ kin, const P *__restrict__ vin, uint64_t *__restrict__ kout,
                                                          P *__restrict__ vout, const uint32_t *__restrict__ seg_start,
                                                          const uint32_t *__restrict__ seg_tile, int nseg, int shift, const uint32_t *__restrict__ ctr)
 {
@@ -164,14 +157,14 @@ __global__ __launch_bounds__(kT) void msd_scatter_kernel(const uint64_t *__restr
     }
 }
 
-__global__ void msd_setup_first_kernel(uint32_t *seg_start, uint32_t *seg_tile, uint32_t n)
+__global__ void one_segment_kernel(uint32_t *seg_start, uint32_t *seg_tile, uint32_t n)
 {
     seg_start[0] = 0; seg_start[1] = n;
     seg_tile[0] = 0; seg_tile[1] = (n + kTile - 1) / kTile;
 }
 
 // The buckets of the first pass become the segments of the second: bucket b starts where digit b's first tile was placed.
-__global__ __launch_bounds__(256) void msd_setup_second_kernel(const uint32_t *__restrict__ ctr1, uint32_t tiles1, uint32_t n,
+__global__ __launch_bounds__(256) void buckets_to_segments_kernel(const uint32_t *__restrict__ ctr1, uint32_t tiles1, uint32_t n,
                                                                uint32_t *__restrict__ seg_start, uint32_t *__restrict__ seg_tile)
 {
     __shared__ uint32_t start[257];
@@ -418,6 +411,48 @@ __global__ __launch_bounds__(256) void msd_sample_verdict_kernel(const uint32_t 
     }
 }
 
+// Least significant digit first.  keys: n entries in a temporary of `tmp`, reordered freely; vals_in: n payloads, only read
+// (it may be the caller's own array).  On return *keys_out / *vals_out point at the sorted arrays: temporaries of `tmp`, or
+// the inputs when there was nothing to sort.
+template <typename P>
+sp_status lsd_sort_t(uint64_t *keys, const P *vals_in, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, uint64_t **keys_out,
+                     const P **vals_out)
+{
+    *keys_out = keys;
+    *vals_out = vals_in;
+    if (n <= 1 || key_bits <= 0) return SP_OK;
+    if (n >= ((int64_t)1 << 32) - kTile) return SP_ERR_TOO_LARGE;
+    const int passes = (key_bits + 7) / 8;
+    const uint32_t n32 = (uint32_t)n, tiles = (n32 + kTile - 1) / kTile;
+    const size_t vbytes = ((size_t)n * sizeof(P) + 15) & ~(size_t)15;
+    uint64_t *kalt = (uint64_t *)tmp.get((size_t)n * 8);
+    P *va = (P *)tmp.get(vbytes);
+    P *vb = passes > 1 ? (P *)tmp.get(vbytes) : va;
+    uint32_t *ctr = (uint32_t *)tmp.get((size_t)256 * tiles * 4);
+    uint32_t *seg = (uint32_t *)tmp.get(16);                     // one segment: every entry
+    if (!kalt || !va || !vb || !ctr || !seg) return SP_ERR_ALLOC;
+    hipLaunchKernelGGL(one_segment_kernel, dim3(1), dim3(1), 0, st, seg, seg + 2, n32);
+    uint64_t *kin = keys, *kout = kalt;
+    const P *vin = vals_in;
+    P *vout = va;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = 8 * p;
+        hipLaunchKernelGGL(partition_hist_kernel, dim3(tiles), dim3(kT), 0, st, (const uint64_t *)kin, (const uint32_t *)seg, (const uint32_t *)(seg + 2), 1, shift,
+                           ctr);
+        SP_HIP(hipGetLastError());
+        SP_TRY(spmi_exclusive_scan(ctr, (int64_t)256 * tiles, 32, tmp, st));
+        hipLaunchKernelGGL(partition_scatter_kernel<P>, dim3(tiles), dim3(kT), 0, st, (const uint64_t *)kin, vin, kout, vout, (const uint32_t *)seg,
+                           (const uint32_t *)(seg + 2), 1, shift, (const uint32_t *)ctr);
+        SP_HIP(hipGetLastError());
+        uint64_t *tk = kin; kin = kout; kout = tk;
+        vin = vout;
+        vout = vout == va ? vb : va;
+    }
+    *keys_out = kin;
+    *vals_out = vin;
+    return SP_OK;
+}
+
 template <typename P>
 sp_status msd_sort_t(uint64_t *keys, const P *vals_in, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, uint32_t *ctr_ready,
                      uint64_t **keys_out, const P **vals_out)
@@ -435,23 +470,23 @@ sp_status msd_sort_t(uint64_t *keys, const P *vals_in, int64_t n, int key_bits, 
     uint32_t *seg_start1 = seg, *seg_tile1 = seg + 2, *seg_start2 = seg + 4, *seg_tile2 = seg + 4 + 257, *chunk_lo = seg + 4 + 2 * 257;
     const int shift1 = key_bits > 8 ? key_bits - 8 : 0, shift2 = key_bits > 16 ? key_bits - 16 : 0;
     // first pass: keys / vals_in -> kb / va
-    hipLaunchKernelGGL(msd_setup_first_kernel, dim3(1), dim3(1), 0, st, seg_start1, seg_tile1, n32);
+    hipLaunchKernelGGL(one_segment_kernel, dim3(1), dim3(1), 0, st, seg_start1, seg_tile1, n32);
     if (!ctr_ready)
-        hipLaunchKernelGGL(msd_hist_kernel, dim3(tiles1), dim3(kT), 0, st, (const uint64_t *)keys, (const uint32_t *)seg_start1, (const uint32_t *)seg_tile1,
+        hipLaunchKernelGGL(partition_hist_kernel, dim3(tiles1), dim3(kT), 0, st, (const uint64_t *)keys, (const uint32_t *)seg_start1, (const uint32_t *)seg_tile1,
                            1, shift1, ctr);
     SP_HIP(hipGetLastError());
     SP_TRY(spmi_exclusive_scan(ctr, (int64_t)256 * tiles1, 32, tmp, st));
-    hipLaunchKernelGGL(msd_scatter_kernel<P>, dim3(tiles1), dim3(kT), 0, st, (const uint64_t *)keys, vals_in, kb, va, (const uint32_t *)seg_start1,
+    hipLaunchKernelGGL(partition_scatter_kernel<P>, dim3(tiles1), dim3(kT), 0, st, (const uint64_t *)keys, vals_in, kb, va, (const uint32_t *)seg_start1,
                        (const uint32_t *)seg_tile1, 1, shift1, (const uint32_t *)ctr);
-    hipLaunchKernelGGL(msd_setup_second_kernel, dim3(1), dim3(256), 0, st, (const uint32_t *)ctr, tiles1, n32, seg_start2, seg_tile2);
+    hipLaunchKernelGGL(buckets_to_segments_kernel, dim3(1), dim3(256), 0, st, (const uint32_t *)ctr, tiles1, n32, seg_start2, seg_tile2);
     SP_HIP(hipGetLastError());
     // second pass: kb / va -> keys / vb.  Tiles past the last one of the last bucket do nothing; their counters stay zero.
     SP_TRY(spmi_fill_zero(ctr, ctr_words * 4, st));
-    hipLaunchKernelGGL(msd_hist_kernel, dim3(tiles2_max), dim3(kT), 0, st, (const uint64_t *)kb, (const uint32_t *)seg_start2, (const uint32_t *)seg_tile2,
+    hipLaunchKernelGGL(partition_hist_kernel, dim3(tiles2_max), dim3(kT), 0, st, (const uint64_t *)kb, (const uint32_t *)seg_start2, (const uint32_t *)seg_tile2,
                        256, shift2, ctr);
     SP_HIP(hipGetLastError());
     SP_TRY(spmi_exclusive_scan(ctr, (int64_t)ctr_words, 32, tmp, st));
-    hipLaunchKernelGGL(msd_scatter_kernel<P>, dim3(tiles2_max), dim3(kT), 0, st, (const uint64_t *)kb, (const P *)va, keys, vb,
+    hipLaunchKernelGGL(partition_scatter_kernel<P>, dim3(tiles2_max), dim3(kT), 0, st, (const uint64_t *)kb, (const P *)va, keys, vb,
                        (const uint32_t *)seg_start2, (const uint32_t *)seg_tile2, 256, shift2, (const uint32_t *)ctr);
     hipLaunchKernelGGL(msd_chunks_kernel, dim3(kSub / 256 + 1), dim3(256), 0, st, (const uint32_t *)ctr, (const uint32_t *)seg_start2,
                        (const uint32_t *)seg_tile2, n32, nchunks, chunk_lo);
@@ -517,4 +552,25 @@ sp_status spmi_msd_sort_pairs(uint64_t *keys, const void *vals, int payload_byte
         return msd_sort_t<uint32_t>(keys, (const uint32_t *)vals, n, key_bits, tmp, st, ctr_ready, keys_out, (const uint32_t **)vals_out);
     return msd_sort_t<unsigned long long>(keys, (const unsigned long long *)vals, n, key_bits, tmp, st, ctr_ready, keys_out,
                                           (const unsigned long long **)vals_out);
+}
+
+std::atomic<int> g_pack_sort_mode{0};
+
+sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                                uint64_t **keys_out, const void **vals_out)
+{
+    if (payload_bytes == 4) return lsd_sort_t<uint32_t>(keys, (const uint32_t *)vals, n, key_bits, tmp, st, keys_out, (const uint32_t **)vals_out);
+    return lsd_sort_t<unsigned long long>(keys, (const unsigned long long *)vals, n, key_bits, tmp, st, keys_out, (const unsigned long long **)vals_out);
+}
+
+sp_status spmi_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st,
+                          const sp_msd_plan *plan, uint64_t **keys_out, const void **vals_out)
+{
+    const int mode = g_pack_sort_mode.load(std::memory_order_relaxed);
+    uint32_t *ctr = plan ? plan->ctr : nullptr, *samp = plan ? plan->samp : nullptr;
+    bool msd = false;
+    if (mode == 2) msd = n >= 1 && n < ((int64_t)1 << 31);
+    else if (mode == 0) SP_TRY(spmi_msd_sort_suits(keys, n, key_bits, tmp, st, samp, &msd));
+    if (msd) return spmi_msd_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, ctr, keys_out, vals_out);
+    return spmi_radix_sort_pairs(keys, vals, payload_bytes, n, key_bits, tmp, st, keys_out, vals_out);
 }

@@ -166,17 +166,43 @@ struct sp_scratch {
     }
 };
 
+// ---- device helpers shared by the sources ---------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Lanes of the wave that hold the same 8-bit digit as this lane (among lanes with valid set).
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
+{
+    uint64_t m = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bb = __ballot(bit);
+        m &= bit ? bb : ~bb;
+    }
+    return m;
+}
+
 // ---- pack.hip ----------------------------------------------------------------------------
 // In-place exclusive prefix sum of n elements of width `bits` (32 or 64); data[n-1] afterwards
 // holds the sum of the first n-1 inputs.
 sp_status spmi_exclusive_scan(void *data, int64_t n, int bits, sp_scratch &tmp, hipStream_t st);
-// Stable LSD radix sort of (key, payload) pairs on the low `key_bits` bits, payload of 4 or 8 bytes.  keys: a temporary of
-// `tmp`, overwritten; vals: only read.  *keys_out / *vals_out: where the sorted arrays are (temporaries of `tmp`, or
-// the inputs themselves when there was nothing to sort).
+sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
+// ---- sort.hip ----
+// Stable radix sort, least significant digit first, of (key, payload) pairs on the low `key_bits` bits taken as whole 8-bit
+// digits (so ceil(key_bits / 8) * 8 bits decide), payload of 4 or 8 bytes.  keys: a temporary of `tmp`, overwritten; vals: only
+// read.  *keys_out / *vals_out: where the sorted arrays are (temporaries of `tmp`, or the inputs themselves when there was
+// nothing to sort).
 sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_bytes, int64_t n, int key_bits, sp_scratch &tmp,
                                 hipStream_t st, uint64_t **keys_out, const void **vals_out);
-sp_status spmi_fill_zero(void *p, size_t bytes, hipStream_t st);
-// ---- msd_sort.hip ----
 // The same sort (same arguments, same stability) with the most significant digits first: two passes over device memory, the
 // rest inside the LDS.  Only for inputs that spmi_msd_sort_suits() accepted: enough entries, keys wide enough, and (from a
 // sampled histogram of the top 16 key bits, samp_ready when the caller has it already; synchronises the stream) few entries
