@@ -97,8 +97,7 @@ __global__ __launch_bounds__(kT) void partition_scatter_kernel(const uint64_t *_
     __shared__ uint32_t wbase[W][256];
     __shared__ uint32_t gbase[256];
     __shared__ uint32_t wsum[W];
-    __shared__ uint64_t skey[kTile];
-    __shared__ P sval[kTile];
+    __shared__ uint64_t stage[kTile];                 // the tile in sorted order: first the keys, then the payloads
     const tile_place p = locate_tile(seg_start, seg_tile, nseg);
     if (!p.any) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -143,17 +142,31 @@ __global__ __launch_bounds__(kT) void partition_scatter_kernel(const uint64_t *_
     for (int r = 0; r < kRounds; ++r) {
         if (wave * PERW + r * 64 + lane < in_tile) {
             const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
-            const uint32_t slot = wbase[wave][d] + lpos[r];
-            skey[slot] = k[r];
-            sval[slot] = v[r];
+            lpos[r] += wbase[wave][d];                 // from here on: the entry's slot in the sorted tile
+            stage[lpos[r]] = k[r];
         }
     }
     __syncthreads();
-    for (int slot = tid; slot < in_tile; slot += kT) {
-        const uint64_t key = skey[slot];
-        const uint32_t q = gbase[(uint32_t)(key >> shift) & 255u] + (uint32_t)slot;
-        kout[q] = key;
-        vout[q] = sval[slot];
+    uint32_t q[kRounds];                              // where the entry that sits in slot tid + j * kT goes
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+        const int slot = tid + j * kT;
+        if (slot < in_tile) {
+            const uint64_t key = stage[slot];
+            q[j] = gbase[(uint32_t)(key >> shift) & 255u] + (uint32_t)slot;
+            kout[q[j]] = key;
+        }
+    }
+    __syncthreads();
+    P *sval = (P *)stage;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+        if (wave * PERW + r * 64 + lane < in_tile) sval[lpos[r]] = v[r];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+        const int slot = tid + j * kT;
+        if (slot < in_tile) vout[q[j]] = sval[slot];
     }
 }
 

@@ -161,6 +161,28 @@ def test_csr_spmv_binned_random_shapes():
         assert np.array_equal(y.cpu().numpy().astype(np.float64), ref[:, 0])
 
 
+def test_csr_spmv_binned_padding_is_inert():
+    """The binned copy pads every bucket to a multiple of 8 entries.  The padding must give exactly 0 whatever x holds: with
+    infinities and NaNs in some columns, the rows that store none of those columns stay finite and exact."""
+    w = W.cfg2_powerlaw_csr(5000, 40000, mean=10.0, cap=700)
+    vals = prng.small_ints(21, 1, w.nnz)
+    A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], vals)
+    sp.sp_tensor_tune(A, sp.SP_TUNE_SPMV_KERNEL, 4)
+    x = prng.small_ints(22, 2, w.shape[1])
+    bad_cols = np.array([0, 1, 8191, 8192, 16384, 39999])          # first and last columns of panels among them
+    xb = x.copy()
+    xb[bad_cols] = [np.inf, np.nan, -np.inf, np.nan, np.inf, np.nan]
+    y = torch.full((w.shape[0],), 7.0, dtype=torch.float64, device=DEV)
+    sp.sp_matmul(A, dev(xb), y)
+    ref, _ = oracle.matmul_coo(w.shape, w.rows, w.cols, vals, x.reshape(-1, 1))
+    touched = np.zeros(w.shape[0], dtype=bool)
+    touched[w.rows[np.isin(w.cols, bad_cols)]] = True
+    got = y.cpu().numpy()
+    assert touched.any() and not touched.all()
+    assert np.array_equal(got[~touched], ref[~touched, 0])
+    assert not np.isfinite(got[touched]).all()
+
+
 def test_csr_spmv_binned_strides_and_refusals():
     w = W.cfg2_powerlaw_csr(3000, 20000, mean=12.0, cap=900)
     A = gpu_pack((0, 1), (0, 1), w.shape, [w.rows, w.cols], w.vals)
