@@ -17,7 +17,10 @@
 
 namespace {
 
-constexpr int kT = 256;                       // threads of the partition kernels
+#ifndef SPMI_SORT_T
+#define SPMI_SORT_T 256
+#endif
+constexpr int kT = SPMI_SORT_T;               // threads of the partition kernels (at least 256: thread d also stands for digit d)
 constexpr int kRounds = 16;
 constexpr int kTile = kSpmiMsdTile;           // entries per tile of a partition pass
 static_assert(kTile == kT * kRounds, "tile");
@@ -65,7 +68,7 @@ __global__ __launch_bounds__(kT) void partition_hist_kernel(const uint64_t *__re
     __shared__ uint32_t h[256];
     const tile_place p = locate_tile(seg_start, seg_tile, nseg);
     if (!p.any) return;
-    h[threadIdx.x] = 0;
+    if (threadIdx.x < 256) h[threadIdx.x] = 0;
     __syncthreads();
     if (p.hi - p.lo == (uint32_t)kTile && (p.lo & 1u) == 0) {     // a whole, 16-byte aligned tile: two keys per lane and load, all loads first
         typedef unsigned long long u2 __attribute__((ext_vector_type(2)));
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(kT) void partition_hist_kernel(const uint64_t *__re
         for (uint32_t i = p.lo + threadIdx.x; i < p.hi; i += kT) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
     }
     __syncthreads();
-    ctr[p.ctr0 + threadIdx.x * p.stride] = h[threadIdx.x];
+    if (threadIdx.x < 256) ctr[p.ctr0 + threadIdx.x * p.stride] = h[threadIdx.x];
 }
 
 // One tile of a partition pass: ranks inside the tile with ballots (tile order = wave, round, lane), the tile sorted by the
@@ -93,17 +96,16 @@ __global__ __launch_bounds__(kT) void partition_scatter_kernel(const uint64_t *_
                                                          const uint32_t *__restrict__ seg_tile, int nseg, int shift, const uint32_t *__restrict__ ctr)
 {
     constexpr int W = kT / 64, PERW = kTile / W;
-    __shared__ uint32_t wrun[W][256];
-    __shared__ uint32_t wbase[W][256];
+    __shared__ uint16_t wrun[W][256];                 // counts and slots inside a tile fit 16 bits
+    __shared__ uint16_t wbase[W][256];
     __shared__ uint32_t gbase[256];
-    __shared__ uint32_t wsum[W];
+    __shared__ uint32_t wsum[4];
     __shared__ uint64_t stage[kTile];                 // the tile in sorted order: first the keys, then the payloads
     const tile_place p = locate_tile(seg_start, seg_tile, nseg);
     if (!p.any) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int in_tile = (int)(p.hi - p.lo);
-#pragma unroll
-    for (int w = 0; w < W; ++w) wrun[w][tid] = 0;
+    for (int i = tid; i < W * 256; i += kT) (&wrun[0][0])[i] = 0;
     uint64_t k[kRounds];
     P v[kRounds];
     uint32_t lpos[kRounds];
@@ -121,21 +123,25 @@ __global__ __launch_bounds__(kT) void partition_scatter_kernel(const uint64_t *_
         const uint64_t m = match_digit(d, valid);
         const uint32_t before = wrun[wave][d];
         lpos[r] = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (valid && (m & ((1ull << lane) - 1ull)) == 0) wrun[wave][d] = before + (uint32_t)__popcll(m);
+        if (valid && (m & ((1ull << lane) - 1ull)) == 0) wrun[wave][d] = (uint16_t)(before + (uint32_t)__popcll(m));
     }
     __syncthreads();
-    {
-        uint32_t c[W], tot = 0;
+    {   // thread d < 256: tile count of digit d, exclusive scan over the digits, per-wave starts
+        uint32_t c[W], tot = 0, incl = 0;
+        if (tid < 256) {
 #pragma unroll
-        for (int w = 0; w < W; ++w) { c[w] = wrun[w][tid]; tot += c[w]; }
-        const uint32_t incl = wave_inclusive_scan(tot, lane);
-        if (lane == 63) wsum[wave] = incl;
+            for (int w = 0; w < W; ++w) { c[w] = wrun[w][tid]; tot += c[w]; }
+            incl = wave_inclusive_scan(tot, lane);
+            if (lane == 63) wsum[wave] = incl;
+        }
         __syncthreads();
-        uint32_t start = incl - tot;
-        for (int w = 0; w < wave; ++w) start += wsum[w];
-        gbase[tid] = ctr[p.ctr0 + tid * p.stride] - start;
+        if (tid < 256) {
+            uint32_t start = incl - tot;
+            for (int w = 0; w < wave; ++w) start += wsum[w];
+            gbase[tid] = ctr[p.ctr0 + tid * p.stride] - start;
 #pragma unroll
-        for (int w = 0; w < W; ++w) { wbase[w][tid] = start; start += c[w]; }
+            for (int w = 0; w < W; ++w) { wbase[w][tid] = (uint16_t)start; start += c[w]; }
+        }
     }
     __syncthreads();
 #pragma unroll

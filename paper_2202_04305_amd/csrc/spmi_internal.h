@@ -212,7 +212,10 @@ sp_status spmi_radix_sort_pairs(uint64_t *keys, const void *vals, int payload_by
 // this sort is out of the question): for the tile e / kSpmiMsdTile of entry e, ctr[digit * tiles + tile] counts the entries
 // whose digit is (key >> digit_shift) & 255 (every word written, zero included), and samp[(key >> samp_shift) & 0xffff]
 // counts every 64th entry (e % 64 == 0; samp arrives zeroed).
-constexpr int kSpmiMsdTile = 4096;
+#ifndef SPMI_SORT_T
+#define SPMI_SORT_T 256
+#endif
+constexpr int kSpmiMsdTile = SPMI_SORT_T * 16;
 struct sp_msd_plan { uint32_t *ctr, *samp; uint32_t tiles; int digit_shift, samp_shift; };
 sp_status spmi_msd_plan(int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, sp_msd_plan *plan);
 sp_status spmi_msd_sort_suits(const uint64_t *keys, int64_t n, int key_bits, sp_scratch &tmp, hipStream_t st, uint32_t *samp_ready, bool *suits);
