@@ -51,6 +51,44 @@ def build(verbose=False):
     return LIB
 
 
+HOSTSAN_LIB = os.path.join(HERE, "libspmi_hostsan.so")
+
+
+def sanitizer_runtime():
+    """The AddressSanitizer runtime of the clang that hipcc drives (to preload into a process that loads HOSTSAN_LIB)."""
+    out = subprocess.check_output(["hipcc", "--offload-arch=gfx950", "-print-file-name=libclang_rt.asan-x86_64.so"]).decode().strip()
+    if os.path.isabs(out) and os.path.exists(out):
+        return out
+    hits = sorted(glob.glob(os.path.join(os.environ.get("ROCM_PATH", "/opt/rocm"), "lib", "llvm", "lib", "clang", "*", "lib", "linux",
+                                         "libclang_rt.asan-x86_64.so")))
+    return hits[-1] if hits else None
+
+
+def build_host_sanitized():
+    """The same library with its HOST code under AddressSanitizer and UndefinedBehaviorSanitizer (the device code is built as
+    usual: GPU sanitizers are not used).  For the CPU test that drives the host-only paths of the ABI; never loaded otherwise."""
+    bdir = os.path.join(HERE, "_build", "hostsan")
+    os.makedirs(bdir, exist_ok=True)
+    san = []
+    for f in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"):
+        san += ["-Xarch_host", f]
+    procs, objs = [], []
+    for src in SOURCES:
+        obj = os.path.join(bdir, os.path.basename(src) + ".o")
+        objs.append(obj)
+        cmd = ["hipcc", "-c", src, "-o", obj, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")] + \
+              [f for f in FLAGS if f not in ("-shared", "-O3")] + ["-O1", "-g"] + san
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (src, out.decode()))
+    tmp = HOSTSAN_LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined", "-shared-libsan", "-o", tmp] + objs)
+    os.replace(tmp, HOSTSAN_LIB)
+    return HOSTSAN_LIB
+
+
 C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "client.c")
 C_CLIENT = os.path.join(ROOT, "tests", "c_client", "client")
 

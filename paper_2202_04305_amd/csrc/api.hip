@@ -6,8 +6,10 @@ thread_local int g_last_hip_error = 0;
 
 extern "C" int sp_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" const char *sp_status_str(sp_status s)
+extern "C" const char *sp_status_str(sp_status status)
 {
+    int s;                                             // any integer may arrive: read it as one, not as the enumeration
+    memcpy(&s, &status, sizeof(s));
     switch (s) {
     case SP_OK: return "ok";
     case SP_ERR_NULL: return "null pointer";
@@ -33,8 +35,13 @@ extern "C" sp_status sp_encode(int rank, const sp_level_type *levelTypes, const 
     if (!levelTypes || !out) return SP_ERR_NULL;
     *out = nullptr;
     if (rank < 1 || rank > SP_MAX_RANK) return SP_ERR_RANK;
-    for (int l = 0; l < rank; ++l)
-        if (levelTypes[l] != SP_DENSE && levelTypes[l] != SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
+    // the caller's array may hold any integer: it is read as integers, not as the enumeration (whose other values C++ may not load)
+    static_assert(sizeof(sp_level_type) == sizeof(int), "level types travel as ints");
+    int lt[SP_MAX_RANK];
+    for (int l = 0; l < rank; ++l) {
+        memcpy(&lt[l], (const char *)levelTypes + (size_t)l * sizeof(int), sizeof(int));
+        if (lt[l] != (int)SP_DENSE && lt[l] != (int)SP_COMPRESSED) return SP_ERR_LEVEL_TYPE;
+    }
     bool seen[SP_MAX_RANK] = {false};
     for (int l = 0; l < rank; ++l) {
         const int d = dimOrdering ? dimOrdering[l] : l;
@@ -47,7 +54,7 @@ extern "C" sp_status sp_encode(int rank, const sp_level_type *levelTypes, const 
     memset(e, 0, sizeof(*e));
     e->rank = rank;
     for (int l = 0; l < rank; ++l) {
-        e->lt[l] = (int)levelTypes[l];
+        e->lt[l] = lt[l];
         e->perm[l] = dimOrdering ? dimOrdering[l] : l;
     }
     e->pw_store = posWidth ? posWidth : 64;

@@ -1235,7 +1235,9 @@ extern "C" sp_status sp_pack(const sp_encoding *enc, const int64_t *shape, int64
     *out = nullptr;
     if ((alloc == nullptr) != (free_ == nullptr)) return SP_ERR_NULL;
     if (nnz > 0 && (!coords || !values)) return SP_ERR_NULL;
-    if (dt != SP_F32 && dt != SP_F64) return SP_ERR_DTYPE;
+    int dti;                                           // any integer may arrive: read it as one, not as the enumeration
+    memcpy(&dti, &dt, sizeof(dti));
+    if (dti != (int)SP_F32 && dti != (int)SP_F64) return SP_ERR_DTYPE;
     if (nnz < 0) return SP_ERR_SHAPE;
     const int rank = enc->rank;
     bool zero_dim = false;
