@@ -62,8 +62,16 @@ class _MeteredAllocator(binding._TorchAllocator):
         return super()._alloc(nbytes, ctx)
 
 
+@pytest.fixture(params=[0, 2], ids=["sort chosen", "most significant digit first"])
+def sort_mode(request):
+    """The storage builder's sort: its own choice (least significant digit first at these sizes), and the other one forced."""
+    sp.sp_pack_sort_mode(request.param)
+    yield request.param
+    sp.sp_pack_sort_mode(0)
+
+
 @pytest.mark.parametrize("fmt", [((0, 1), (0, 1)), ((1, 1), (1, 0)), ((0, 1, 1), (0, 2, 1))])
-def test_allocator_running_dry_is_an_error_and_leaves_nothing_behind(fmt):
+def test_allocator_running_dry_is_an_error_and_leaves_nothing_behind(fmt, sort_mode):
     lt, order = fmt
     if len(lt) == 2:
         w = W.cfg2_powerlaw_csr(3000, 2500, cap=500)
