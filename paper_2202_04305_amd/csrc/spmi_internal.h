@@ -178,17 +178,21 @@ __device__ __forceinline__ T wave_inclusive_scan(T v, int lane)
     return v;
 }
 
-// Lanes of the wave that hold the same 8-bit digit as this lane (among lanes with valid set).
+// Lanes of the wave that hold the same 8-bit digit as this lane (among lanes with valid set).  Per bit: the lanes that agree
+// with this one are ~(ballot ^ mine), `mine` being all ones or all zeros; m & ~(ballot ^ mine) is one three-input bit
+// operation per 32-bit half (truth table 0x90 with m as the first input), five vector instructions per bit in all.
 __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid)
 {
-    uint64_t m = __ballot(valid);
+    const uint64_t v = __builtin_amdgcn_ballot_w64(valid);
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const uint64_t bb = __ballot(bit);
-        m &= bit ? bb : ~bb;
+        const int mine = __builtin_amdgcn_sbfe((int)d, b, 1);
+        const uint64_t bb = __builtin_amdgcn_ballot_w64(mine != 0);
+        lo = __builtin_amdgcn_bitop3_b32(lo, (uint32_t)bb, (uint32_t)mine, 0x90);
+        hi = __builtin_amdgcn_bitop3_b32(hi, (uint32_t)(bb >> 32), (uint32_t)mine, 0x90);
     }
-    return m;
+    return ((uint64_t)hi << 32) | lo;
 }
 
 // ---- pack.hip ----------------------------------------------------------------------------
