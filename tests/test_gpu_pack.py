@@ -172,9 +172,18 @@ def test_convert_between_encodings():
     assert_storage_equal(Bt, oracle.pack((1, 1), (1, 0), w.shape, [w.rows, w.cols], w.vals, 32, 32))
 
 
-def test_random_ranks_levels_orderings_and_widths():
+@pytest.fixture(params=[0, 2], ids=["sort chosen", "most significant digit first"])
+def sort_mode(request):
+    """The storage builder's sort: its own choice (least significant digit first at these sizes), and the other one forced."""
+    sp.sp_pack_sort_mode(request.param)
+    yield request.param
+    sp.sp_pack_sort_mode(0)
+
+
+def test_random_ranks_levels_orderings_and_widths(sort_mode):
     """Seeded random encodings of rank 1 to 6: any mix of level types, any ordering, pos / crd widths from 8 to 64 bits
-    (whatever the sizes allow), several sort tiles of entries; the storage bit for bit, then back to coordinates."""
+    (whatever the sizes allow), several sort tiles of entries; the storage bit for bit, then back to coordinates.  Under
+    either sort of the builder."""
     rng = np.random.default_rng(220204305)
     done = 0
     while done < 48:
