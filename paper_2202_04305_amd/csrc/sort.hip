@@ -410,7 +410,7 @@ __global__ __launch_bounds__(256) void msd_sample_kernel(const uint64_t *__restr
 
 // out[0] = estimated number of entries in sub-buckets that alone overflow a finishing block, out[1] = estimated size of the
 // largest sub-bucket.
-__global__ __launch_bounds__(256) void msd_sample_verdict_kernel(const uint32_t *__restrict__ samp, unsigned long long *__restrict__ out)
+__global__ __launch_bounds__(256) void msd_sample_summary_kernel(const uint32_t *__restrict__ samp, unsigned long long *__restrict__ out)
 {
     unsigned long long heavy = 0, largest = 0;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < kSub; i += gridDim.x * 256) {
@@ -552,11 +552,11 @@ sp_status spmi_msd_sort_suits(const uint64_t *keys, int64_t n, int key_bits, sp_
         const int64_t samples = (n + 63) / 64;
         hipLaunchKernelGGL(msd_sample_kernel, dim3((unsigned)((samples + 255) / 256)), dim3(256), 0, st, keys, n, key_bits - 16, samp);
     }
-    unsigned long long *verdict = (unsigned long long *)(samp + kSub);       // zero so far
-    hipLaunchKernelGGL(msd_sample_verdict_kernel, dim3(64), dim3(256), 0, st, (const uint32_t *)samp, verdict);
+    unsigned long long *summary = (unsigned long long *)(samp + kSub);       // zero so far
+    hipLaunchKernelGGL(msd_sample_summary_kernel, dim3(64), dim3(256), 0, st, (const uint32_t *)samp, summary);
     SP_HIP(hipGetLastError());
     unsigned long long h[2] = {0, 0};
-    SP_HIP(hipMemcpyAsync(h, verdict, 16, hipMemcpyDeviceToHost, st));
+    SP_HIP(hipMemcpyAsync(h, summary, 16, hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
     // a finishing block that gets more than it can hold in the LDS sorts its range alone through device memory: fine for a
     // tenth of the entries spread over many blocks, not for one block with a large share of them
