@@ -435,52 +435,62 @@ __global__ __launch_bounds__(kThreads) void max_span_kernel(const int32_t *__res
 // with whatever else the caller reads back: enqueue (marks, their scan, the longest run of rows in one window; the
 // answers land in the probe once the stream has been synchronised), then decide (and compact, when worth it).
 struct nonempty_probe {
-    uint32_t *mark = nullptr;
     int64_t nrows = 0;
-    uint32_t last_mark = 0, last_excl = 0;
-    unsigned long long span = 0;
+    unsigned long long nz = 0, span = 0;
     bool active = false;
     // the answers come back inside the builder's 64-byte flags block (one copy to the host for everything):
-    // ints 8 and 9 = the last mark and the last exclusive count, ints 10-11 = the longest run as a 64-bit value
-    void take(const int *h) { last_mark = (uint32_t)h[8]; last_excl = (uint32_t)h[9]; memcpy(&span, &h[10], 8); }
+    // ints 8-9 = the number of non-empty rows, ints 10-11 = the longest run, both as 64-bit values
+    void take(const int *h) { memcpy(&nz, &h[8], 8); memcpy(&span, &h[10], 8); }
 };
 
-__global__ void copy_word_kernel(const uint32_t *__restrict__ src, int *__restrict__ dst) { *dst = (int)*src; }
+// *out += the number of rows that hold something: grid-stride count per thread, wave and block reduction, one atomic per block
+template <typename PT>
+__global__ __launch_bounds__(kThreads) void count_nonempty_kernel(const PT *__restrict__ pos, int64_t nrows, unsigned long long *__restrict__ out)
+{
+    __shared__ unsigned long long wsum[kThreads / 64];
+    unsigned long long c = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nrows; i += (int64_t)gridDim.x * kThreads) c += pos[i + 1] > pos[i] ? 1u : 0u;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) c += wsum[w];
+        if (c) atomicAdd(out, c);
+    }
+}
 
 // flags: the 64 zeroed device bytes of the build (see nonempty_probe for the slots used here)
-static sp_status nonempty_enqueue(const sp_tensor *t, sp_scratch &tmp, hipStream_t st, int *flags, nonempty_probe &q)
+static sp_status nonempty_enqueue(const sp_tensor *t, hipStream_t st, int *flags, nonempty_probe &q)
 {
     if (t->enc.rank != 2 || t->enc.lt[0] != SP_DENSE || t->enc.lt[1] != SP_COMPRESSED) return SP_OK;
     const int64_t nrows = t->npos[1] - 1;
     if (nrows < 4096 || nrows >= ((int64_t)1 << 31) - 1 || t->ncrd[1] == 0) return SP_OK;
-    uint32_t *mark = (uint32_t *)tmp.get((size_t)nrows * 4);
-    if (!mark) return SP_ERR_ALLOC;
+    const unsigned cnt_blocks = blocks_for(nrows) < 256u ? blocks_for(nrows) : 256u;
     if (t->enc.pw == 32)
-        hipLaunchKernelGGL(mark_nonempty_kernel<int32_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, mark);
+        hipLaunchKernelGGL(count_nonempty_kernel<int32_t>, dim3(cnt_blocks), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows,
+                           (unsigned long long *)(flags + 8));
     else
-        hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
-    SP_HIP(hipGetLastError());
-    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(1), 0, st, (const uint32_t *)(mark + (nrows - 1)), flags + 8);   // the scan overwrites the marks
-    SP_HIP(hipGetLastError());
-    SP_TRY(spmi_exclusive_scan(mark, nrows, 32, tmp, st));
-    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(1), 0, st, (const uint32_t *)(mark + (nrows - 1)), flags + 9);
+        hipLaunchKernelGGL(count_nonempty_kernel<int64_t>, dim3(cnt_blocks), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows,
+                           (unsigned long long *)(flags + 8));
     SP_HIP(hipGetLastError());
     if (t->rowblocks.start) {
         hipLaunchKernelGGL(max_span_kernel, dim3(blocks_for(t->rowblocks.nblocks)), dim3(kThreads), 0, st, (const int32_t *)t->rowblocks.start,
                            t->rowblocks.nblocks, (unsigned long long *)(flags + 10));
         SP_HIP(hipGetLastError());
     }
-    q.mark = mark; q.nrows = nrows; q.active = true;
+    q.nrows = nrows; q.active = true;
     return SP_OK;
 }
 
-// after the stream has been synchronised; *launched = kernels were enqueued
-static sp_status nonempty_decide(const sp_tensor *t, hipStream_t st, const nonempty_probe &q, bool *launched)
+// after the stream has been synchronised; *launched = kernels were enqueued (they use a temporary of `tmp`: synchronise
+// before it goes)
+static sp_status nonempty_decide(const sp_tensor *t, sp_scratch &tmp, hipStream_t st, const nonempty_probe &q, bool *launched)
 {
     *launched = false;
     if (!q.active) return SP_OK;
     const int64_t nrows = q.nrows;
-    const int64_t nz = (int64_t)q.last_excl + q.last_mark;
+    const int64_t nz = (int64_t)q.nz;
     // not worth it when at least half of the rows hold something, unless one window of the streaming kernels would have to walk
     // over a very long run of empty rows all by itself
     if (nz * 2 > nrows && q.span < 65536) return SP_OK;
@@ -488,11 +498,18 @@ static sp_status nonempty_decide(const sp_tensor *t, hipStream_t st, const nonem
     const int ps = t->enc.pw / 8, cs = t->enc.cw / 8;
     void *rid = mem.get(pad16((size_t)(nz > 0 ? nz : 1) * cs));
     void *npos = mem.get(pad16((size_t)(nz + 1) * ps));
-    if (!rid || !npos) { mem.put(rid); mem.put(npos); return SP_ERR_ALLOC; }
+    uint32_t *mark = (uint32_t *)tmp.get((size_t)nrows * 4);
+    if (!rid || !npos || !mark) { mem.put(rid); mem.put(npos); return SP_ERR_ALLOC; }
     *launched = true;
+    if (t->enc.pw == 32)
+        hipLaunchKernelGGL(mark_nonempty_kernel<int32_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int32_t *)t->pos[1], nrows, mark);
+    else
+        hipLaunchKernelGGL(mark_nonempty_kernel<int64_t>, dim3(blocks_for(nrows)), dim3(kThreads), 0, st, (const int64_t *)t->pos[1], nrows, mark);
+    sp_status ss = hipGetLastError() == hipSuccess ? spmi_exclusive_scan(mark, nrows, 32, tmp, st) : SP_ERR_HIP;
+    if (ss != SP_OK) { mem.put(rid); mem.put(npos); return ss; }
 #define SPMI_COMPACT(PT, CT)                                                                                                  \
     hipLaunchKernelGGL((compact_rows_kernel<PT, CT>), dim3(blocks_for(nrows + 1)), dim3(kThreads), 0, st, (const PT *)t->pos[1], nrows, \
-                       (const uint32_t *)q.mark, nz, (CT *)rid, (PT *)npos)
+                       (const uint32_t *)mark, nz, (CT *)rid, (PT *)npos)
     if (t->enc.pw == 32 && t->enc.cw == 32) SPMI_COMPACT(int32_t, int32_t);
     else if (t->enc.pw == 32) SPMI_COMPACT(int32_t, int64_t);
     else if (t->enc.cw == 32) SPMI_COMPACT(int64_t, int32_t);
@@ -511,14 +528,14 @@ static sp_status build_nonempty_rows(const sp_tensor *t, sp_scratch &tmp, hipStr
     if (!flags) return SP_ERR_ALLOC;
     SP_TRY(spmi_fill_zero(flags, 64, st));
     nonempty_probe q;
-    SP_TRY(nonempty_enqueue(t, tmp, st, flags, q));
+    SP_TRY(nonempty_enqueue(t, st, flags, q));
     if (!q.active) return SP_OK;
     int h[16];
     SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
     q.take(h);
     bool launched = false;
-    return nonempty_decide(t, st, q, &launched);
+    return nonempty_decide(t, tmp, st, q, &launched);
 }
 
 // Column-segmented copy of a CSR tensor (see sp_segments): entries keyed by (panel, row, column) and packed
@@ -894,12 +911,65 @@ extern "C" void sp_tensor_free(sp_tensor *t)
     delete t;
 }
 
+// The same for the innermost level of a format whose levels above are all dense (CSR, CSC and their kin of any rank): every
+// entry is its own child, its parent is the key divided by the level's size.  Four consecutive entries per thread, their keys
+// and the two neighbours loaded once, the four coordinates written with one store.
+template <typename PT, typename CT>
+__global__ __launch_bounds__(kThreads) void emit_inner_kernel(const uint64_t *__restrict__ keys, int64_t nnz, divisor size, PT *__restrict__ cnt,
+                                                              CT *__restrict__ crd, int *__restrict__ dup_flags)
+{
+    typedef unsigned long long u2 __attribute__((ext_vector_type(2)));
+    typedef typename std::conditional<sizeof(PT) == 8, unsigned long long, unsigned int>::type UT;
+    const int64_t e0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (e0 >= nnz) return;
+    uint64_t k[6];                                       // k[1..4] = the thread's keys, k[0] and k[5] the neighbours
+    const bool whole = e0 + 4 <= nnz;
+    if (whole) {
+        const u2 a = *(const u2 *)(keys + e0), b = *(const u2 *)(keys + e0 + 2);
+        k[1] = a[0]; k[2] = a[1]; k[3] = b[0]; k[4] = b[1];
+    } else {
+        for (int i = 0; i < 4; ++i) k[1 + i] = e0 + i < nnz ? keys[e0 + i] : 0;
+    }
+    k[0] = e0 > 0 ? keys[e0 - 1] : 0;
+    k[5] = e0 + 4 < nnz ? keys[e0 + 4] : 0;
+    uint64_t up[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) up[i] = div_by(k[i], size);
+    CT c[4];
+    bool dup = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t e = e0 + i;
+        c[i] = (CT)(k[1 + i] - up[1 + i] * size.d);
+        if (e < nnz) {
+            dup |= e > 0 && k[1 + i] == k[i];
+            const bool head = e == 0 || up[i] != up[1 + i];
+            const bool tail = e == nnz - 1 || up[2 + i] != up[1 + i];
+            // children of a parent = (last child + 1) - first child: integer atomics, so the order does not matter
+            if (head && tail) atomicAdd((UT *)&cnt[up[1 + i]], (UT)1);
+            else if (tail) atomicAdd((UT *)&cnt[up[1 + i]], (UT)(e + 1));
+            else if (head) atomicAdd((UT *)&cnt[up[1 + i]], (UT)0 - (UT)e);
+        }
+    }
+    if (dup_flags && dup) atomicOr(&dup_flags[1], 1);
+    if (whole && sizeof(CT) == 4) {
+        typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+        *(u4 *)(crd + e0) = u4{(unsigned)c[0], (unsigned)c[1], (unsigned)c[2], (unsigned)c[3]};
+    } else {
+        for (int i = 0; i < 4; ++i) if (e0 + i < nnz) crd[e0 + i] = c[i];
+    }
+}
+
 template <typename PT, typename CT>
 static sp_status launch_emit(const uint64_t *keys, int64_t nnz, divisor stride, divisor size, const uint32_t *child_excl,
                              const uint64_t *pin, uint64_t *pout, void *cnt, void *crd, int *dup_flags, hipStream_t st)
 {
-    hipLaunchKernelGGL((emit_level_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, keys, nnz, stride, size, child_excl,
-                       pin, pout, (PT *)cnt, (CT *)crd, dup_flags);
+    if (!child_excl && !pin && !pout && stride.d == 1)
+        hipLaunchKernelGGL((emit_inner_kernel<PT, CT>), dim3(blocks_for((nnz + 3) / 4)), dim3(kThreads), 0, st, keys, nnz, size, (PT *)cnt, (CT *)crd,
+                           dup_flags);
+    else
+        hipLaunchKernelGGL((emit_level_kernel<PT, CT>), dim3(blocks_for(nnz)), dim3(kThreads), 0, st, keys, nnz, stride, size, child_excl,
+                           pin, pout, (PT *)cnt, (CT *)crd, dup_flags);
     SP_HIP(hipGetLastError());
     return SP_OK;
 }
@@ -927,7 +997,7 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
     // non-empty-rows list (all in bounds whatever the input checks say), then one synchronisation for all read-backs
     SP_TRY(spmi_build_rowblocks(t, st));
     nonempty_probe q;
-    SP_TRY(nonempty_enqueue(t, tmp, st, flags, q));
+    SP_TRY(nonempty_enqueue(t, st, flags, q));
     int h[16] = {0};
     if (want_max || input_flags || q.active) SP_HIP(hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, st));
     SP_HIP(hipStreamSynchronize(st));
@@ -941,7 +1011,7 @@ sp_status spmi_finish_tensor(sp_tensor *t, int *flags, sp_scratch &tmp, hipStrea
     memcpy(&hmx, &h[4], 8);
     if (want_max) t->max_segment = (int64_t)hmx;
     bool launched = false;
-    SP_TRY(nonempty_decide(t, st, q, &launched));
+    SP_TRY(nonempty_decide(t, tmp, st, q, &launched));
     if (launched) SP_HIP(hipStreamSynchronize(st));
     return SP_OK;
 }
